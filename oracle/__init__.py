@@ -1,0 +1,208 @@
+"""ctypes access to the CPU oracle (oracle/kvcrush_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY.  Only tests, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the GPU library and its Python
+binding never do.  Tensors are torch CPU tensors (contiguous); nothing here
+touches a GPU.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+
+import torch
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "kvcrush_oracle.cpp")
+_LIB = os.path.join(_DIR, "libkvcrush_oracle.so")
+CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC"]
+
+F32, BF16 = 0, 1
+ANCHOR_RANDOM, ANCHOR_MEAN, ANCHOR_ALTERNATING, ANCHOR_EXPLICIT = 0, 1, 2, 3
+ANCHORS = {"random": 0, "mean": 1, "alternating": 2, "explicit": 3}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (single translation unit, no dependencies)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.run(["g++", *CXXFLAGS, "-o", tmp, _SRC], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        vp, i32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
+        L.kvcrush_oracle_head_colsums.argtypes = [i32, i32, i32, vp, vp, i32, i32, vp, vp]
+        L.kvcrush_oracle_scores.argtypes = [i32] * 7 + [vp] * 4
+        L.kvcrush_oracle_topk.argtypes = [vp, i32, i32, vp]
+        L.kvcrush_oracle_splitmix64.argtypes = [u64, i32, vp]
+        L.kvcrush_oracle_splitmix64.restype = None
+        L.kvcrush_oracle_bits.argtypes = [i32, i32, i32, vp, vp]
+        L.kvcrush_oracle_group.argtypes = [i32, i32, vp, vp, i32, i32, u64, i32, vp, vp, vp]
+        L.kvcrush_oracle_select.argtypes = [i32] * 7 + [u64, vp, vp, vp, vp, vp]
+        L.kvcrush_oracle_compact.argtypes = [i32] * 6 + [vp, vp, vp, vp, i32, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"oracle handles float32 and bfloat16, got {t.dtype}")
+
+
+def _cpu(t: torch.Tensor) -> torch.Tensor:
+    assert t.device.type == "cpu", "the oracle reads host memory only"
+    return t.contiguous()
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def words_for(Hs: int) -> int:
+    return (Hs + 63) // 64
+
+
+def head_colsums(q_head, k_head, row_begin=0, row_end=None, want_lse=False):
+    """Received attention for one head over query rows [row_begin, row_end).
+
+    q_head, k_head: [S, D].  Returns float64 [S] (and float64 lse [S], zero
+    outside the row range, when want_lse)."""
+    q_head, k_head = _cpu(q_head), _cpu(k_head)
+    S, D = q_head.shape
+    row_end = S if row_end is None else row_end
+    c = torch.zeros(S, dtype=torch.float64)
+    lse = torch.zeros(S, dtype=torch.float64) if want_lse else None
+    rc = lib().kvcrush_oracle_head_colsums(S, D, _dtype_code(q_head), _ptr(q_head), _ptr(k_head),
+                                           row_begin, row_end, _ptr(c), _ptr(lse))
+    _check(rc, "head_colsums")
+    return (c, lse) if want_lse else c
+
+
+def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1):
+    """scores [B,Hs,S] fp32 from q [B,Hq,S,D], k [B,Hkv,S,D].
+
+    threads > 1 spreads independent (batch, head) units of the unchanged
+    single-threaded routine over host threads (the foreign call releases the
+    GIL); the group sum is then formed here in float64, heads ascending,
+    rounded once, exactly as the C++ whole-tensor routine does."""
+    q, k = _cpu(q), _cpu(k)
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (B, Hkv, S, D) and Hq % Hkv == 0 and q.dtype == k.dtype
+    G = Hq // Hkv
+    Hs = Hkv if reduce_groups else Hq
+    if threads <= 1:
+        out = torch.empty(B, Hs, S, dtype=torch.float32)
+        lse = torch.empty(B, Hq, S, dtype=torch.float32) if want_lse else None
+        rc = lib().kvcrush_oracle_scores(B, Hq, Hkv, S, D, _dtype_code(q), int(reduce_groups),
+                                         _ptr(q), _ptr(k), _ptr(out), _ptr(lse))
+        _check(rc, "scores")
+        return (out, lse) if want_lse else out
+
+    units = [(b, h) for b in range(B) for h in range(Hq)]
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        res = list(ex.map(lambda u: head_colsums(q[u[0], u[1]], k[u[0], u[1] // G], want_lse=True),
+                          units))
+    c = torch.stack([r[0] for r in res]).view(B, Hq, S)
+    lse = torch.stack([r[1] for r in res]).view(B, Hq, S).to(torch.float32)
+    if reduce_groups:
+        acc = torch.zeros(B, Hkv, S, dtype=torch.float64)
+        for hh in range(G):  # ascending head order within each group
+            acc = acc + c[:, hh::G, :]
+        out = acc.to(torch.float32)
+    else:
+        out = c.to(torch.float32)
+    return (out, lse) if want_lse else out
+
+
+def topk(v, k: int):
+    v = _cpu(v.to(torch.float32))
+    out = torch.empty(k, dtype=torch.int32)
+    _check(lib().kvcrush_oracle_topk(_ptr(v), v.numel(), k, _ptr(out)), "topk")
+    return out
+
+
+def splitmix64(seed: int, count: int):
+    out = torch.empty(count, dtype=torch.int64)
+    lib().kvcrush_oracle_splitmix64(ctypes.c_uint64(seed & (2**64 - 1)), count, _ptr(out))
+    return [int(x) & (2**64 - 1) for x in out.tolist()]
+
+
+def bits(scores_1seq, kbit: int):
+    """scores_1seq [Hs,S] fp32 -> packed head-behaviour words [S,W] (int64 storage)."""
+    sc = _cpu(scores_1seq.to(torch.float32))
+    Hs, S = sc.shape
+    out = torch.empty(S, words_for(Hs), dtype=torch.int64)
+    _check(lib().kvcrush_oracle_bits(Hs, S, kbit, _ptr(sc), _ptr(out)), "bits")
+    return out
+
+
+def group(Hs, bits_1seq, is_important, Br, anchor="alternating", anchor_seed=0, batch_index=0,
+          anchor_explicit=None):
+    """Alg. 2 on one sequence.  Returns (reps int32 [Br] in bucket order, anchor words)."""
+    bw = _cpu(bits_1seq.to(torch.int64))
+    S, W = bw.shape
+    assert W == words_for(Hs)
+    imp = _cpu(is_important.to(torch.uint8))
+    reps = torch.empty(max(Br, 1), dtype=torch.int32)
+    anc = torch.zeros(W, dtype=torch.int64)
+    ae = None if anchor_explicit is None else _cpu(anchor_explicit.to(torch.int64))
+    rc = lib().kvcrush_oracle_group(Hs, S, _ptr(bw), _ptr(imp), Br, ANCHORS[anchor],
+                                    ctypes.c_uint64(anchor_seed & (2**64 - 1)), batch_index,
+                                    _ptr(ae), _ptr(reps), _ptr(anc))
+    _check(rc, "group")
+    return reps[:Br], anc
+
+
+def select(scores_t, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
+           anchor_bits=None):
+    """Stages 2-4.  scores_t [B,Hs,S] fp32 -> (idx int32 [B,budget], kind uint8, bits int64 [B,S,W])."""
+    sc = _cpu(scores_t.to(torch.float32))
+    B, Hs, S = sc.shape
+    W = words_for(Hs)
+    idx = torch.empty(B, budget, dtype=torch.int32)
+    kind = torch.empty(B, budget, dtype=torch.uint8)
+    bw = torch.empty(B, S, W, dtype=torch.int64)
+    ab = None if anchor_bits is None else _cpu(anchor_bits.to(torch.int64))
+    rc = lib().kvcrush_oracle_select(B, Hs, S, budget, n_important, bit_topk, ANCHORS[anchor],
+                                     ctypes.c_uint64(anchor_seed & (2**64 - 1)), _ptr(ab), _ptr(sc),
+                                     _ptr(idx), _ptr(kind), _ptr(bw))
+    _check(rc, "select")
+    return idx, kind, bw
+
+
+def compact(k, v, idx, block_table=None, block_size=16, dense_shape=None):
+    """Stage 5.  Dense k, v [B,Hkv,S,D]; or paged pools [n_blocks,block_size,Hkv,D]
+    with block_table [B,S/block_size] and dense_shape=(B,Hkv,S,D)."""
+    k, v, idx = _cpu(k), _cpu(v), _cpu(idx.to(torch.int32))
+    if block_table is None:
+        B, Hkv, S, D = k.shape
+    else:
+        B, Hkv, S, D = dense_shape
+        block_table = _cpu(block_table.to(torch.int32))
+    budget = idx.shape[1]
+    ko = torch.empty(B, Hkv, budget, D, dtype=k.dtype)
+    vo = torch.empty(B, Hkv, budget, D, dtype=v.dtype)
+    rc = lib().kvcrush_oracle_compact(B, Hkv, S, D, _dtype_code(k), budget, _ptr(k), _ptr(v),
+                                      _ptr(idx), _ptr(block_table), block_size, _ptr(ko), _ptr(vo))
+    _check(rc, "compact")
+    return ko, vo

@@ -1,0 +1,341 @@
+// KVCrush oracle: a plain, slow, single-threaded CPU statement of the per-layer
+// KV-cache compression step.  TEST INFRASTRUCTURE ONLY: it exists so that the
+// GPU library can be checked against something written straight from the
+// paper.  It shares no code with the GPU sources, is never linked into the
+// product, and nothing on the product path may call it.
+//
+// What it follows (KVCrush, arXiv 2503.00022):
+//   * Algorithm 1 + Sec. 3.1  -- per-head attention weights, a per-head
+//     threshold keeping a target fraction of tokens, one bit per head.
+//   * Algorithm 2 + Sec. 3.2  -- anchor vector, Hamming distance to it,
+//     B_representative buckets, one representative nearest each bucket centroid.
+//   * Sec. 3 (first paragraph) -- budget B = B_important + B_representative,
+//     the important set chosen by the baseline (H2O: largest accumulated
+//     attention, Sec. 2.3 and Sec. 4.1.1); final cache = union of both sets.
+//
+// Readings taken where the paper is silent or garbled (listed in the design
+// notes too):
+//   * The printed score of Alg. 1 sums a softmax row, which is 1 for every
+//     token.  The H2O meaning is used instead: the attention a token RECEIVES,
+//     c_h[t] = sum over queries i >= t of A_h(i, t), causal mask, no 1/S factor.
+//   * theta_h "retains a target fraction of tokens for each head": exact
+//     per-head top-k, ties resolved towards the lower token index.
+//   * "Assign to one of B_representative buckets based on d_t": tokens are
+//     ordered by (d_t, token index) and cut into B_representative contiguous
+//     rank ranges [floor(j*N/Br), floor((j+1)*N/Br)).
+//   * Only tokens NOT kept as important are grouped ("proxies of the evicted
+//     tokens"), so the two sets are disjoint and the cache holds exactly B.
+//   * "Closest to the centroid": L1 distance to the fractional centroid times
+//     the bucket size, an integer: sum_r (bit_r ? n - cnt_r : cnt_r).
+//   * Every tie goes to the lower token index.  Output ascending by position.
+//
+// Parity pins (tests/test_oracle_*.py): brute force with the full SxS matrix,
+// the harmonic closed form for uniform attention, column sums totalling the
+// number of query rows, float64 library softmax, hand-worked Hamming/bucket
+// examples, splitmix64's published first outputs.  Whether the retained
+// tokens preserve model accuracy is "parity unpinned" (needs the paper's
+// datasets and weights).
+//
+// Build: g++ -O2 -std=c++17 -ffp-contract=off -fno-fast-math -shared -fPIC
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ANCHOR_RANDOM = 0, ANCHOR_MEAN = 1, ANCHOR_ALTERNATING = 2, ANCHOR_EXPLICIT = 3 };
+
+// bf16 is the upper 16 bits of an IEEE binary32; widening is exact.
+double widen(const void* base, size_t i, int dtype) {
+  if (dtype == ORC_F32) return (double)((const float*)base)[i];
+  uint32_t u = (uint32_t)((const uint16_t*)base)[i] << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return (double)f;
+}
+
+size_t elem_size(int dtype) { return dtype == ORC_F32 ? 4 : 2; }
+
+int words_for(int Hs) { return (Hs + 63) / 64; }
+
+// One splitmix64 step (public-domain generator by S. Vigna): advances the
+// state by the golden-ratio increment and returns the mixed value.
+uint64_t splitmix64_next(uint64_t* state) {
+  *state += 0x9E3779B97F4A7C15ull;
+  uint64_t z = *state;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+// Indices of the k largest values, ties to the lower index: a full stable sort
+// by descending value (stability keeps equal values in index order).
+std::vector<int> topk_indices(const float* v, int n, int k) {
+  std::vector<int> order(n);
+  for (int i = 0; i < n; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [v](int a, int b) { return v[a] > v[b]; });
+  order.resize(k);
+  return order;
+}
+
+bool get_bit(const uint64_t* w, int r) { return (w[r / 64] >> (r % 64)) & 1ull; }
+
+}  // namespace
+
+extern "C" {
+
+// Alg. 1 (attention weights) with the received-attention reading: for one
+// head, adds to c[t] the probability that each query row i in
+// [row_begin, row_end) puts on key t <= i.  q_head, k_head: [S, D] row-major.
+// lse (nullable, [S]) receives log(sum_j exp(s_ij)) for the rows visited.
+// c is accumulated into (caller zeroes it), so disjoint row ranges add up.
+int kvcrush_oracle_head_colsums(int S, int D, int dtype, const void* q_head, const void* k_head,
+                                int row_begin, int row_end, double* c, double* lse) {
+  if (S < 1 || D < 1 || row_begin < 0 || row_end > S || row_begin > row_end) return 1;
+  std::vector<double> kd((size_t)S * D), qrow(D), s(S), p(S);
+  for (size_t i = 0; i < (size_t)S * D; ++i) kd[i] = widen(k_head, i, dtype);
+  const double inv_sqrt_d = 1.0 / std::sqrt((double)D);
+  for (int i = row_begin; i < row_end; ++i) {
+    for (int d = 0; d < D; ++d) qrow[d] = widen(q_head, (size_t)i * D + d, dtype);
+    double m = -INFINITY;
+    for (int j = 0; j <= i; ++j) {
+      double dot = 0.0;
+      const double* kr = &kd[(size_t)j * D];
+      for (int d = 0; d < D; ++d) dot += qrow[d] * kr[d];
+      s[j] = dot * inv_sqrt_d;
+      if (s[j] > m) m = s[j];
+    }
+    double L = 0.0;
+    for (int j = 0; j <= i; ++j) {
+      p[j] = std::exp(s[j] - m);
+      L += p[j];
+    }
+    for (int j = 0; j <= i; ++j) c[j] += p[j] / L;
+    if (lse) lse[i] = m + std::log(L);
+  }
+  return 0;
+}
+
+// Whole score tensor.  q: [B,Hq,S,D], k: [B,Hkv,S,D]; query head h reads KV
+// head h / (Hq/Hkv).  scores: [B,Hs,S] fp32 with Hs = Hkv when reduce_groups
+// (the heads of a group are summed in double, ascending, and rounded once),
+// else Hs = Hq.  lse_out (nullable): [B,Hq,S] fp32.
+int kvcrush_oracle_scores(int B, int Hq, int Hkv, int S, int D, int dtype, int reduce_groups,
+                          const void* q, const void* k, float* scores, float* lse_out) {
+  if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || D < 1) return 1;
+  const int G = Hq / Hkv;
+  const size_t es = elem_size(dtype), head_elems = (size_t)S * D;
+  std::vector<double> c(S), acc(S), lse(S);
+  for (int b = 0; b < B; ++b) {
+    for (int g = 0; g < Hkv; ++g) {
+      std::fill(acc.begin(), acc.end(), 0.0);
+      for (int hh = 0; hh < G; ++hh) {
+        const int h = g * G + hh;
+        std::fill(c.begin(), c.end(), 0.0);
+        const char* qh = (const char*)q + ((size_t)b * Hq + h) * head_elems * es;
+        const char* kh = (const char*)k + ((size_t)b * Hkv + g) * head_elems * es;
+        int rc = kvcrush_oracle_head_colsums(S, D, dtype, qh, kh, 0, S, c.data(), lse.data());
+        if (rc) return rc;
+        if (lse_out)
+          for (int t = 0; t < S; ++t) lse_out[((size_t)b * Hq + h) * S + t] = (float)lse[t];
+        if (reduce_groups) {
+          for (int t = 0; t < S; ++t) acc[t] += c[t];
+        } else {
+          for (int t = 0; t < S; ++t) scores[((size_t)b * Hq + h) * S + t] = (float)c[t];
+        }
+      }
+      if (reduce_groups)
+        for (int t = 0; t < S; ++t) scores[((size_t)b * Hkv + g) * S + t] = (float)acc[t];
+    }
+  }
+  return 0;
+}
+
+// The k largest of v[0..n), ties to the lower index, in rank order.
+int kvcrush_oracle_topk(const float* v, int n, int k, int32_t* out) {
+  if (n < 0 || k < 0 || k > n) return 1;
+  std::vector<int> sel = topk_indices(v, n, k);
+  for (int i = 0; i < k; ++i) out[i] = sel[i];
+  return 0;
+}
+
+// First `count` outputs of splitmix64 started at `seed`.
+void kvcrush_oracle_splitmix64(uint64_t seed, int count, uint64_t* out) {
+  uint64_t st = seed;
+  for (int i = 0; i < count; ++i) out[i] = splitmix64_next(&st);
+}
+
+// Alg. 1's thresholding for one sequence: bit r of token t is set iff t is in
+// the top-kbit of score row r.  scores: [Hs,S]; bits: [S,W] (W = ceil(Hs/64)),
+// head r -> bit r%64 of word r/64.
+int kvcrush_oracle_bits(int Hs, int S, int kbit, const float* scores, uint64_t* bits) {
+  if (Hs < 1 || S < 1 || kbit < 0 || kbit > S) return 1;
+  const int W = words_for(Hs);
+  std::memset(bits, 0, sizeof(uint64_t) * (size_t)S * W);
+  for (int r = 0; r < Hs; ++r) {
+    std::vector<int> sel = topk_indices(scores + (size_t)r * S, S, kbit);
+    for (int t : sel) bits[(size_t)t * W + r / 64] |= 1ull << (r % 64);
+  }
+  return 0;
+}
+
+// Alg. 2 for one sequence.  bits: [S,W]; is_important: [S] flags (those tokens
+// are left out of the grouping); Br buckets; anchor per `mode` (batch_index
+// enters the random anchor's seed; anchor_explicit: [W], EXPLICIT only).
+// reps: [Br] token ids in bucket order.  anchor_out (nullable): [W].
+int kvcrush_oracle_group(int Hs, int S, const uint64_t* bits, const uint8_t* is_important, int Br,
+                         int mode, uint64_t anchor_seed, int batch_index,
+                         const uint64_t* anchor_explicit, int32_t* reps, uint64_t* anchor_out) {
+  if (Hs < 1 || S < 1 || Br < 0) return 1;
+  const int W = words_for(Hs);
+  std::vector<int> disc;  // discarded tokens, ascending
+  for (int t = 0; t < S; ++t)
+    if (!is_important[t]) disc.push_back(t);
+  const long long N = (long long)disc.size();
+  if (Br > N) return 1;
+
+  // anchor
+  std::vector<uint64_t> a(W, 0);
+  if (mode == ANCHOR_RANDOM) {
+    uint64_t st = anchor_seed + (uint64_t)batch_index;
+    for (int w = 0; w < W; ++w) a[w] = splitmix64_next(&st);
+  } else if (mode == ANCHOR_ALTERNATING) {
+    for (int r = 0; r < Hs; ++r)
+      if (r & 1) a[r / 64] |= 1ull << (r % 64);
+  } else if (mode == ANCHOR_MEAN) {
+    for (int r = 0; r < Hs; ++r) {
+      long long cnt = 0;
+      for (int t : disc) cnt += get_bit(bits + (size_t)t * W, r) ? 1 : 0;
+      if (2 * cnt > N) a[r / 64] |= 1ull << (r % 64);
+    }
+  } else if (mode == ANCHOR_EXPLICIT) {
+    if (!anchor_explicit) return 1;
+    for (int w = 0; w < W; ++w) a[w] = anchor_explicit[w];
+  } else {
+    return 1;
+  }
+  // keep only the Hs meaningful bits
+  for (int r = Hs; r < W * 64; ++r) a[r / 64] &= ~(1ull << (r % 64));
+  if (anchor_out)
+    for (int w = 0; w < W; ++w) anchor_out[w] = a[w];
+  if (Br == 0) return 0;
+
+  // Hamming distance of every grouped token to the anchor, bit by bit.
+  std::vector<int> dist(S, 0);
+  for (int t : disc) {
+    int d = 0;
+    for (int r = 0; r < Hs; ++r)
+      d += (get_bit(bits + (size_t)t * W, r) != get_bit(a.data(), r)) ? 1 : 0;
+    dist[t] = d;
+  }
+  // order by distance; equal distances stay in token order
+  std::vector<int> order = disc;
+  std::stable_sort(order.begin(), order.end(), [&dist](int x, int y) { return dist[x] < dist[y]; });
+
+  for (long long j = 0; j < Br; ++j) {
+    const long long lo = j * N / Br, hi = (j + 1) * N / Br;
+    const long long n = hi - lo;
+    std::vector<long long> cnt(Hs, 0);
+    for (long long m = lo; m < hi; ++m)
+      for (int r = 0; r < Hs; ++r) cnt[r] += get_bit(bits + (size_t)order[m] * W, r) ? 1 : 0;
+    long long best_cost = -1;
+    int best_t = -1;
+    for (long long m = lo; m < hi; ++m) {
+      const int t = order[m];
+      long long cost = 0;
+      for (int r = 0; r < Hs; ++r) cost += get_bit(bits + (size_t)t * W, r) ? (n - cnt[r]) : cnt[r];
+      if (best_t < 0 || cost < best_cost || (cost == best_cost && t < best_t)) {
+        best_cost = cost;
+        best_t = t;
+      }
+    }
+    reps[j] = best_t;
+  }
+  return 0;
+}
+
+// Stages 2-4 for a batch.  scores: [B,Hs,S] fp32.  Outputs: idx [B,budget]
+// ascending token ids; kind (nullable) [B,budget]: 0 = kept as important,
+// 1 = kept as representative; bits (nullable) [B,S,W].
+// Token importance is the fp32 sum of the Hs rows taken in row order.
+int kvcrush_oracle_select(int B, int Hs, int S, int budget, int n_important, int bit_topk,
+                          int anchor_mode, uint64_t anchor_seed, const uint64_t* anchor_bits,
+                          const float* scores, int32_t* idx, uint8_t* kind, uint64_t* bits_out) {
+  if (B < 1 || Hs < 1 || S < 1 || budget < 0 || budget > S || n_important < 0 ||
+      n_important > budget)
+    return 1;
+  const int kbit = bit_topk == 0 ? budget : bit_topk;
+  if (kbit < 0 || kbit > S) return 1;
+  const int W = words_for(Hs), Br = budget - n_important;
+  std::vector<uint64_t> bits((size_t)S * W);
+  std::vector<float> imp(S);
+  std::vector<uint8_t> is_imp(S), is_rep(S);
+  std::vector<int32_t> reps(Br > 0 ? Br : 1);
+  for (int b = 0; b < B; ++b) {
+    const float* sc = scores + (size_t)b * Hs * S;
+    int rc = kvcrush_oracle_bits(Hs, S, kbit, sc, bits.data());
+    if (rc) return rc;
+    for (int t = 0; t < S; ++t) {
+      float acc = 0.0f;
+      for (int r = 0; r < Hs; ++r) acc = acc + sc[(size_t)r * S + t];
+      imp[t] = acc;
+    }
+    std::fill(is_imp.begin(), is_imp.end(), 0);
+    std::fill(is_rep.begin(), is_rep.end(), 0);
+    for (int t : topk_indices(imp.data(), S, n_important)) is_imp[t] = 1;
+    rc = kvcrush_oracle_group(Hs, S, bits.data(), is_imp.data(), Br, anchor_mode, anchor_seed, b,
+                              anchor_bits ? anchor_bits + (size_t)b * W : nullptr, reps.data(),
+                              nullptr);
+    if (rc) return rc;
+    for (int j = 0; j < Br; ++j) {
+      if (is_imp[reps[j]] || is_rep[reps[j]]) return 2;  // must be disjoint and distinct
+      is_rep[reps[j]] = 1;
+    }
+    int o = 0;
+    for (int t = 0; t < S; ++t) {
+      if (is_imp[t] || is_rep[t]) {
+        if (o >= budget) return 2;
+        idx[(size_t)b * budget + o] = t;
+        if (kind) kind[(size_t)b * budget + o] = is_rep[t] ? 1 : 0;
+        ++o;
+      }
+    }
+    if (o != budget) return 2;
+    if (bits_out) std::memcpy(bits_out + (size_t)b * S * W, bits.data(), sizeof(uint64_t) * S * W);
+  }
+  return 0;
+}
+
+// Stage 5.  Dense source: k, v [B,Hkv,S,D].  Paged source (block_table
+// non-null): pool [n_blocks, block_size, Hkv, D], block_table [B, S/block_size]
+// gives the physical block of each logical block.  Output [B,Hkv,budget,D].
+int kvcrush_oracle_compact(int B, int Hkv, int S, int D, int dtype, int budget, const void* k,
+                           const void* v, const int32_t* idx, const int32_t* block_table,
+                           int block_size, void* k_out, void* v_out) {
+  if (B < 1 || Hkv < 1 || S < 1 || D < 1 || budget < 0 || budget > S) return 1;
+  if (block_table && (block_size < 1 || S % block_size != 0)) return 1;
+  const size_t row = (size_t)D * elem_size(dtype);
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < Hkv; ++h)
+      for (int j = 0; j < budget; ++j) {
+        const int t = idx[(size_t)b * budget + j];
+        if (t < 0 || t >= S) return 1;
+        size_t src;
+        if (block_table) {
+          const size_t blk = (size_t)block_table[(size_t)b * (S / block_size) + t / block_size];
+          src = ((blk * block_size + t % block_size) * Hkv + h) * row;
+        } else {
+          src = (((size_t)b * Hkv + h) * S + t) * row;
+        }
+        const size_t dst = (((size_t)b * Hkv + h) * budget + j) * row;
+        std::memcpy((char*)k_out + dst, (const char*)k + src, row);
+        std::memcpy((char*)v_out + dst, (const char*)v + src, row);
+      }
+  return 0;
+}
+
+}  // extern "C"
