@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the KVCrush per-layer compression step on one MI355X.
+
+A step is one pass of the whole hot path over one layer of the workload:
+row normalisers (pass A) -> received-attention scores (pass B) -> selection
+(top-k, bits, Hamming grouping, representatives) -> K/V gather.  The layers'
+Q/K/V are generated once and stay resident in HBM; successive steps walk
+through the layers so that the 256 MB last-level cache cannot serve repeats.
+
+Prints ONE JSON line (the last line of stdout).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak, vendor figure
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak, vendor figure
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", type=int, default=3, help="workload id 1..5 (default: the S=16384 GQA layer)")
+    ap.add_argument("--layers", type=int, default=0, help="resident layers (0: the workload's own count, capped at 32)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer):
+    """The oracle as it stands, single-threaded, on a bounded sample: every query
+    row of ONE query head of layer 0 (1/Hq of the layer's score work), plus the
+    full selection and gather of that layer.  Extrapolated to a whole layer."""
+    import oracle
+    import torch
+    from paper_2503_00022_amd import inputs
+
+    q_h = q0[0, 0].cpu()
+    k_h = k0[0, 0].cpu()
+    t0 = time.perf_counter()
+    oracle.head_colsums(q_h, k_h)
+    t_head = time.perf_counter() - t0
+    sc = sc_gpu_layer0.cpu()
+    t0 = time.perf_counter()
+    idx, _, _ = oracle.select(sc, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(layer))
+    t_sel = time.perf_counter() - t0
+    kc, vc = k0.cpu(), v0.cpu()
+    t0 = time.perf_counter()
+    oracle.compact(kc, vc, idx)
+    t_cmp = time.perf_counter() - t0
+    t_layer = t_head * w.Hq * w.B + t_sel + t_cmp
+    return {
+        "value": w.B * w.S / t_layer, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "sample": (f"layer 0: all {w.S} query rows of 1 of {w.B * w.Hq} (sequence, query head) pairs timed "
+                   f"({t_head:.2f} s) and scaled by {w.B * w.Hq}; selection ({t_sel:.3f} s) and gather "
+                   f"({t_cmp:.3f} s) timed in full"),
+        "seconds_per_layer_extrapolated": t_layer,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path has no cross-GPU step); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_00022_amd import binding as kv
+    from paper_2503_00022_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    kv.load()
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w = inputs.CONFIGS[args.config]
+    n_layers = args.layers or min(w.layers, 32)
+    # a single-layer workload still rotates over a few copies so that repeats miss the cache
+    if w.layers == 1 and not args.layers:
+        n_layers = 4
+    G = w.Hq // w.Hkv
+    Hs = w.Hs
+
+    layers = []
+    for L in range(n_layers):
+        q, k, v = inputs.make_qkv(w, inputs.layer_seed(args.config, L), device=dev)
+        ent = {"q": q, "k": k, "v": v}
+        if w.paged:
+            bt = inputs.make_block_table(w, inputs.layer_seed(args.config, L))
+            ent["bt"] = bt.to(dev)
+            ent["kp"] = inputs.to_paged(k, bt, w.block_size)
+            ent["vp"] = inputs.to_paged(v, bt, w.block_size)
+        layers.append(ent)
+    torch.cuda.synchronize()
+
+    shape = kv.make_shape(layers[0]["q"], layers[0]["k"], w.reduce_groups)
+    lse = torch.empty(w.B, w.Hq, w.S, dtype=torch.float32, device=dev)
+    scores = torch.empty(w.B, Hs, w.S, dtype=torch.float32, device=dev)
+    idx = torch.empty(w.B, w.budget, dtype=torch.int32, device=dev)
+    sel_ws = torch.empty(kv.kvcrush_select_workspace(
+        kv.make_select_args(w.B, Hs, w.S, w.budget, w.n_important)), dtype=torch.uint8, device=dev)
+    k_out = torch.empty(w.B, w.Hkv, w.budget, w.D, dtype=w.torch_dtype, device=dev)
+    v_out = torch.empty_like(k_out)
+
+    def step(i, ev=None):
+        L = i % n_layers
+        ent = layers[L]
+        if ev:
+            ev[0].record()
+        kv.kvcrush_row_lse(ent["q"], ent["k"], lse_out=lse)
+        if ev:
+            ev[1].record()
+        kv.kvcrush_scores(ent["q"], ent["k"], w.reduce_groups, lse=lse, scores=scores)
+        if ev:
+            ev[2].record()
+        kv.kvcrush_select(scores, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(L), want_kind=False,
+                          idx=idx, workspace=sel_ws)
+        if ev:
+            ev[3].record()
+        if w.paged:
+            kv.kvcrush_compact(ent["kp"], ent["vp"], idx, block_table=ent["bt"], block_size=w.block_size,
+                               dense_shape=(w.B, w.Hkv, w.S, w.D), k_out=k_out, v_out=v_out, validate=False)
+        else:
+            kv.kvcrush_compact(ent["k"], ent["v"], idx, k_out=k_out, v_out=v_out, validate=False)
+        if ev:
+            ev[4].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    stage = [sum(e[j].elapsed_time(e[j + 1]) for e in evs) / args.steps for j in range(4)]  # ms
+    t_lse, t_col, t_sel, t_cmp = stage
+    tokens = w.B * w.S
+
+    # algorithmic work (what the method must compute / move, not what a kernel happens to do)
+    pairs = w.S * (w.S + 1) // 2                                  # causal (query, key) pairs per head
+    flop_pass = 2.0 * w.D * pairs * w.Hq * w.B                    # one sweep of Q K^T
+    esz = 2 if w.dtype == "bf16" else 4
+    bytes_sel = 4.0 * Hs * w.S * w.B + 4.0 * w.budget * w.B
+    bytes_cmp = 2.0 * 2.0 * w.B * w.Hkv * w.budget * w.D * esz + 4.0 * w.budget * w.B
+    dom_name, dom_ms = ("colsum_kernel", t_col) if t_col >= t_lse else ("lse_kernel", t_lse)
+    achieved = flop_pass / (dom_ms * 1e-3) / 1e12
+    peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 157.3
+    roofline = {
+        "bound": "mfma", "kernel": dom_name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+        "frac": achieved / peak, "traffic": None,
+        "flop_per_launch": flop_pass, "avg_launch_ms": dom_ms,
+    }
+    stages = {
+        "lse_ms": t_lse, "colsum_ms": t_col, "select_ms": t_sel, "compact_ms": t_cmp,
+        "scores_tflops": 2 * flop_pass / ((t_lse + t_col) * 1e-3) / 1e12,
+        "scores_frac_of_mfma_peak": 2 * flop_pass / ((t_lse + t_col) * 1e-3) / 1e12 / peak,
+        "select_compact_gbs": (bytes_sel + bytes_cmp) / ((t_sel + t_cmp) * 1e-3) / 1e9,
+        "select_compact_frac_of_hbm_peak": (bytes_sel + bytes_cmp) / ((t_sel + t_cmp) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "compact_gbs": bytes_cmp / (t_cmp * 1e-3) / 1e9,
+    }
+
+    # cheap sanity check of the last step's scores: every row totals (group size) x S
+    tot = scores.double().sum(-1)
+    want = float((G if w.reduce_groups else 1) * w.S)
+    ok = bool(torch.allclose(tot, torch.full_like(tot, want), rtol=1e-4))
+
+    out = {
+        "metric": "kv_compressed_tokens_per_sec_per_layer", "value": tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "S": w.S, "D": w.D,
+                   "budget": w.budget, "n_important": w.n_important, "n_representative": w.n_rep,
+                   "anchor": w.anchor, "reduce_groups": w.reduce_groups, "paged": w.paged,
+                   "resident_layers": n_layers},
+        "roofline": roofline, "stages": stages, "row_sum_check": ok,
+    }
+    if not args.no_cpu_baseline:
+        # layer 0 again, so that its scores are the ones handed to the oracle's selection
+        step(0)
+        torch.cuda.synchronize()
+        out["cpu_baseline"] = cpu_baseline(w, layers[0]["q"], layers[0]["k"], layers[0]["v"], scores, 0)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

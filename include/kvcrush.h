@@ -1,0 +1,173 @@
+/*
+ * kvcrush.h -- C ABI of the MI355X (gfx950) KVCrush per-layer KV-cache
+ * compression library (KVCrush, arXiv 2503.00022).
+ *
+ * One layer's compression is three calls on one HIP stream:
+ *
+ *   kvcrush_scores   attention each cached token receives, per head
+ *                    (Alg. 1, attention weights; Sec. 2.3 / 4.1.1: H2O's
+ *                    accumulated attention)
+ *   kvcrush_select   important tokens (baseline top-n, Sec. 3 first
+ *                    paragraph), head-behaviour bit vectors (Alg. 1, Sec. 3.1),
+ *                    Hamming grouping and one representative per bucket
+ *                    (Alg. 2, Sec. 3.2)
+ *   kvcrush_compact  the reduced cache: retained K/V rows gathered into a
+ *                    dense layout (Sec. 3.2, last step)
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers unless a comment says "host".
+ *     The argument structs themselves are host memory, read during the call.
+ *   - The caller owns every buffer.  The library allocates, frees and keeps
+ *     nothing; scratch memory is passed in as `workspace` whose size the
+ *     matching *_workspace() function returns.  Pointers must be 16-byte
+ *     aligned.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*;
+ *     NULL is the default stream) and return without synchronising.  Outputs
+ *     are complete when the stream reaches the end of the enqueued work.
+ *   - Errors are return codes.  Arguments are validated on the host before
+ *     anything is launched; on an error nothing has been enqueued.
+ *   - Inputs are assumed finite.  NaN scores give an unspecified (but memory
+ *     safe) selection.  -0.0 and +0.0 compare equal.
+ *   - Overlapping calls that share a workspace race; give each concurrent
+ *     stream its own workspace.
+ */
+#ifndef KVCRUSH_H
+#define KVCRUSH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KVCRUSH_OK = 0,
+  KVCRUSH_ERR_INVALID_ARG = 1, /* a size, pointer or enum value is not allowed   */
+  KVCRUSH_ERR_UNSUPPORTED = 2, /* legal in the method, not built (e.g. D = 96)   */
+  KVCRUSH_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than required        */
+  KVCRUSH_ERR_HIP = 4          /* the HIP runtime refused a launch or a query    */
+} kvcrush_status;
+
+typedef enum { KVCRUSH_F32 = 0, KVCRUSH_BF16 = 1 } kvcrush_dtype;
+
+/* Anchor vector of Alg. 2 ("random, mean of input vectors, or alternating 0-1"). */
+typedef enum {
+  KVCRUSH_ANCHOR_RANDOM = 0,      /* word w of sequence b = output w+1 of splitmix64 seeded
+                                     with anchor_seed + b, masked to Hs bits           */
+  KVCRUSH_ANCHOR_MEAN = 1,        /* bit r = 1 iff more than half of the grouped (non-
+                                     important) tokens have bit r set                  */
+  KVCRUSH_ANCHOR_ALTERNATING = 2, /* bit r = r & 1 (head 0 -> 0, head 1 -> 1, ...)     */
+  KVCRUSH_ANCHOR_EXPLICIT = 3     /* caller supplies anchor_bits                       */
+} kvcrush_anchor;
+
+/* Problem shape of one layer.  Query head h reads KV head h / (Hq / Hkv). */
+typedef struct {
+  int32_t B;             /* independent sequences                                     */
+  int32_t Hq;            /* query heads                                               */
+  int32_t Hkv;           /* key/value heads, divides Hq                               */
+  int32_t S;             /* tokens per sequence (all sequences equal length)          */
+  int32_t D;             /* head dimension: 64 or 128                                 */
+  int32_t dtype;         /* kvcrush_dtype of Q and K                                  */
+  int32_t reduce_groups; /* 1: sum each KV group's query heads -> Hs = Hkv score rows
+                            0: one score row per query head    -> Hs = Hq            */
+} kvcrush_shape;
+
+/* ---------------------------------------------------------------- stage 1 --
+ * scores[b, r, t] = sum over the query heads h of row r, and over query
+ * positions i >= t, of softmax_i(Q_h K^T / sqrt(D), causal)[t]
+ * (Alg. 1's attention weights A_h, accumulated over the queries as H2O does;
+ * no 1/S factor; the S x S matrix is never written to memory).
+ * Every row of every head sums to one, so each score row totals S (times the
+ * group size when reduce_groups = 1).
+ *
+ *   q       [B, Hq,  S, D]  row-major, D contiguous, dtype as in shape
+ *   k       [B, Hkv, S, D]
+ *   lse     nullable [B, Hq, S] fp32: natural-log sum-exp of each query row's
+ *           scaled causal logits, as an attention forward pass leaves it.
+ *           NULL: computed here (one more pass over Q K^T) and left in the
+ *           first B*Hq*S floats of the workspace.
+ *   scores  [B, Hs, S] fp32, fully overwritten
+ *   workspace  kvcrush_scores_workspace(shape) bytes
+ * Accuracy: bf16 (or fp32) products, fp32 accumulation; each score is within
+ * 2e-3 relative of the exact value.
+ */
+size_t kvcrush_scores_workspace(const kvcrush_shape* shape);
+kvcrush_status kvcrush_scores(const kvcrush_shape* shape, const void* q, const void* k,
+                              const float* lse, float* scores, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
+/* First half of stage 1 on its own: lse_out[b, h, i] = natural log of
+ * sum_{j <= i} exp(Q_h[i] . K[j] / sqrt(D))  (the normaliser of row i of Alg. 1's
+ * A_h), fp32 [B, Hq, S], fully overwritten.  Passing the result as `lse` to
+ * kvcrush_scores gives exactly what kvcrush_scores computes with lse = NULL;
+ * callers whose attention kernel already produced these values skip this call.
+ * shape->reduce_groups is ignored. */
+kvcrush_status kvcrush_row_lse(const kvcrush_shape* shape, const void* q, const void* k,
+                               float* lse_out, void* hip_stream);
+
+/* ------------------------------------------------------------ stages 2-4 --
+ * Per sequence b, from scores[b] ([Hs, S] fp32):
+ *   bits[t] bit r   = 1 iff t is among the bit_topk largest of row r
+ *                     (Alg. 1's per-head threshold keeping a fixed fraction)
+ *   importance[t]   = ((row0[t] + row1[t]) + row2[t]) + ...  in fp32
+ *   important       = the n_important largest importance values
+ *   grouped tokens  = all others, N = S - n_important of them
+ *   d[t]            = popcount(bits[t] XOR anchor)             (Alg. 2)
+ *   buckets         = grouped tokens ordered by (d, t), cut into
+ *                     Br = budget - n_important rank ranges
+ *                     [floor(j N / Br), floor((j+1) N / Br))
+ *   representative  = bucket member with the least summed Hamming distance to
+ *                     the bucket's members (nearest the centroid)
+ *   idx             = important and representatives merged, ascending
+ * Every tie (equal scores, equal costs) goes to the lower token index, so the
+ * result is unique for a given score tensor.
+ */
+typedef struct {
+  int32_t B, Hs, S;        /* Hs score rows per sequence, 1 <= Hs <= 128               */
+  int32_t budget;          /* tokens kept per sequence, 0 <= budget <= S               */
+  int32_t n_important;     /* 0 <= n_important <= budget; the rest are representatives */
+  int32_t bit_topk;        /* per-head top-k that sets a bit; 0 means `budget`         */
+  int32_t anchor;          /* kvcrush_anchor                                           */
+  uint64_t anchor_seed;    /* RANDOM only                                              */
+  const uint64_t* anchor_bits; /* EXPLICIT only: device [B, W], W = ceil(Hs / 64)      */
+} kvcrush_select_args;
+
+size_t kvcrush_select_workspace(const kvcrush_select_args* args);
+/*   scores  [B, Hs, S] fp32
+ *   idx     [B, budget] int32, ascending token positions
+ *   kind    nullable [B, budget] uint8: 0 kept as important, 1 as representative
+ *   bits    nullable [B, S, W] uint64: head r is bit r % 64 of word r / 64
+ */
+kvcrush_status kvcrush_select(const kvcrush_select_args* args, const float* scores, int32_t* idx,
+                              uint8_t* kind, uint64_t* bits, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
+/* ---------------------------------------------------------------- stage 5 --
+ * k_out[b, h, j, :] = K[b, h, idx[b, j], :], same for V (Sec. 3.2: the
+ * retained tokens form the final cache).  Pure copy, bit exact.
+ *
+ *   dense source  (block_table == NULL): k, v [B, Hkv, S, D]
+ *   paged source  (block_table != NULL): k, v are pools
+ *                 [n_blocks, block_size, Hkv, D]; block_table [B, S / block_size]
+ *                 int32 holds the pool block of each logical block;
+ *                 S % block_size == 0; entries must be valid pool blocks
+ *                 (not checked on the device).
+ *   idx     [B, budget] int32 with 0 <= idx < S (as written by kvcrush_select)
+ *   k_out, v_out [B, Hkv, budget, D], same dtype
+ *   D * sizeof(dtype) must be a multiple of 16.
+ */
+kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int32_t D, int32_t dtype,
+                               int32_t budget, const void* k, const void* v, const int32_t* idx,
+                               const int32_t* block_table, int32_t block_size, void* k_out,
+                               void* v_out, void* hip_stream);
+
+const char* kvcrush_status_string(kvcrush_status status);
+
+/* Library version, e.g. 100 for 0.1.0. */
+int32_t kvcrush_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVCRUSH_H */

@@ -1,0 +1,228 @@
+"""Thin ctypes binding over libkvcrush.so: same names as the C ABI
+(include/kvcrush.h), argument marshalling only.  torch is used for device
+memory and the current HIP stream; every computation happens in the library's
+kernels.  There is no fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libkvcrush.so")
+
+F32, BF16 = 0, 1
+ANCHORS = {"random": 0, "mean": 1, "alternating": 2, "explicit": 3}
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
+
+EXPORTS = (
+    "kvcrush_scores_workspace", "kvcrush_scores", "kvcrush_row_lse", "kvcrush_select_workspace", "kvcrush_select",
+    "kvcrush_compact", "kvcrush_status_string", "kvcrush_version",
+)
+
+
+class KVCrushError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} (status {status})")
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hq", "Hkv", "S", "D", "dtype", "reduce_groups")]
+
+
+class SelectArgs(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hs", "S", "budget", "n_important", "bit_topk", "anchor")] + [
+        ("anchor_seed", ctypes.c_uint64), ("anchor_bits", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load the library built by `paper_2503_00022_amd.build` (never builds, never falls back)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2503_00022_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.kvcrush_scores_workspace.argtypes = [ctypes.POINTER(Shape)]
+        L.kvcrush_scores_workspace.restype = sz
+        L.kvcrush_scores.argtypes = [ctypes.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
+        L.kvcrush_scores.restype = ctypes.c_int
+        L.kvcrush_row_lse.argtypes = [ctypes.POINTER(Shape), vp, vp, vp, vp]
+        L.kvcrush_row_lse.restype = ctypes.c_int
+        L.kvcrush_select_workspace.argtypes = [ctypes.POINTER(SelectArgs)]
+        L.kvcrush_select_workspace.restype = sz
+        L.kvcrush_select.argtypes = [ctypes.POINTER(SelectArgs), vp, vp, vp, vp, vp, sz, vp]
+        L.kvcrush_select.restype = ctypes.c_int
+        L.kvcrush_compact.argtypes = [i32] * 6 + [vp, vp, vp, vp, i32, vp, vp, vp]
+        L.kvcrush_compact.restype = ctypes.c_int
+        L.kvcrush_status_string.argtypes = [ctypes.c_int]
+        L.kvcrush_status_string.restype = ctypes.c_char_p
+        L.kvcrush_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().kvcrush_status_string(status).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"kvcrush handles float32 and bfloat16, got {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
+    if t.device.type != "cuda":
+        raise ValueError(f"{name} must live in GPU memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, what: str):
+    if status != OK:
+        raise KVCrushError(status, what)
+
+
+def make_shape(q: torch.Tensor, k: torch.Tensor, reduce_groups: bool) -> Shape:
+    B, Hq, S, D = q.shape
+    return Shape(B, Hq, k.shape[1], S, D, _dtype_code(q), int(bool(reduce_groups)))
+
+
+def kvcrush_scores_workspace(shape: Shape) -> int:
+    return int(load().kvcrush_scores_workspace(ctypes.byref(shape)))
+
+
+def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=None, stream=None):
+    """q [B,Hq,S,D], k [B,Hkv,S,D] on the GPU -> scores [B,Hs,S] fp32.
+    Returns (scores, workspace); the workspace's first B*Hq*S floats hold the
+    row log-sum-exps when `lse` was not supplied."""
+    q, k = _dev(q, "q"), _dev(k, "k")
+    if q.dtype != k.dtype or q.dim() != 4 or k.dim() != 4 or q.shape[0] != k.shape[0] \
+            or q.shape[2:] != k.shape[2:]:
+        raise ValueError("q and k must be [B,H,S,D] tensors of one dtype with matching B, S, D")
+    shape = make_shape(q, k, reduce_groups)
+    Hs = shape.Hkv if reduce_groups else shape.Hq
+    if scores is None:
+        scores = torch.empty(shape.B, Hs, shape.S, dtype=torch.float32, device=q.device)
+    need = kvcrush_scores_workspace(shape)
+    if workspace is None and lse is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    if lse is not None:
+        lse = _dev(lse, "lse")
+        if lse.dtype != torch.float32 or tuple(lse.shape) != (shape.B, shape.Hq, shape.S):
+            raise ValueError("lse must be fp32 [B,Hq,S]")
+    st = load().kvcrush_scores(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(lse), _ptr(_dev(scores, "scores")),
+                               _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream))
+    _check(st, "kvcrush_scores")
+    return scores, workspace
+
+
+def kvcrush_row_lse(q, k, lse_out=None, stream=None):
+    """q [B,Hq,S,D], k [B,Hkv,S,D] on the GPU -> natural-log row normalisers fp32 [B,Hq,S]."""
+    q, k = _dev(q, "q"), _dev(k, "k")
+    shape = make_shape(q, k, False)
+    if lse_out is None:
+        lse_out = torch.empty(shape.B, shape.Hq, shape.S, dtype=torch.float32, device=q.device)
+    st = load().kvcrush_row_lse(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(_dev(lse_out, "lse_out")),
+                                _stream(stream))
+    _check(st, "kvcrush_row_lse")
+    return lse_out
+
+
+def lse_from_workspace(workspace: torch.Tensor, B: int, Hq: int, S: int) -> torch.Tensor:
+    return workspace[: B * Hq * S * 4].view(torch.float32).view(B, Hq, S)
+
+
+def make_select_args(B, Hs, S, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
+                     anchor_bits=None) -> SelectArgs:
+    return SelectArgs(B, Hs, S, budget, n_important, bit_topk, ANCHORS[anchor] if isinstance(anchor, str) else anchor,
+                      anchor_seed & (2**64 - 1), None if anchor_bits is None else anchor_bits.data_ptr())
+
+
+def kvcrush_select_workspace(args: SelectArgs) -> int:
+    return int(load().kvcrush_select_workspace(ctypes.byref(args)))
+
+
+def kvcrush_select(scores, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
+                   anchor_bits=None, want_kind=True, want_bits=False, idx=None, workspace=None, stream=None):
+    """scores [B,Hs,S] fp32 on the GPU -> (idx int32 [B,budget], kind uint8 | None, bits int64 [B,S,W] | None)."""
+    scores = _dev(scores, "scores")
+    if scores.dtype != torch.float32 or scores.dim() != 3:
+        raise ValueError("scores must be fp32 [B,Hs,S]")
+    B, Hs, S = scores.shape
+    if anchor_bits is not None:
+        anchor_bits = _dev(anchor_bits, "anchor_bits")
+    args = make_select_args(B, Hs, S, budget, n_important, bit_topk, anchor, anchor_seed, anchor_bits)
+    dev = scores.device
+    if idx is None:
+        idx = torch.empty(B, budget, dtype=torch.int32, device=dev)
+    kind = torch.empty(B, budget, dtype=torch.uint8, device=dev) if want_kind else None
+    W = (Hs + 63) // 64
+    bits = torch.empty(B, S, W, dtype=torch.int64, device=dev) if want_bits else None
+    if workspace is None:
+        workspace = torch.empty(max(kvcrush_select_workspace(args), 16), dtype=torch.uint8, device=dev)
+    st = load().kvcrush_select(ctypes.byref(args), _ptr(scores), _ptr(idx), _ptr(kind), _ptr(bits),
+                               _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "kvcrush_select")
+    return idx, kind, bits
+
+
+def kvcrush_compact(k, v, idx, block_table=None, block_size=16, dense_shape=None, k_out=None, v_out=None,
+                    stream=None, validate=True):
+    """Dense k, v [B,Hkv,S,D]; or paged pools [n_blocks,block_size,Hkv,D] with block_table
+    [B,S/block_size] int32 and dense_shape=(B,Hkv,S,D).  Returns (k_out, v_out) [B,Hkv,budget,D]."""
+    k, v, idx = _dev(k, "k"), _dev(v, "v"), _dev(idx, "idx")
+    if idx.dtype != torch.int32 or k.dtype != v.dtype or k.shape != v.shape:
+        raise ValueError("idx must be int32; k and v must match")
+    if block_table is None:
+        B, Hkv, S, D = k.shape
+    else:
+        B, Hkv, S, D = dense_shape
+        block_table = _dev(block_table, "block_table")
+        if block_table.dtype != torch.int32 or tuple(block_table.shape) != (B, S // block_size):
+            raise ValueError("block_table must be int32 [B, S/block_size]")
+        if tuple(k.shape[1:]) != (block_size, Hkv, D):
+            raise ValueError("paged pools must be [n_blocks, block_size, Hkv, D]")
+    budget = idx.shape[1]
+    if idx.shape[0] != B:
+        raise ValueError("idx must be [B,budget]")
+    if validate:  # host-side bounds checks of the gather's index operands (synchronises)
+        if budget and (int(idx.min()) < 0 or int(idx.max()) >= S):
+            raise ValueError("idx out of range")
+        if block_table is not None and (int(block_table.min()) < 0 or int(block_table.max()) >= k.shape[0]):
+            raise ValueError("block_table names a block outside the pool")
+    if k_out is None:
+        k_out = torch.empty(B, Hkv, budget, D, dtype=k.dtype, device=k.device)
+    if v_out is None:
+        v_out = torch.empty(B, Hkv, budget, D, dtype=v.dtype, device=v.device)
+    st = load().kvcrush_compact(B, Hkv, S, D, _dtype_code(k), budget, _ptr(k), _ptr(v), _ptr(idx),
+                                _ptr(block_table), block_size, _ptr(_dev(k_out, "k_out")),
+                                _ptr(_dev(v_out, "v_out")), _stream(stream))
+    _check(st, "kvcrush_compact")
+    return k_out, v_out
+
+
+def kvcrush_version() -> int:
+    return int(load().kvcrush_version())

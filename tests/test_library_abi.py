@@ -1,0 +1,109 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every function the
+header declares, and rejects bad arguments on the host before any launch (no
+compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_00022_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "kvcrush.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2503_00022_amd import build
+        build.build_library()
+    return binding.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvcrush_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_status_strings(lib):
+    assert binding.kvcrush_version() >= 100
+    assert binding.status_string(0) == "ok"
+    for s in range(1, 5):
+        assert binding.status_string(s) not in ("ok", "unknown status")
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_workspace_sizes(lib):
+    sh = binding.Shape(1, 32, 8, 16384, 128, binding.BF16, 1)
+    assert binding.kvcrush_scores_workspace(sh) == 32 * 16384 * 4
+    assert binding.kvcrush_scores_workspace(binding.Shape(1, 30, 8, 16, 128, 1, 1)) == 0   # Hq % Hkv != 0
+    a = binding.make_select_args(1, 8, 16384, 4096, 3072)
+    need = binding.kvcrush_select_workspace(a)
+    nw = 16384 // 64
+    assert need >= (9 * nw + nw) * 8 + 16384 * 4 + 16384 * 8
+    assert binding.kvcrush_select_workspace(binding.make_select_args(1, 8, 100, 101, 5)) == 0  # budget > S
+
+
+FAKE = ctypes.c_void_p(0x1000)  # aligned, never dereferenced: validation fails first
+
+
+def test_scores_rejects_bad_arguments(lib):
+    def call(shape, q=FAKE, k=FAKE, lse=None, scores=FAKE, ws=FAKE, ws_bytes=1 << 40):
+        return lib.kvcrush_scores(ctypes.byref(shape), q, k, lse, scores, ws, ws_bytes, None)
+
+    good = dict(B=1, Hq=4, Hkv=2, S=64, D=128, dtype=1, reduce_groups=0)
+
+    def shape(**kw):
+        d = dict(good, **kw)
+        return binding.Shape(d["B"], d["Hq"], d["Hkv"], d["S"], d["D"], d["dtype"], d["reduce_groups"])
+
+    assert call(shape(S=0)) == binding.ERR_INVALID_ARG
+    assert call(shape(Hq=5)) == binding.ERR_INVALID_ARG
+    assert call(shape(dtype=7)) == binding.ERR_INVALID_ARG
+    assert call(shape(reduce_groups=2)) == binding.ERR_INVALID_ARG
+    assert call(shape(D=96)) == binding.ERR_UNSUPPORTED
+    assert call(shape(), q=None) == binding.ERR_INVALID_ARG
+    assert call(shape(), q=ctypes.c_void_p(0x1004)) == binding.ERR_INVALID_ARG      # misaligned
+    assert call(shape(), ws=None) == binding.ERR_WORKSPACE
+    assert call(shape(), ws_bytes=16) == binding.ERR_WORKSPACE
+
+
+def test_select_rejects_bad_arguments(lib):
+    def call(args, scores=FAKE, idx=FAKE, ws=FAKE, ws_bytes=1 << 40):
+        return lib.kvcrush_select(ctypes.byref(args), scores, idx, None, None, ws, ws_bytes, None)
+
+    mk = binding.make_select_args
+    assert call(mk(1, 8, 100, 101, 10)) == binding.ERR_INVALID_ARG           # budget > S
+    assert call(mk(1, 8, 100, 50, 51)) == binding.ERR_INVALID_ARG            # n_important > budget
+    assert call(mk(1, 8, 100, 50, 10, bit_topk=101)) == binding.ERR_INVALID_ARG
+    assert call(mk(1, 0, 100, 50, 10)) == binding.ERR_INVALID_ARG
+    assert call(mk(1, 129, 100, 50, 10)) == binding.ERR_UNSUPPORTED          # more than 128 heads
+    assert call(mk(1, 8, 100, 50, 10, anchor=9)) == binding.ERR_INVALID_ARG
+    assert call(mk(1, 8, 100, 50, 10, anchor="explicit")) == binding.ERR_INVALID_ARG  # no anchor_bits
+    assert call(mk(1, 8, 100, 50, 10), scores=None) == binding.ERR_INVALID_ARG
+    assert call(mk(1, 8, 100, 50, 10), ws=None) == binding.ERR_WORKSPACE
+    assert call(mk(1, 8, 100, 50, 10), ws_bytes=64) == binding.ERR_WORKSPACE
+
+
+def test_compact_rejects_bad_arguments(lib):
+    def call(B=1, Hkv=2, S=64, D=128, dtype=1, budget=16, k=FAKE, v=FAKE, idx=FAKE, bt=None, bs=16,
+             ko=FAKE, vo=FAKE):
+        return lib.kvcrush_compact(B, Hkv, S, D, dtype, budget, k, v, idx, bt, bs, ko, vo, None)
+
+    assert call(budget=65) == binding.ERR_INVALID_ARG
+    assert call(budget=-1) == binding.ERR_INVALID_ARG
+    assert call(dtype=3) == binding.ERR_INVALID_ARG
+    assert call(D=4) == binding.ERR_UNSUPPORTED                 # 8-byte rows cannot be moved as 16-byte vectors
+    assert call(k=None) == binding.ERR_INVALID_ARG
+    assert call(ko=ctypes.c_void_p(0x1008)) == binding.ERR_INVALID_ARG
+    assert call(S=70, bt=FAKE, bs=16) == binding.ERR_INVALID_ARG  # S not a multiple of the block size
+    assert call(budget=0, k=None, v=None, idx=None, ko=None, vo=None) == binding.OK   # nothing to do
