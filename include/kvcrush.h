@@ -88,7 +88,8 @@ typedef struct {
  *           NULL: computed here (one more pass over Q K^T) and left in the
  *           first B*Hq*S floats of the workspace.
  *   scores  [B, Hs, S] fp32, fully overwritten
- *   workspace  kvcrush_scores_workspace(shape) bytes
+ *   workspace  kvcrush_scores_workspace(shape) bytes, always required: the
+ *           row log-sum-exps first, then partial column sums of long sequences
  * Accuracy: bf16 (or fp32) products, fp32 accumulation; each score is within
  * 2e-3 relative of the exact value.
  */

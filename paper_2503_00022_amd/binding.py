@@ -127,7 +127,7 @@ def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=N
     if scores is None:
         scores = torch.empty(shape.B, Hs, shape.S, dtype=torch.float32, device=q.device)
     need = kvcrush_scores_workspace(shape)
-    if workspace is None and lse is None:
+    if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
     if lse is not None:
         lse = _dev(lse, "lse")

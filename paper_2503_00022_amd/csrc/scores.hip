@@ -114,19 +114,108 @@ struct ScoreParams {
   const char* k;     // [B,Hkv,S,D]
   float* lse;        // [B,Hq,S] natural log (written by pass A, read by pass B)
   float* scores;     // [B,Hs,S]
+  float* partial;    // pass B: [n_bh, n_kb, n_chunks, 256] partial column sums (n_chunks > 1)
   int B, Hq, Hkv, S, G;
   int reduce_groups;
   int heads_per_wg;  // pass A: query heads sharing one workgroup's K stream (1, 2 or 4)
-  int n_blocks;      // blocks along the sequence
+  int n_blocks;      // pass A: query blocks; pass B: 256-key blocks
   int n_bh;          // (batch, head-group) pairs
+  int chunk_tiles;   // pass B: query tiles per work piece
+  int n_chunks;      // pass B: chunks along the query axis
   float scale_log2;  // log2(e) / sqrt(D)
 };
+
+constexpr int kKeysPerWg = 64 * kWaves;  // pass B: keys held by one workgroup
+
+template <class C>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[2]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+}
+
+// Two 32x32 tiles of one step.  STREAM_IS_A: the LDS sub-tile supplies the rows
+// (keys) and the two register operands the columns (pass A); otherwise the two
+// register operands supply rows (keys) and the LDS sub-tile the columns (pass B).
+template <class C, bool BF16, bool STREAM_IS_A>
+__device__ __forceinline__ void mma_pair(f32x16 (&acc)[2], const char* buf, int sub,
+                                         const u32x4 (&r0)[C::kSteps], const u32x4 (&r1)[C::kSteps],
+                                         int lane) {
+  zero_acc<C>(acc);
+#pragma unroll
+  for (int s = 0; s < C::kSteps; ++s) {
+    const u32x4 f = lds_frag<C>(buf, sub, s, lane);
+    if constexpr (STREAM_IS_A) {
+      mma_step<BF16>(acc[0], f, r0[s]);
+      mma_step<BF16>(acc[1], f, r1[s]);
+    } else {
+      mma_step<BF16>(acc[0], r0[s], f);
+      mma_step<BF16>(acc[1], r1[s], f);
+    }
+  }
+}
+
+// Online max / sum over the 16 key rows a lane holds of one tile (pass A).
+// `lim` >= 15 + 8 means no masking; otherwise rows with 8*(r/4)+(r%4) > lim are
+// keys after the query and are left out.
+template <bool MASK>
+__device__ __forceinline__ void softmax_update(f32x16& acc, float& m, float& l, float c, int lim) {
+  if constexpr (MASK) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = (8 * (r >> 2) + (r & 3)) <= lim ? acc[r] : -INFINITY;
+  }
+#ifdef KVC_EXP_NO_VALU
+  if constexpr (!MASK) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) l += acc[r];
+    return;
+  }
+#endif
+  float mx = acc[0];
+#pragma unroll
+  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+  const float mnew = fmaxf(m, mx * c);
+  float sum = 0.0f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[r], c, -mnew));
+  l = l * __builtin_amdgcn_exp2f(m - mnew) + sum;
+  m = mnew;
+}
+
+// Probabilities of one tile added to the running column sums (pass B).
+template <bool MASK>
+__device__ __forceinline__ void colsum_update(const f32x16& acc, f32x16& col, float c, float lse2,
+                                              int lim) {
+#ifdef KVC_EXP_NO_VALU
+  if constexpr (!MASK) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) col[r] += acc[r];
+    return;
+  }
+#endif
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[r], c, -lse2));
+    if constexpr (MASK)
+      col[r] += (8 * (r >> 2) + (r & 3)) <= lim ? e : 0.0f;
+    else
+      col[r] += e;
+  }
+}
+
+// Finite stand-in for "no key seen yet": keeps exp2(m_old - m_new) free of inf - inf.
+constexpr float kNegBig = -1.0e30f;
 
 // ------------------------------------------------------------- pass A ------
 // Workgroup = 4 waves sharing one stream of K tiles.  Each wave keeps 64 query
 // rows of one head in registers (two 32-row sub-tiles).  With grouped-query
 // attention the waves take different heads of the same KV group (same query
 // range); otherwise they take consecutive 64-row query blocks of one head.
+// K tiles wholly before the workgroup's first query need no mask: they run in a
+// software-pipelined loop where the MFMAs of the next sub-tile are issued
+// together with the max/exp/sum work on the previous one.  The few tiles that
+// touch the diagonal go through a plain masked loop afterwards.
 template <bool BF16, int D>
 __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   using C = Cfg<BF16, D>;
@@ -154,61 +243,67 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
 
   const int wg_qmax = min(S, wg_q0 + 64 * qsub) - 1;
   const int n_tiles = wg_qmax / C::kTile + 1;
+  const int n_full = wg_q0 / C::kTile;  // tiles whose keys all precede every query of the workgroup
 
-  float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.0f, 0.0f};
+  float m[2] = {kNegBig, kNegBig}, l[2] = {0.0f, 0.0f};
   const float c = p.scale_log2;
-
   u32x4 st[C::kStage];
-  stage_load<C>(st, kh, 0, S, tid);
-  stage_store<C>(st, lds[0], tid);
-  __syncthreads();
 
-  for (int it = 0; it < n_tiles; ++it) {
-    const int kt = it * C::kTile;
-    const char* buf = lds[it & 1];
-    if (it + 1 < n_tiles) stage_load<C>(st, kh, kt + C::kTile, S, tid);
-
+  if (n_full > 0) {
+    stage_load<C>(st, kh, 0, S, tid);
+    stage_store<C>(st, lds[0], tid);
+    __syncthreads();
+    f32x16 acc_a[2], acc_b[2];
+    mma_pair<C, BF16, true>(acc_a, lds[0], 0, qf[0], qf[1], lane);
+    for (int it = 0; it < n_full; ++it) {
+      const bool has_next = it + 1 < n_full;
+      if (has_next) stage_load<C>(st, kh, (it + 1) * C::kTile, S, tid);
 #pragma unroll
-    for (int ks = 0; ks < C::kTileSub; ++ks) {
-      const int kmin = kt + 32 * ks, kmax = kmin + 31;
-      if (kmin > q0 + 63) continue;  // every key of this sub-tile is in the future of all 64 rows
-      f32x16 acc[2];
-#pragma unroll
-      for (int ns = 0; ns < 2; ++ns)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[ns][r] = 0.0f;
-#pragma unroll
-      for (int s = 0; s < C::kSteps; ++s) {
-        const u32x4 a = lds_frag<C>(buf, ks, s, lane);
-        mma_step<BF16>(acc[0], a, qf[0][s]);
-        mma_step<BF16>(acc[1], a, qf[1][s]);
-      }
-#pragma unroll
-      for (int ns = 0; ns < 2; ++ns) {
-        const int qmin = q0 + 32 * ns;
-        if (kmin > qmin + 31) continue;  // uniform: nothing visible for this sub-tile
-        if (kmax > qmin) {               // diagonal sub-tile: hide keys after the query
-          const int lim = qmin + (lane & 31) - kmin - 4 * (lane >> 5);
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            acc[ns][r] = (8 * (r >> 2) + (r & 3)) <= lim ? acc[ns][r] : -INFINITY;
+      for (int ks = 0; ks < C::kTileSub; ++ks) {
+        if (ks + 1 < C::kTileSub) {
+          mma_pair<C, BF16, true>(acc_b, lds[it & 1], ks + 1, qf[0], qf[1], lane);
+        } else {
+          if (has_next) stage_store<C>(st, lds[(it + 1) & 1], tid);
+          __syncthreads();
+          if (has_next) mma_pair<C, BF16, true>(acc_b, lds[(it + 1) & 1], 0, qf[0], qf[1], lane);
         }
-        float mx = acc[ns][0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[ns][r]);
-        const float mnew = fmaxf(m[ns], mx * c);
-        if (mnew > -INFINITY) {
-          float sum = 0.0f;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[ns][r], c, -mnew));
-          l[ns] = l[ns] * __builtin_amdgcn_exp2f(m[ns] - mnew) + sum;
-          m[ns] = mnew;
-        }
+        softmax_update<false>(acc_a[0], m[0], l[0], c, 0);
+        softmax_update<false>(acc_a[1], m[1], l[1], c, 0);
+        acc_a[0] = acc_b[0];
+        acc_a[1] = acc_b[1];
       }
     }
+  }
 
-    if (it + 1 < n_tiles) stage_store<C>(st, lds[(it + 1) & 1], tid);
+  if (n_tiles > n_full) {
+    stage_load<C>(st, kh, n_full * C::kTile, S, tid);
+    stage_store<C>(st, lds[0], tid);
     __syncthreads();
+    for (int it = n_full; it < n_tiles; ++it) {
+      const int kt = it * C::kTile;
+      const char* buf = lds[(it - n_full) & 1];
+      if (it + 1 < n_tiles) stage_load<C>(st, kh, kt + C::kTile, S, tid);
+#pragma unroll
+      for (int ks = 0; ks < C::kTileSub; ++ks) {
+        const int kmin = kt + 32 * ks, kmax = kmin + 31;
+        if (kmin > q0 + 63) continue;  // every key of this sub-tile comes after all 64 rows
+        f32x16 acc[2];
+        mma_pair<C, BF16, true>(acc, buf, ks, qf[0], qf[1], lane);
+#pragma unroll
+        for (int ns = 0; ns < 2; ++ns) {
+          const int qmin = q0 + 32 * ns;
+          if (kmin > qmin + 31) continue;  // uniform: nothing visible for this sub-tile
+          if (kmax > qmin) {
+            const int lim = qmin + (lane & 31) - kmin - 4 * (lane >> 5);
+            softmax_update<true>(acc[ns], m[ns], l[ns], c, lim);
+          } else {
+            softmax_update<false>(acc[ns], m[ns], l[ns], c, 0);
+          }
+        }
+      }
+      if (it + 1 < n_tiles) stage_store<C>(st, lds[(it - n_full + 1) & 1], tid);
+      __syncthreads();
+    }
   }
 
   // lanes l and l^32 saw disjoint key rows of the same query: merge, then store
@@ -216,9 +311,7 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   for (int ns = 0; ns < 2; ++ns) {
     const float mo = __shfl_xor(m[ns], 32), lo = __shfl_xor(l[ns], 32);
     const float mt = fmaxf(m[ns], mo);
-    float lt = 0.0f;
-    if (m[ns] > -INFINITY) lt += l[ns] * __builtin_amdgcn_exp2f(m[ns] - mt);
-    if (mo > -INFINITY) lt += lo * __builtin_amdgcn_exp2f(mo - mt);
+    const float lt = l[ns] * __builtin_amdgcn_exp2f(m[ns] - mt) + lo * __builtin_amdgcn_exp2f(mo - mt);
     const int qi = q0 + 32 * ns + (lane & 31);
     if (lane < 32 && qi < S)
       p.lse[((size_t)b * p.Hq + head) * S + qi] = (mt + __builtin_amdgcn_logf(lt)) * kLn2;
@@ -228,9 +321,15 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
 // ------------------------------------------------------------- pass B ------
 // Workgroup = 4 waves sharing one stream of Q tiles (and their lse).  Each wave
 // keeps 64 key rows in registers and 2x16 running column sums; the workgroup
-// covers 256 consecutive keys of one KV head and walks the query tiles from
-// the end of the sequence down to its own diagonal, for one query head or,
-// when the group is reduced, for each head of the group in turn.
+// covers 256 consecutive keys of one KV head.  The causal triangle of
+// (key block, query tile) pairs is cut into pieces of at most `chunk_tiles`
+// query tiles so that all workgroups get similar amounts of work; pieces that
+// share a query chunk are neighbours in launch order, so the Q tiles they
+// stream stay in the L2 of their XCD.  A piece covers every query head of the
+// score row (one head, or the whole group when groups are reduced).  When a key
+// block needs more than one piece, each writes partial sums and
+// colsum_reduce_kernel adds them in a fixed order (no floating-point atomics:
+// the result does not depend on scheduling).
 template <bool BF16, int D>
 __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, const float* lse_in) {
   using C = Cfg<BF16, D>;
@@ -239,14 +338,30 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
 
   const int tid = threadIdx.x, lane = kvc::lane_id(), wave = tid / KVC_WAVE;
   const int S = p.S;
-  const int blk = (int)(blockIdx.x / p.n_bh);  // key block, early (heavy) blocks first
+  constexpr int kTpk = kKeysPerWg / C::kTile;  // query tiles spanned by the workgroup's keys
+  const int n_tiles = (S + C::kTile - 1) / C::kTile;
+  const int n_kb = p.n_blocks;
+
+  // piece -> (chunk, key block): chunks from the end of the sequence backwards
   const int bh = (int)(blockIdx.x % p.n_bh);
+  int rem = (int)(blockIdx.x / p.n_bh);
+  int chunk = p.n_chunks - 1;
+  int t_last;
+  for (;;) {
+    t_last = min((chunk + 1) * p.chunk_tiles, n_tiles) - 1;
+    const int cnt = min(n_kb, t_last / kTpk + 1);
+    if (rem < cnt) break;
+    rem -= cnt;
+    --chunk;
+  }
+  const int kb = rem;
+
   const int rows = p.reduce_groups ? p.Hkv : p.Hq;
   const int b = bh / rows, row = bh % rows;
   const int kvh = p.reduce_groups ? row : row / p.G;
   const int head0 = p.reduce_groups ? row * p.G : row;
   const int n_heads = p.reduce_groups ? p.G : 1;
-  const int wg_k0 = blk * 64 * kWaves;
+  const int wg_k0 = kb * kKeysPerWg;
   const int k0 = wg_k0 + wave * 64;  // first key row of this wave
 
   const char* kh = p.k + ((size_t)b * p.Hkv + kvh) * S * C::kRowBytes;
@@ -254,95 +369,131 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   load_stationary<C>(kf[0], kh, k0, S, lane);
   load_stationary<C>(kf[1], kh, k0 + 32, S, lane);
 
-  const int tile_lo = wg_k0 / C::kTile, tile_hi = (S - 1) / C::kTile;  // inclusive
-  const int tiles_per_head = tile_hi - tile_lo + 1;
-  const int n_iter = tiles_per_head * n_heads;
+  // tiles of this piece: [t_first, t_last]; those below f_first touch the diagonal
+  const int t_first = max(chunk * p.chunk_tiles, kb * kTpk);
+  const int f_first = max(t_first, kb * kTpk + kTpk);
+  const int n_fullt = max(0, t_last - f_first + 1);
+  const int d_last = min(t_last, kb * kTpk + kTpk - 1);
+  const int n_diagt = max(0, d_last - t_first + 1);
   const float c = p.scale_log2;
 
   f32x16 col[2];
-#pragma unroll
-  for (int ms = 0; ms < 2; ++ms)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) col[ms][r] = 0.0f;
+  zero_acc<C>(col);
 
-  auto tile_of = [&](int it, int& head, int& qt) {
-    head = head0 + it / tiles_per_head;
-    qt = (tile_hi - it % tiles_per_head) * C::kTile;
-  };
+  auto q_head = [&](int head) { return p.q + ((size_t)b * p.Hq + head) * S * C::kRowBytes; };
   auto load_lse = [&](int head, int qt) -> float {
     // +inf for rows past the end makes their probabilities exactly zero
     float v = INFINITY;
     if (tid < C::kTile && qt + tid < S) v = lse_in[((size_t)b * p.Hq + head) * S + qt + tid] * kLog2e;
     return v;
   };
-
   u32x4 st[C::kStage];
   float st_lse;
-  {
+
+  // ---- tiles after the diagonal: no mask, software pipelined
+  const int n_fast = n_heads * n_fullt;
+  if (n_fast > 0) {
+    auto tile_of = [&](int it, int& head, int& qt) {
+      head = head0 + it / n_fullt;
+      qt = (t_last - it % n_fullt) * C::kTile;
+    };
     int head, qt;
     tile_of(0, head, qt);
-    stage_load<C>(st, p.q + ((size_t)b * p.Hq + head) * S * C::kRowBytes, qt, S, tid);
+    stage_load<C>(st, q_head(head), qt, S, tid);
     st_lse = load_lse(head, qt);
     stage_store<C>(st, lds[0], tid);
     if (tid < C::kTile) lds_lse[0][tid] = st_lse;
-  }
-  __syncthreads();
-
-  for (int it = 0; it < n_iter; ++it) {
-    int head, qt;
-    tile_of(it, head, qt);
-    const char* buf = lds[it & 1];
-    if (it + 1 < n_iter) {
-      int nh, nqt;
-      tile_of(it + 1, nh, nqt);
-      stage_load<C>(st, p.q + ((size_t)b * p.Hq + nh) * S * C::kRowBytes, nqt, S, tid);
-      st_lse = load_lse(nh, nqt);
-    }
-
-#pragma unroll
-    for (int ns = 0; ns < C::kTileSub; ++ns) {
-      const int qmin = qt + 32 * ns, qmax = qmin + 31;
-      if (qmax < k0) continue;  // all 64 keys of this wave are in the future of these queries
-      const float lse2 = lds_lse[it & 1][32 * ns + (lane & 31)];
-      f32x16 acc[2];
-#pragma unroll
-      for (int ms = 0; ms < 2; ++ms)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[ms][r] = 0.0f;
-#pragma unroll
-      for (int s = 0; s < C::kSteps; ++s) {
-        const u32x4 bq = lds_frag<C>(buf, ns, s, lane);
-        mma_step<BF16>(acc[0], kf[0][s], bq);
-        mma_step<BF16>(acc[1], kf[1][s], bq);
+    __syncthreads();
+    f32x16 acc_a[2], acc_b[2];
+    mma_pair<C, BF16, false>(acc_a, lds[0], 0, kf[0], kf[1], lane);
+    for (int it = 0; it < n_fast; ++it) {
+      const bool has_next = it + 1 < n_fast;
+      if (has_next) {
+        tile_of(it + 1, head, qt);
+        stage_load<C>(st, q_head(head), qt, S, tid);
+        st_lse = load_lse(head, qt);
       }
 #pragma unroll
-      for (int ms = 0; ms < 2; ++ms) {
-        const int kmin = k0 + 32 * ms;
-        if (qmax < kmin) continue;
-        if (kmin + 31 > qmin) {  // diagonal sub-tile
-          const int lim = qmin + (lane & 31) - kmin - 4 * (lane >> 5);
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[ms][r], c, -lse2));
-            col[ms][r] += (8 * (r >> 2) + (r & 3)) <= lim ? e : 0.0f;
-          }
+      for (int ns = 0; ns < C::kTileSub; ++ns) {
+        const float lse2 = lds_lse[it & 1][32 * ns + (lane & 31)];  // read before the barrier below
+        if (ns + 1 < C::kTileSub) {
+          mma_pair<C, BF16, false>(acc_b, lds[it & 1], ns + 1, kf[0], kf[1], lane);
         } else {
+          if (has_next) {
+            stage_store<C>(st, lds[(it + 1) & 1], tid);
+            if (tid < C::kTile) lds_lse[(it + 1) & 1][tid] = st_lse;
+          }
+          __syncthreads();
+          if (has_next) mma_pair<C, BF16, false>(acc_b, lds[(it + 1) & 1], 0, kf[0], kf[1], lane);
+        }
+        colsum_update<false>(acc_a[0], col[0], c, lse2, 0);
+        colsum_update<false>(acc_a[1], col[1], c, lse2, 0);
+        acc_a[0] = acc_b[0];
+        acc_a[1] = acc_b[1];
+      }
+    }
+  }
+
+  // ---- tiles on the diagonal: masked, plain loop
+  const int n_slow = n_heads * n_diagt;
+  if (n_slow > 0) {
+    auto tile_of = [&](int it, int& head, int& qt) {
+      head = head0 + it / n_diagt;
+      qt = (d_last - it % n_diagt) * C::kTile;
+    };
+    int head, qt;
+    tile_of(0, head, qt);
+    stage_load<C>(st, q_head(head), qt, S, tid);
+    st_lse = load_lse(head, qt);
+    stage_store<C>(st, lds[0], tid);
+    if (tid < C::kTile) lds_lse[0][tid] = st_lse;
+    __syncthreads();
+    for (int it = 0; it < n_slow; ++it) {
+      tile_of(it, head, qt);
+      const int qt_cur = qt;
+      const char* buf = lds[it & 1];
+      if (it + 1 < n_slow) {
+        tile_of(it + 1, head, qt);
+        stage_load<C>(st, q_head(head), qt, S, tid);
+        st_lse = load_lse(head, qt);
+      }
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            col[ms][r] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[ms][r], c, -lse2));
+      for (int ns = 0; ns < C::kTileSub; ++ns) {
+        const int qmin = qt_cur + 32 * ns, qmax = qmin + 31;
+        if (qmax < k0) continue;  // all 64 keys of this wave come after these queries
+        const float lse2 = lds_lse[it & 1][32 * ns + (lane & 31)];
+        f32x16 acc[2];
+        mma_pair<C, BF16, false>(acc, buf, ns, kf[0], kf[1], lane);
+#pragma unroll
+        for (int ms = 0; ms < 2; ++ms) {
+          const int kmin = k0 + 32 * ms;
+          if (qmax < kmin) continue;
+          if (kmin + 31 > qmin) {
+            const int lim = qmin + (lane & 31) - kmin - 4 * (lane >> 5);
+            colsum_update<true>(acc[ms], col[ms], c, lse2, lim);
+          } else {
+            colsum_update<false>(acc[ms], col[ms], c, lse2, 0);
+          }
         }
       }
+      if (it + 1 < n_slow) {
+        stage_store<C>(st, lds[(it + 1) & 1], tid);
+        if (tid < C::kTile) lds_lse[(it + 1) & 1][tid] = st_lse;
+      }
+      __syncthreads();
     }
-
-    if (it + 1 < n_iter) {
-      stage_store<C>(st, lds[(it + 1) & 1], tid);
-      if (tid < C::kTile) lds_lse[(it + 1) & 1][tid] = st_lse;
-    }
-    __syncthreads();
   }
 
   // sum over the 32 query lanes of each half-wave; lanes 0 and 32 then hold the rows
-  float* out = p.scores + ((size_t)b * rows + row) * S;
+  float* out;
+  int t_limit;
+  if (p.n_chunks == 1) {
+    out = p.scores + (size_t)bh * S + k0;
+    t_limit = S - k0;
+  } else {
+    out = p.partial + (((size_t)bh * n_kb + kb) * p.n_chunks + chunk) * kKeysPerWg + wave * 64;
+    t_limit = 64;
+  }
 #pragma unroll
   for (int ms = 0; ms < 2; ++ms) {
 #pragma unroll
@@ -350,11 +501,45 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       float v = col[ms][r];
 #pragma unroll
       for (int off = 16; off > 0; off >>= 1) v += __shfl_xor(v, off);
-      const int t = k0 + 32 * ms + acc_row(r, lane);
-      if ((lane & 31) == 0 && t < S) out[t] = v;
+      const int t = 32 * ms + acc_row(r, lane);
+      if ((lane & 31) == 0 && t < t_limit) out[t] = v;
     }
   }
 }
+
+// scores[bh, t] = sum of the partial sums of key t's pieces, chunks ascending.
+__global__ __launch_bounds__(kKeysPerWg) void colsum_reduce_kernel(ScoreParams p, int tiles_per_kb) {
+  const int kb = blockIdx.x, bh = blockIdx.y;
+  const int t = kb * kKeysPerWg + threadIdx.x;
+  if (t >= p.S) return;
+  const int c_min = kb * tiles_per_kb / p.chunk_tiles;
+  const float* src = p.partial + ((size_t)bh * p.n_blocks + kb) * p.n_chunks * kKeysPerWg + threadIdx.x;
+  float acc = 0.0f;
+  for (int c = c_min; c < p.n_chunks; ++c) acc += src[(size_t)c * kKeysPerWg];
+  p.scores[(size_t)bh * p.S + t] = acc;
+}
+
+// Work pieces of pass B for a sequence of n_tiles query tiles.
+struct ColsumPlan {
+  int n_kb, n_chunks, chunk_tiles, pieces;  // pieces per (batch, score row)
+};
+
+ColsumPlan colsum_plan(int S, int tile, int chunk_tiles_wanted) {
+  ColsumPlan pl;
+  const int n_tiles = (S + tile - 1) / tile, tpk = kKeysPerWg / tile;
+  pl.n_kb = (S + kKeysPerWg - 1) / kKeysPerWg;
+  pl.chunk_tiles = chunk_tiles_wanted;
+  pl.n_chunks = (n_tiles + pl.chunk_tiles - 1) / pl.chunk_tiles;
+  pl.pieces = 0;
+  for (int c = 0; c < pl.n_chunks; ++c) {
+    const int t_last = (c + 1) * pl.chunk_tiles < n_tiles ? (c + 1) * pl.chunk_tiles - 1 : n_tiles - 1;
+    const int cnt = t_last / tpk + 1;
+    pl.pieces += cnt < pl.n_kb ? cnt : pl.n_kb;
+  }
+  return pl;
+}
+
+constexpr int kChunkQueries = 1024;  // queries per pass-B work piece
 
 template <bool BF16, int D>
 kvcrush_status launch_lse(const ScoreParams& base, hipStream_t stream) {
@@ -371,17 +556,39 @@ kvcrush_status launch_lse(const ScoreParams& base, hipStream_t stream) {
 template <bool BF16, int D>
 kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, bool lse_only,
                              hipStream_t stream) {
+  using C = Cfg<BF16, D>;
   ScoreParams p = base;
-  const int S = p.S;
   if (!lse_user) {
     if (launch_lse<BF16, D>(p, stream) != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
   if (lse_only) return KVCRUSH_OK;
-  p.n_blocks = (S + 64 * kWaves - 1) / (64 * kWaves);
+  const ColsumPlan pl = colsum_plan(p.S, C::kTile, kChunkQueries / C::kTile);
+  p.n_blocks = pl.n_kb;
+  p.n_chunks = pl.n_chunks;
+  p.chunk_tiles = pl.chunk_tiles;
   p.n_bh = p.B * (p.reduce_groups ? p.Hkv : p.Hq);
-  hipLaunchKernelGGL((colsum_kernel<BF16, D>), dim3((unsigned)(p.n_blocks * p.n_bh)), dim3(kThreads),
-                     0, stream, p, lse_user ? lse_user : p.lse);
-  return kvc::launch_status();
+  hipLaunchKernelGGL((colsum_kernel<BF16, D>), dim3((unsigned)(pl.pieces * p.n_bh)), dim3(kThreads), 0,
+                     stream, p, lse_user ? lse_user : p.lse);
+  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  if (pl.n_chunks > 1) {
+    hipLaunchKernelGGL(colsum_reduce_kernel, dim3(pl.n_kb, p.n_bh), dim3(kKeysPerWg), 0, stream, p,
+                       kKeysPerWg / C::kTile);
+    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  }
+  return KVCRUSH_OK;
+}
+
+// Workspace: [lse: B*Hq*S floats][partial column sums]
+size_t lse_bytes(const kvcrush_shape* s) {
+  return kvc::align_up((size_t)s->B * s->Hq * s->S * sizeof(float), 256);
+}
+
+size_t partial_bytes(const kvcrush_shape* s) {
+  const int tile = s->dtype == KVCRUSH_BF16 ? 64 : 32;
+  const ColsumPlan pl = colsum_plan(s->S, tile, kChunkQueries / tile);
+  if (pl.n_chunks <= 1) return 0;
+  const size_t rows = (size_t)s->B * (s->reduce_groups ? s->Hkv : s->Hq);
+  return kvc::align_up(rows * pl.n_kb * pl.n_chunks * kKeysPerWg * sizeof(float), 256);
 }
 
 bool shape_ok(const kvcrush_shape* s) {
@@ -397,21 +604,22 @@ bool shape_ok(const kvcrush_shape* s) {
 
 extern "C" size_t kvcrush_scores_workspace(const kvcrush_shape* shape) {
   if (!shape_ok(shape)) return 0;
-  return kvc::align_up((size_t)shape->B * shape->Hq * shape->S * sizeof(float), 256);
+  return lse_bytes(shape) + partial_bytes(shape);
 }
 
 namespace {
 
 kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const void* k,
-                            const float* lse, float* lse_out, float* scores, bool lse_only,
-                            hipStream_t stream) {
+                            const float* lse, float* lse_out, float* partial, float* scores,
+                            bool lse_only, hipStream_t stream) {
   const long long blocks_a = (long long)shape->B * shape->Hq * ((shape->S + 63) / 64);
-  if (blocks_a > 0x7FFFFFFFll) return KVCRUSH_ERR_UNSUPPORTED;
+  if (blocks_a > 0x3FFFFFFFll) return KVCRUSH_ERR_UNSUPPORTED;
   ScoreParams p;
   p.q = (const char*)q;
   p.k = (const char*)k;
   p.lse = lse_out;
   p.scores = scores;
+  p.partial = partial;
   p.B = shape->B;
   p.Hq = shape->Hq;
   p.Hkv = shape->Hkv;
@@ -421,6 +629,8 @@ kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const voi
   p.heads_per_wg = 1;
   p.n_blocks = 0;
   p.n_bh = 0;
+  p.chunk_tiles = 1;
+  p.n_chunks = 1;
   p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)shape->D));
   const bool bf16 = shape->dtype == KVCRUSH_BF16;
   if (bf16 && shape->D == 128) return launch_scores<true, 128>(p, lse, lse_only, stream);
@@ -439,12 +649,11 @@ extern "C" kvcrush_status kvcrush_scores(const kvcrush_shape* shape, const void*
   if (!q || !k || !scores) return KVCRUSH_ERR_INVALID_ARG;
   if (!kvc::aligned16(q) || !kvc::aligned16(k) || !kvc::aligned16(scores) || !kvc::aligned16(lse))
     return KVCRUSH_ERR_INVALID_ARG;
-  if (!lse) {
-    if (!workspace || !kvc::aligned16(workspace) ||
-        workspace_bytes < kvcrush_scores_workspace(shape))
-      return KVCRUSH_ERR_WORKSPACE;
-  }
-  return scores_entry(shape, q, k, lse, (float*)workspace, scores, false, (hipStream_t)hip_stream);
+  if (!workspace || !kvc::aligned16(workspace) || workspace_bytes < kvcrush_scores_workspace(shape))
+    return KVCRUSH_ERR_WORKSPACE;
+  float* partial = (float*)((char*)workspace + lse_bytes(shape));
+  return scores_entry(shape, q, k, lse, (float*)workspace, partial, scores, false,
+                      (hipStream_t)hip_stream);
 }
 
 extern "C" kvcrush_status kvcrush_row_lse(const kvcrush_shape* shape, const void* q, const void* k,
@@ -454,7 +663,7 @@ extern "C" kvcrush_status kvcrush_row_lse(const kvcrush_shape* shape, const void
   if (!q || !k || !lse_out) return KVCRUSH_ERR_INVALID_ARG;
   if (!kvc::aligned16(q) || !kvc::aligned16(k) || !kvc::aligned16(lse_out))
     return KVCRUSH_ERR_INVALID_ARG;
-  return scores_entry(shape, q, k, nullptr, lse_out, nullptr, true, (hipStream_t)hip_stream);
+  return scores_entry(shape, q, k, nullptr, lse_out, nullptr, nullptr, true, (hipStream_t)hip_stream);
 }
 
 extern "C" const char* kvcrush_status_string(kvcrush_status status) {
