@@ -18,10 +18,22 @@
 //     cross-lane reduction over queries happens once, at the very end.
 // The operand that stays fixed for a workgroup's lifetime (64 query rows per
 // wave in pass A, 64 key rows per wave in pass B) lives in registers; the other
-// one streams through double-buffered LDS tiles shared by the four waves.
-// The k-index permutation inside an MFMA step is free as long as both operands
-// use the same one, which lets every lane fetch its 8 (bf16) or 4 (fp32)
-// contiguous elements with a single 16-byte load.
+// one streams through LDS tiles shared by the four waves.
+//
+// Data movement.  Tiles go from global memory straight into LDS
+// (global_load_lds_dwordx4, no register staging) one whole iteration ahead of
+// their use, through three rotating buffers; rows are stored unpadded and the 16-byte chunks of every 256-byte
+// line are XOR-swizzled by the line number, which keeps the ds_read_b128
+// fragment reads free of bank conflicts.  The k-index permutation inside an
+// MFMA step is free as long as both operands use the same one: lane group g
+// (lane / 32) takes chunk  step + g * steps  of a row, i.e. one 16-byte load.
+//
+// Instruction order.  Away from the diagonal the bf16 kernels run a software
+// pipeline written out by hand: every pair of MFMAs of the current 64x32 block
+// is followed by the ds_read that fetches the same fragment of the NEXT block
+// (so LDS latency is hidden behind a whole block of work) and by a slice of the
+// exp / max / sum work on the PREVIOUS block's accumulators (so the matrix core
+// and the VALU run side by side inside one wave).
 #include "common.h"
 
 namespace {
@@ -32,20 +44,23 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / KVC_WAVE;
+constexpr int kKeysPerWg = 64 * kWaves;  // pass B: keys held by one workgroup
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kNegBig = -1.0e30f;  // finite "no key seen yet": exp2(m_old - m_new) never sees inf - inf
 
 template <bool BF16, int D>
 struct Cfg {
   static constexpr int kRowBytes = D * (BF16 ? 2 : 4);
-  static constexpr int kSteps = kRowBytes / 32;        // 16-byte fragments per lane and row
-  static constexpr int kLdsStride = kRowBytes + 16;    // pad: 16 consecutive rows hit 64 banks
-  static constexpr int kTile = BF16 ? 64 : 32;         // streamed rows per LDS buffer
-  static constexpr int kTileSub = kTile / 32;
+  static constexpr int kSteps = kRowBytes / 32;      // 16-byte fragments per lane and row
   static constexpr int kChunksPerRow = kRowBytes / 16;
-  static constexpr int kStage = kTile * kChunksPerRow / kThreads;  // 16-byte chunks per thread
-  static constexpr int kLdsBytes = kTile * kLdsStride;
-  static_assert(kTile * kChunksPerRow % kThreads == 0, "tile must split evenly over the threads");
+  static constexpr int kTile = BF16 ? 64 : 32;       // streamed rows per LDS buffer
+  static constexpr int kTileSub = kTile / 32;
+  static constexpr int kTileBytes = kTile * kRowBytes;
+  static constexpr int kSubBytes = 32 * kRowBytes;
+  static constexpr int kLoadsPerWave = kTileBytes / 1024 / kWaves;  // 1 KiB per wave instruction
+  static constexpr bool kPipelined = BF16;           // hand-pipelined loop needs two sub-tiles a tile
+  static_assert(kTileBytes % (1024 * kWaves) == 0, "tile must split evenly over the waves");
 };
 
 // One MFMA "load step": C += A_frag . B_frag^T over this step's k-slice.
@@ -67,31 +82,59 @@ __device__ __forceinline__ int acc_row(int r, int lane) {
   return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
 }
 
+// Byte offset, inside a tile buffer, of 16-byte chunk `cidx` of row `row`.
 template <class C>
-__device__ __forceinline__ void stage_load(u32x4 (&st)[C::kStage], const char* head_base, int row0,
-                                           int S, int tid) {
-#pragma unroll
-  for (int i = 0; i < C::kStage; ++i) {
-    const int c = tid + kThreads * i;
-    const int row = c / C::kChunksPerRow, col = c % C::kChunksPerRow;
-    const int t = row0 + row;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (t < S) v = *(const u32x4*)(head_base + (size_t)t * C::kRowBytes + col * 16);
-    st[i] = v;
-  }
+__device__ __forceinline__ int lds_chunk_offset(int row, int cidx) {
+  const int q = row * C::kChunksPerRow + cidx;
+  const int line = q >> 4, pos = q & 15;
+  return (line << 8) | ((pos ^ (line & 15)) << 4);
+}
+
+// Offset of this lane's step-0 fragment of sub-tile 0; step s is at (off0 ^ (s << 4)),
+// sub-tile u adds u * kSubBytes (neither changes the swizzle bits).
+template <class C>
+__device__ __forceinline__ int lds_frag_offset0(int lane) {
+  return lds_chunk_offset<C>(lane & 31, (lane >> 5) * C::kSteps);
 }
 
 template <class C>
-__device__ __forceinline__ void stage_store(const u32x4 (&st)[C::kStage], char* buf, int tid) {
+__device__ __forceinline__ u32x4 lds_frag(const char* buf, int off0, int sub, int step) {
+  return *(const u32x4*)(buf + sub * C::kSubBytes + (off0 ^ (step << 4)));
+}
+
+// Asynchronous copy of tile rows [row0, row0 + kTile) of one head into an LDS
+// buffer.  Rows past the end of the sequence are clamped to the last row (the
+// callers mask or ignore them).  Completion: s_waitcnt vmcnt(0), then a barrier.
+template <class C>
+__device__ __forceinline__ void tile_load_async(const char* head_base, int row0, int S, char* buf,
+                                                int wave, int lane) {
 #pragma unroll
-  for (int i = 0; i < C::kStage; ++i) {
-    const int c = tid + kThreads * i;
-    const int row = c / C::kChunksPerRow, col = c % C::kChunksPerRow;
-    *(u32x4*)(buf + row * C::kLdsStride + col * 16) = st[i];
+  for (int j = 0; j < C::kLoadsPerWave; ++j) {
+    const int inst = wave + kWaves * j;
+    const int p = inst * 64 + lane;  // physical chunk this lane fills
+    const int line = p >> 4, pos = (p & 15) ^ (line & 15);
+    const int q = line * 16 + pos;   // logical chunk
+    const int row = q / C::kChunksPerRow, cidx = q % C::kChunksPerRow;
+    const int t = min(row0 + row, S - 1);
+    const char* src = head_base + (size_t)t * C::kRowBytes + cidx * 16;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(buf + inst * 1024), 16, 0, 0);
   }
 }
 
-// Fragments of 32 stationary rows, straight from global memory to registers.
+__device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+#ifdef KVC_PROFILE
+__device__ unsigned long long kvc_prof[16];
+#define KVC_T(x) const unsigned long long x = __builtin_readcyclecounter()
+#define KVC_ACC(i, v) do { if (kvc::lane_id() == 0) atomicAdd(&kvc_prof[i], (unsigned long long)(v)); } while (0)
+#else
+#define KVC_T(x) do { } while (0)
+#define KVC_ACC(i, v) do { } while (0)
+#endif
+
+// Fragments of 32 stationary rows, straight from global memory to registers
+// (zero rows past the end of the sequence).
 template <class C>
 __device__ __forceinline__ void load_stationary(u32x4 (&frag)[C::kSteps], const char* head_base,
                                                 int row0, int S, int lane) {
@@ -99,14 +142,10 @@ __device__ __forceinline__ void load_stationary(u32x4 (&frag)[C::kSteps], const 
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
     u32x4 v = {0u, 0u, 0u, 0u};
-    if (t < S) v = *(const u32x4*)(head_base + (size_t)t * C::kRowBytes + s * 32 + (lane >> 5) * 16);
+    if (t < S)
+      v = *(const u32x4*)(head_base + (size_t)t * C::kRowBytes + (s + (lane >> 5) * C::kSteps) * 16);
     frag[s] = v;
   }
-}
-
-template <class C>
-__device__ __forceinline__ u32x4 lds_frag(const char* buf, int sub, int step, int lane) {
-  return *(const u32x4*)(buf + (sub * 32 + (lane & 31)) * C::kLdsStride + step * 32 + (lane >> 5) * 16);
 }
 
 struct ScoreParams {
@@ -125,9 +164,6 @@ struct ScoreParams {
   float scale_log2;  // log2(e) / sqrt(D)
 };
 
-constexpr int kKeysPerWg = 64 * kWaves;  // pass B: keys held by one workgroup
-
-template <class C>
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2]) {
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -135,17 +171,17 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2]) {
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
 }
 
-// Two 32x32 tiles of one step.  STREAM_IS_A: the LDS sub-tile supplies the rows
-// (keys) and the two register operands the columns (pass A); otherwise the two
-// register operands supply rows (keys) and the LDS sub-tile the columns (pass B).
+// Two 32x32 tiles of one block, fragments read from LDS on the spot (used off
+// the fast path).  STREAM_IS_A: the LDS sub-tile supplies the rows (keys) and
+// the two register operands the columns (pass A); otherwise the register
+// operands supply the rows (keys) and the LDS sub-tile the columns (pass B).
 template <class C, bool BF16, bool STREAM_IS_A>
-__device__ __forceinline__ void mma_pair(f32x16 (&acc)[2], const char* buf, int sub,
-                                         const u32x4 (&r0)[C::kSteps], const u32x4 (&r1)[C::kSteps],
-                                         int lane) {
-  zero_acc<C>(acc);
+__device__ __forceinline__ void mma_pair(f32x16 (&acc)[2], const char* buf, int off0, int sub,
+                                         const u32x4 (&r0)[C::kSteps], const u32x4 (&r1)[C::kSteps]) {
+  zero_acc(acc);
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
-    const u32x4 f = lds_frag<C>(buf, sub, s, lane);
+    const u32x4 f = lds_frag<C>(buf, off0, sub, s);
     if constexpr (STREAM_IS_A) {
       mma_step<BF16>(acc[0], f, r0[s]);
       mma_step<BF16>(acc[1], f, r1[s]);
@@ -157,21 +193,13 @@ __device__ __forceinline__ void mma_pair(f32x16 (&acc)[2], const char* buf, int 
 }
 
 // Online max / sum over the 16 key rows a lane holds of one tile (pass A).
-// `lim` >= 15 + 8 means no masking; otherwise rows with 8*(r/4)+(r%4) > lim are
-// keys after the query and are left out.
+// With MASK, rows with 8*(r/4)+(r%4) > lim are keys after the query: left out.
 template <bool MASK>
 __device__ __forceinline__ void softmax_update(f32x16& acc, float& m, float& l, float c, int lim) {
   if constexpr (MASK) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = (8 * (r >> 2) + (r & 3)) <= lim ? acc[r] : -INFINITY;
   }
-#ifdef KVC_EXP_NO_VALU
-  if constexpr (!MASK) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) l += acc[r];
-    return;
-  }
-#endif
   float mx = acc[0];
 #pragma unroll
   for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
@@ -187,13 +215,6 @@ __device__ __forceinline__ void softmax_update(f32x16& acc, float& m, float& l, 
 template <bool MASK>
 __device__ __forceinline__ void colsum_update(const f32x16& acc, f32x16& col, float c, float lse2,
                                               int lim) {
-#ifdef KVC_EXP_NO_VALU
-  if constexpr (!MASK) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) col[r] += acc[r];
-    return;
-  }
-#endif
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[r], c, -lse2));
@@ -204,22 +225,118 @@ __device__ __forceinline__ void colsum_update(const f32x16& acc, f32x16& col, fl
   }
 }
 
-// Finite stand-in for "no key seen yet": keeps exp2(m_old - m_new) free of inf - inf.
-constexpr float kNegBig = -1.0e30f;
+// sched_group_barrier classes: matrix ops, LDS reads, vector ALU incl. transcendentals
+constexpr int kSchedMfma = 0x008, kSchedDsRead = 0x100, kSchedValu = 0x002 | 0x400;
+
+// ---- hand-pipelined half steps (bf16, 8 fragments a block) -----------------
+// acc_new = block whose fragments sit in fr[]; after each MFMA pair the same
+// fragment slot is refilled from `next` (the block after it) and a slice of the
+// VALU work on acc_old (the block before it) is issued.
+
+// Fragment ring: kSteps / 2 slots.  Slot s % ring holds fragment s of the block
+// being multiplied; once used it is refilled with fragment s + ring of the same
+// block (first half of the steps) or fragment s - ring of the next block.
+template <class C>
+__device__ __forceinline__ void ring_refill(u32x4 (&fr)[C::kSteps / 2], int s, const char* cur,
+                                            const char* next, int off0) {
+  constexpr int kRing = C::kSteps / 2;
+  if (s < kRing)
+    fr[s] = *(const u32x4*)(cur + (off0 ^ ((s + kRing) << 4)));
+  else
+    fr[s - kRing] = *(const u32x4*)(next + (off0 ^ ((s - kRing) << 4)));
+}
+
+// pass B slice: 32 / kSteps of the 32 elements of acc_old per MFMA pair.
+template <class C>
+__device__ __forceinline__ void colsum_half(f32x16 (&acc_new)[2], const f32x16 (&acc_old)[2],
+                                            f32x16 (&col)[2], u32x4 (&fr)[C::kSteps / 2],
+                                            const u32x4 (&kf0)[C::kSteps], const u32x4 (&kf1)[C::kSteps],
+                                            const char* cur, const char* next, int off0, float c,
+                                            float lse_old) {
+  constexpr int kRing = C::kSteps / 2;
+  constexpr int kPer = 32 / C::kSteps;  // elements of acc_old handled per MFMA pair
+  zero_acc(acc_new);
+#pragma unroll
+  for (int s = 0; s < C::kSteps; ++s) {
+    mma_step<true>(acc_new[0], kf0[s], fr[s % kRing]);
+    mma_step<true>(acc_new[1], kf1[s], fr[s % kRing]);
+    ring_refill<C>(fr, s, cur, next, off0);
+#pragma unroll
+    for (int e = s * kPer; e < (s + 1) * kPer; ++e) {
+      const int t = e >> 4, r = e & 15;
+      col[t][r] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc_old[t][r], c, -lse_old));
+    }
+  }
+  // issue order for the machine scheduler: per MFMA pair, its refill read and a
+  // slice of the exp work (fma, exp, add per element plus the read's address)
+#pragma unroll
+  for (int s = 0; s < C::kSteps; ++s) {
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer + 3, 0);
+  }
+}
+
+// pass A slice: the two tile maxima first, then the 32 exponentials spread over
+// the remaining MFMA pairs.
+template <class C>
+__device__ __forceinline__ void lse_half(f32x16 (&acc_new)[2], const f32x16 (&acc_old)[2], float (&m)[2],
+                                         float (&l)[2], u32x4 (&fr)[C::kSteps / 2],
+                                         const u32x4 (&qf0)[C::kSteps], const u32x4 (&qf1)[C::kSteps],
+                                         const char* cur, const char* next, int off0, float c) {
+  constexpr int kRing = C::kSteps / 2;
+  zero_acc(acc_new);
+  float mnew[2], sum[2] = {0.0f, 0.0f};
+#pragma unroll
+  for (int s = 0; s < C::kSteps; ++s) {
+    mma_step<true>(acc_new[0], fr[s % kRing], qf0[s]);
+    mma_step<true>(acc_new[1], fr[s % kRing], qf1[s]);
+    ring_refill<C>(fr, s, cur, next, off0);
+    if (s == 0) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        float mx = acc_old[t][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc_old[t][r]);
+        mnew[t] = fmaxf(m[t], mx * c);
+      }
+    } else {
+      constexpr int kSlices = C::kSteps - 1;
+      const int e0 = (s - 1) * 32 / kSlices, e1 = s * 32 / kSlices;
+#pragma unroll
+      for (int e = e0; e < e1; ++e) {
+        const int t = e >> 4, r = e & 15;
+        sum[t] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc_old[t][r], c, -mnew[t]));
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    l[t] = l[t] * __builtin_amdgcn_exp2f(m[t] - mnew[t]) + sum[t];
+    m[t] = mnew[t];
+  }
+  // issue order for the machine scheduler: per MFMA pair, its refill read and an
+  // even share of the ~130 VALU instructions of the block
+#pragma unroll
+  for (int s = 0; s < C::kSteps; ++s) {
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 136 / C::kSteps, 0);
+  }
+}
 
 // ------------------------------------------------------------- pass A ------
 // Workgroup = 4 waves sharing one stream of K tiles.  Each wave keeps 64 query
 // rows of one head in registers (two 32-row sub-tiles).  With grouped-query
 // attention the waves take different heads of the same KV group (same query
 // range); otherwise they take consecutive 64-row query blocks of one head.
-// K tiles wholly before the workgroup's first query need no mask: they run in a
-// software-pipelined loop where the MFMAs of the next sub-tile are issued
-// together with the max/exp/sum work on the previous one.  The few tiles that
-// touch the diagonal go through a plain masked loop afterwards.
+// K tiles wholly before the workgroup's first query need no mask and run in the
+// pipelined loop; the few tiles that touch the diagonal go through a plain
+// masked loop afterwards.
 template <bool BF16, int D>
 __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   using C = Cfg<BF16, D>;
-  __shared__ __attribute__((aligned(16))) char lds[2][C::kLdsBytes];
+  __shared__ __attribute__((aligned(1024))) char lds[3][C::kTileBytes];
 
   const int tid = threadIdx.x, lane = kvc::lane_id(), wave = tid / KVC_WAVE;
   const int S = p.S;
@@ -243,52 +360,70 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
 
   const int wg_qmax = min(S, wg_q0 + 64 * qsub) - 1;
   const int n_tiles = wg_qmax / C::kTile + 1;
-  const int n_full = wg_q0 / C::kTile;  // tiles whose keys all precede every query of the workgroup
+  // tiles whose keys all precede every query of the workgroup
+  const int n_full = C::kPipelined ? wg_q0 / C::kTile : 0;
+  const int off0 = lds_frag_offset0<C>(lane);
 
   float m[2] = {kNegBig, kNegBig}, l[2] = {0.0f, 0.0f};
   const float c = p.scale_log2;
-  u32x4 st[C::kStage];
 
-  if (n_full > 0) {
-    stage_load<C>(st, kh, 0, S, tid);
-    stage_store<C>(st, lds[0], tid);
-    __syncthreads();
-    f32x16 acc_a[2], acc_b[2];
-    mma_pair<C, BF16, true>(acc_a, lds[0], 0, qf[0], qf[1], lane);
-    for (int it = 0; it < n_full; ++it) {
-      const bool has_next = it + 1 < n_full;
-      if (has_next) stage_load<C>(st, kh, (it + 1) * C::kTile, S, tid);
+  if constexpr (C::kPipelined) {
+    if (n_full > 0) {
+      tile_load_async<C>(kh, 0, S, lds[0], wave, lane);
+      if (n_full > 1) tile_load_async<C>(kh, C::kTile, S, lds[1], wave, lane);
+      wait_async_loads();
+      __syncthreads();
+      // tile t lives in lds[t % 3]: while iteration `it` multiplies tiles it and
+      // it + 1, tile it + 2 lands in the buffer tile it - 1 has left.
+      f32x16 acc0[2], acc1[2];
+      u32x4 fr[C::kSteps / 2];
+      mma_pair<C, BF16, true>(acc0, lds[0], off0, 0, qf[0], qf[1]);
 #pragma unroll
-      for (int ks = 0; ks < C::kTileSub; ++ks) {
-        if (ks + 1 < C::kTileSub) {
-          mma_pair<C, BF16, true>(acc_b, lds[it & 1], ks + 1, qf[0], qf[1], lane);
-        } else {
-          if (has_next) stage_store<C>(st, lds[(it + 1) & 1], tid);
-          __syncthreads();
-          if (has_next) mma_pair<C, BF16, true>(acc_b, lds[(it + 1) & 1], 0, qf[0], qf[1], lane);
-        }
-        softmax_update<false>(acc_a[0], m[0], l[0], c, 0);
-        softmax_update<false>(acc_a[1], m[1], l[1], c, 0);
-        acc_a[0] = acc_b[0];
-        acc_a[1] = acc_b[1];
+      for (int s = 0; s < C::kSteps / 2; ++s) fr[s] = lds_frag<C>(lds[0], off0, 1, s);
+#ifdef KVC_PROFILE
+      unsigned long long pw = 0, pb = 0;
+      KVC_T(t_begin);
+#endif
+      for (int it = 0; it < n_full; ++it) {
+        if (it + 2 < n_full) tile_load_async<C>(kh, (it + 2) * C::kTile, S, lds[(it + 2) % 3], wave, lane);
+        const char* cur = lds[it % 3];
+        const char* nxt = lds[(it + 1) % 3];
+        lse_half<C>(acc1, acc0, m, l, fr, qf[0], qf[1], cur + C::kSubBytes, nxt, off0, c);
+        lse_half<C>(acc0, acc1, m, l, fr, qf[0], qf[1], nxt, nxt + C::kSubBytes, off0, c);
+        KVC_T(ta);
+        wait_async_loads();
+        KVC_T(tb);
+        __syncthreads();
+#ifdef KVC_PROFILE
+        KVC_T(tc);
+        pw += tb - ta;
+        pb += tc - tb;
+#endif
       }
+#ifdef KVC_PROFILE
+      KVC_T(t_end);
+      KVC_ACC(0, t_end - t_begin);
+      KVC_ACC(1, pw);
+      KVC_ACC(2, pb);
+      KVC_ACC(3, n_full);
+#endif
     }
   }
 
   if (n_tiles > n_full) {
-    stage_load<C>(st, kh, n_full * C::kTile, S, tid);
-    stage_store<C>(st, lds[0], tid);
+    tile_load_async<C>(kh, n_full * C::kTile, S, lds[0], wave, lane);
+    wait_async_loads();
     __syncthreads();
     for (int it = n_full; it < n_tiles; ++it) {
       const int kt = it * C::kTile;
       const char* buf = lds[(it - n_full) & 1];
-      if (it + 1 < n_tiles) stage_load<C>(st, kh, kt + C::kTile, S, tid);
+      if (it + 1 < n_tiles) tile_load_async<C>(kh, kt + C::kTile, S, lds[(it - n_full + 1) & 1], wave, lane);
 #pragma unroll
       for (int ks = 0; ks < C::kTileSub; ++ks) {
         const int kmin = kt + 32 * ks, kmax = kmin + 31;
         if (kmin > q0 + 63) continue;  // every key of this sub-tile comes after all 64 rows
         f32x16 acc[2];
-        mma_pair<C, BF16, true>(acc, buf, ks, qf[0], qf[1], lane);
+        mma_pair<C, BF16, true>(acc, buf, off0, ks, qf[0], qf[1]);
 #pragma unroll
         for (int ns = 0; ns < 2; ++ns) {
           const int qmin = q0 + 32 * ns;
@@ -301,7 +436,7 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
           }
         }
       }
-      if (it + 1 < n_tiles) stage_store<C>(st, lds[(it - n_full + 1) & 1], tid);
+      wait_async_loads();
       __syncthreads();
     }
   }
@@ -333,8 +468,8 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
 template <bool BF16, int D>
 __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, const float* lse_in) {
   using C = Cfg<BF16, D>;
-  __shared__ __attribute__((aligned(16))) char lds[2][C::kLdsBytes];
-  __shared__ float lds_lse[2][C::kTile];
+  __shared__ __attribute__((aligned(1024))) char lds[3][C::kTileBytes];
+  __shared__ float lds_lse[3][kThreads];  // first kTile entries of a row are used
 
   const int tid = threadIdx.x, lane = kvc::lane_id(), wave = tid / KVC_WAVE;
   const int S = p.S;
@@ -371,70 +506,73 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
 
   // tiles of this piece: [t_first, t_last]; those below f_first touch the diagonal
   const int t_first = max(chunk * p.chunk_tiles, kb * kTpk);
-  const int f_first = max(t_first, kb * kTpk + kTpk);
+  const int f_first = C::kPipelined ? max(t_first, kb * kTpk + kTpk) : t_last + 1;
   const int n_fullt = max(0, t_last - f_first + 1);
-  const int d_last = min(t_last, kb * kTpk + kTpk - 1);
+  const int d_last = t_last - n_fullt;
   const int n_diagt = max(0, d_last - t_first + 1);
   const float c = p.scale_log2;
+  const int off0 = lds_frag_offset0<C>(lane);
 
   f32x16 col[2];
-  zero_acc<C>(col);
+  zero_acc(col);
 
   auto q_head = [&](int head) { return p.q + ((size_t)b * p.Hq + head) * S * C::kRowBytes; };
   auto load_lse = [&](int head, int qt) -> float {
-    // +inf for rows past the end makes their probabilities exactly zero
-    float v = INFINITY;
-    if (tid < C::kTile && qt + tid < S) v = lse_in[((size_t)b * p.Hq + head) * S + qt + tid] * kLog2e;
-    return v;
+    // +inf for rows past the end makes their probabilities exactly zero.  Branch
+    // free (clamped address, select) so that the caller's loop body stays one
+    // straight block; threads beyond the tile re-read its rows and are ignored.
+    const int i = qt + (tid & (C::kTile - 1));
+    const float v = lse_in[((size_t)b * p.Hq + head) * S + min(i, S - 1)] * kLog2e;
+    return i < S ? v : INFINITY;
   };
-  u32x4 st[C::kStage];
-  float st_lse;
 
-  // ---- tiles after the diagonal: no mask, software pipelined
-  const int n_fast = n_heads * n_fullt;
-  if (n_fast > 0) {
-    auto tile_of = [&](int it, int& head, int& qt) {
-      head = head0 + it / n_fullt;
-      qt = (t_last - it % n_fullt) * C::kTile;
-    };
-    int head, qt;
-    tile_of(0, head, qt);
-    stage_load<C>(st, q_head(head), qt, S, tid);
-    st_lse = load_lse(head, qt);
-    stage_store<C>(st, lds[0], tid);
-    if (tid < C::kTile) lds_lse[0][tid] = st_lse;
-    __syncthreads();
-    f32x16 acc_a[2], acc_b[2];
-    mma_pair<C, BF16, false>(acc_a, lds[0], 0, kf[0], kf[1], lane);
-    for (int it = 0; it < n_fast; ++it) {
-      const bool has_next = it + 1 < n_fast;
-      if (has_next) {
-        tile_of(it + 1, head, qt);
-        stage_load<C>(st, q_head(head), qt, S, tid);
-        st_lse = load_lse(head, qt);
+  // ---- tiles after the diagonal: no mask, hand-pipelined
+  if constexpr (C::kPipelined) {
+    const int n_fast = n_heads * n_fullt;
+    if (n_fast > 0) {
+      auto tile_of = [&](int it, int& head, int& qt) {
+        head = head0 + it / n_fullt;
+        qt = (t_last - it % n_fullt) * C::kTile;
+      };
+      int head, qt;
+      tile_of(0, head, qt);
+      tile_load_async<C>(q_head(head), qt, S, lds[0], wave, lane);
+      lds_lse[0][tid] = load_lse(head, qt);
+      if (n_fast > 1) {
+        tile_of(1, head, qt);
+        tile_load_async<C>(q_head(head), qt, S, lds[1], wave, lane);
+        lds_lse[1][tid] = load_lse(head, qt);
       }
+      wait_async_loads();
+      __syncthreads();
+      // tile t (and its lse) lives in buffer t % 3, as in pass A
+      f32x16 acc0[2], acc1[2];
+      u32x4 fr[C::kSteps / 2];
+      mma_pair<C, BF16, false>(acc0, lds[0], off0, 0, kf[0], kf[1]);
 #pragma unroll
-      for (int ns = 0; ns < C::kTileSub; ++ns) {
-        const float lse2 = lds_lse[it & 1][32 * ns + (lane & 31)];  // read before the barrier below
-        if (ns + 1 < C::kTileSub) {
-          mma_pair<C, BF16, false>(acc_b, lds[it & 1], ns + 1, kf[0], kf[1], lane);
-        } else {
-          if (has_next) {
-            stage_store<C>(st, lds[(it + 1) & 1], tid);
-            if (tid < C::kTile) lds_lse[(it + 1) & 1][tid] = st_lse;
-          }
-          __syncthreads();
-          if (has_next) mma_pair<C, BF16, false>(acc_b, lds[(it + 1) & 1], 0, kf[0], kf[1], lane);
+      for (int s = 0; s < C::kSteps / 2; ++s) fr[s] = lds_frag<C>(lds[0], off0, 1, s);
+      for (int it = 0; it < n_fast; ++it) {
+        float st_lse = INFINITY;
+        if (it + 2 < n_fast) {
+          tile_of(it + 2, head, qt);
+          tile_load_async<C>(q_head(head), qt, S, lds[(it + 2) % 3], wave, lane);
+          st_lse = load_lse(head, qt);
         }
-        colsum_update<false>(acc_a[0], col[0], c, lse2, 0);
-        colsum_update<false>(acc_a[1], col[1], c, lse2, 0);
-        acc_a[0] = acc_b[0];
-        acc_a[1] = acc_b[1];
+        const float* lv = lds_lse[it % 3];
+        const float lse_a = lv[lane & 31], lse_b = lv[32 + (lane & 31)];
+        __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);  // the two lse reads lead the block
+        const char* cur = lds[it % 3];
+        const char* nxt = lds[(it + 1) % 3];
+        colsum_half<C>(acc1, acc0, col, fr, kf[0], kf[1], cur + C::kSubBytes, nxt, off0, c, lse_a);
+        colsum_half<C>(acc0, acc1, col, fr, kf[0], kf[1], nxt, nxt + C::kSubBytes, off0, c, lse_b);
+        lds_lse[(it + 2) % 3][tid] = st_lse;  // unconditional: keeps the block free of exec changes
+        wait_async_loads();
+        __syncthreads();
       }
     }
   }
 
-  // ---- tiles on the diagonal: masked, plain loop
+  // ---- tiles on the diagonal (and every tile of the fp32 path): masked, plain loop
   const int n_slow = n_heads * n_diagt;
   if (n_slow > 0) {
     auto tile_of = [&](int it, int& head, int& qt) {
@@ -443,18 +581,18 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
     };
     int head, qt;
     tile_of(0, head, qt);
-    stage_load<C>(st, q_head(head), qt, S, tid);
-    st_lse = load_lse(head, qt);
-    stage_store<C>(st, lds[0], tid);
-    if (tid < C::kTile) lds_lse[0][tid] = st_lse;
+    tile_load_async<C>(q_head(head), qt, S, lds[0], wave, lane);
+    lds_lse[0][tid] = load_lse(head, qt);
+    wait_async_loads();
     __syncthreads();
     for (int it = 0; it < n_slow; ++it) {
       tile_of(it, head, qt);
       const int qt_cur = qt;
       const char* buf = lds[it & 1];
+      float st_lse = 0.0f;
       if (it + 1 < n_slow) {
         tile_of(it + 1, head, qt);
-        stage_load<C>(st, q_head(head), qt, S, tid);
+        tile_load_async<C>(q_head(head), qt, S, lds[(it + 1) & 1], wave, lane);
         st_lse = load_lse(head, qt);
       }
 #pragma unroll
@@ -463,7 +601,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
         if (qmax < k0) continue;  // all 64 keys of this wave come after these queries
         const float lse2 = lds_lse[it & 1][32 * ns + (lane & 31)];
         f32x16 acc[2];
-        mma_pair<C, BF16, false>(acc, buf, ns, kf[0], kf[1], lane);
+        mma_pair<C, BF16, false>(acc, buf, off0, ns, kf[0], kf[1]);
 #pragma unroll
         for (int ms = 0; ms < 2; ++ms) {
           const int kmin = k0 + 32 * ms;
@@ -476,10 +614,8 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
           }
         }
       }
-      if (it + 1 < n_slow) {
-        stage_store<C>(st, lds[(it + 1) & 1], tid);
-        if (tid < C::kTile) lds_lse[(it + 1) & 1][tid] = st_lse;
-      }
+      if (it + 1 < n_slow) lds_lse[(it + 1) & 1][tid] = st_lse;
+      wait_async_loads();
       __syncthreads();
     }
   }
@@ -600,15 +736,6 @@ bool shape_ok(const kvcrush_shape* s) {
   return true;
 }
 
-}  // namespace
-
-extern "C" size_t kvcrush_scores_workspace(const kvcrush_shape* shape) {
-  if (!shape_ok(shape)) return 0;
-  return lse_bytes(shape) + partial_bytes(shape);
-}
-
-namespace {
-
 kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const void* k,
                             const float* lse, float* lse_out, float* partial, float* scores,
                             bool lse_only, hipStream_t stream) {
@@ -640,6 +767,11 @@ kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const voi
 }
 
 }  // namespace
+
+extern "C" size_t kvcrush_scores_workspace(const kvcrush_shape* shape) {
+  if (!shape_ok(shape)) return 0;
+  return lse_bytes(shape) + partial_bytes(shape);
+}
 
 extern "C" kvcrush_status kvcrush_scores(const kvcrush_shape* shape, const void* q, const void* k,
                                          const float* lse, float* scores, void* workspace,
@@ -678,3 +810,14 @@ extern "C" const char* kvcrush_status_string(kvcrush_status status) {
 }
 
 extern "C" int32_t kvcrush_version(void) { return 100; }
+
+#ifdef KVC_PROFILE
+extern "C" int kvcrush_debug_prof(unsigned long long* out16, int reset) {
+  if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(kvc_prof), sizeof(unsigned long long) * 16) != hipSuccess) return 1;
+  if (reset) {
+    unsigned long long z[16] = {0};
+    if (hipMemcpyToSymbol(HIP_SYMBOL(kvc_prof), z, sizeof(z)) != hipSuccess) return 1;
+  }
+  return 0;
+}
+#endif
