@@ -102,36 +102,44 @@ __device__ __forceinline__ u32x4 lds_frag(const char* buf, int off0, int sub, in
   return *(const u32x4*)(buf + sub * C::kSubBytes + (off0 ^ (step << 4)));
 }
 
-// Asynchronous copy of tile rows [row0, row0 + kTile) of one head into an LDS
-// buffer.  Rows past the end of the sequence are clamped to the last row (the
-// callers mask or ignore them).  Completion: s_waitcnt vmcnt(0), then a barrier.
+// Per-lane byte offsets, relative to a tile's first row, of the 16-byte chunks
+// this lane copies (one per wave instruction; see tile_load_async).
 template <class C>
-__device__ __forceinline__ void tile_load_async(const char* head_base, int row0, int S, char* buf,
-                                                int wave, int lane) {
+__device__ __forceinline__ void tile_lane_offsets(uint32_t (&rel)[C::kLoadsPerWave], int wave, int lane) {
 #pragma unroll
   for (int j = 0; j < C::kLoadsPerWave; ++j) {
     const int inst = wave + kWaves * j;
     const int p = inst * 64 + lane;  // physical chunk this lane fills
     const int line = p >> 4, pos = (p & 15) ^ (line & 15);
     const int q = line * 16 + pos;   // logical chunk
-    const int row = q / C::kChunksPerRow, cidx = q % C::kChunksPerRow;
-    const int t = min(row0 + row, S - 1);
-    const char* src = head_base + (size_t)t * C::kRowBytes + cidx * 16;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)(buf + inst * 1024), 16, 0, 0);
+    rel[j] = (uint32_t)((q / C::kChunksPerRow) * C::kRowBytes + (q % C::kChunksPerRow) * 16);
+  }
+}
+
+// Asynchronous copy of tile rows [row0, row0 + kTile) of one head into an LDS
+// buffer: uniform tile address + per-lane offset, no vector address arithmetic.
+// Rows past the end of the sequence are clamped to the last row (the callers
+// mask or ignore them).  Completion: s_waitcnt vmcnt(0), then a barrier.
+template <class C>
+__device__ __forceinline__ void tile_load_async(const char* head_base, int row0, int S, char* buf,
+                                                const uint32_t (&rel)[C::kLoadsPerWave], int wave) {
+  const char* tile = head_base + (size_t)row0 * C::kRowBytes;
+  const int valid = S - row0;  // rows of this tile inside the sequence
+#pragma unroll
+  for (int j = 0; j < C::kLoadsPerWave; ++j) {
+    uint32_t off = rel[j];
+    if (valid < C::kTile) {  // ragged last tile (uniform branch)
+      const uint32_t row = off / C::kRowBytes, in_row = off % C::kRowBytes;
+      off = min(row, (uint32_t)(valid - 1)) * C::kRowBytes + in_row;
+    }
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile + off),
+                                     (__attribute__((address_space(3))) void*)(buf + (wave + kWaves * j) * 1024),
+                                     16, 0, 0);
   }
 }
 
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-#ifdef KVC_PROFILE
-__device__ unsigned long long kvc_prof[16];
-#define KVC_T(x) const unsigned long long x = __builtin_readcyclecounter()
-#define KVC_ACC(i, v) do { if (kvc::lane_id() == 0) atomicAdd(&kvc_prof[i], (unsigned long long)(v)); } while (0)
-#else
-#define KVC_T(x) do { } while (0)
-#define KVC_ACC(i, v) do { } while (0)
-#endif
 
 // Fragments of 32 stationary rows, straight from global memory to registers
 // (zero rows past the end of the sequence).
@@ -236,22 +244,25 @@ constexpr int kSchedMfma = 0x008, kSchedDsRead = 0x100, kSchedValu = 0x002 | 0x4
 // Fragment ring: kSteps / 2 slots.  Slot s % ring holds fragment s of the block
 // being multiplied; once used it is refilled with fragment s + ring of the same
 // block (first half of the steps) or fragment s - ring of the next block.
-template <class C>
-__device__ __forceinline__ void ring_refill(u32x4 (&fr)[C::kSteps / 2], int s, const char* cur,
-                                            const char* next, int off0) {
+// CUR / NEXT are compile-time byte offsets of those blocks from the LDS base and
+// fo[s] the lane's offset of fragment s inside a block, so that every read is
+// "register + immediate" and costs no address arithmetic.
+template <class C, int CUR, int NEXT>
+__device__ __forceinline__ void ring_refill(u32x4 (&fr)[C::kSteps / 2], int s, const char* lds_base,
+                                            const int (&fo)[C::kSteps]) {
   constexpr int kRing = C::kSteps / 2;
   if (s < kRing)
-    fr[s] = *(const u32x4*)(cur + (off0 ^ ((s + kRing) << 4)));
+    fr[s] = *(const u32x4*)(lds_base + CUR + fo[s + kRing]);
   else
-    fr[s - kRing] = *(const u32x4*)(next + (off0 ^ ((s - kRing) << 4)));
+    fr[s - kRing] = *(const u32x4*)(lds_base + NEXT + fo[s - kRing]);
 }
 
 // pass B slice: 32 / kSteps of the 32 elements of acc_old per MFMA pair.
-template <class C>
+template <class C, int CUR, int NEXT>
 __device__ __forceinline__ void colsum_half(f32x16 (&acc_new)[2], const f32x16 (&acc_old)[2],
                                             f32x16 (&col)[2], u32x4 (&fr)[C::kSteps / 2],
                                             const u32x4 (&kf0)[C::kSteps], const u32x4 (&kf1)[C::kSteps],
-                                            const char* cur, const char* next, int off0, float c,
+                                            const char* lds_base, const int (&fo)[C::kSteps], float c,
                                             float lse_old) {
   constexpr int kRing = C::kSteps / 2;
   constexpr int kPer = 32 / C::kSteps;  // elements of acc_old handled per MFMA pair
@@ -260,7 +271,7 @@ __device__ __forceinline__ void colsum_half(f32x16 (&acc_new)[2], const f32x16 (
   for (int s = 0; s < C::kSteps; ++s) {
     mma_step<true>(acc_new[0], kf0[s], fr[s % kRing]);
     mma_step<true>(acc_new[1], kf1[s], fr[s % kRing]);
-    ring_refill<C>(fr, s, cur, next, off0);
+    ring_refill<C, CUR, NEXT>(fr, s, lds_base, fo);
 #pragma unroll
     for (int e = s * kPer; e < (s + 1) * kPer; ++e) {
       const int t = e >> 4, r = e & 15;
@@ -268,62 +279,66 @@ __device__ __forceinline__ void colsum_half(f32x16 (&acc_new)[2], const f32x16 (
     }
   }
   // issue order for the machine scheduler: per MFMA pair, its refill read and a
-  // slice of the exp work (fma, exp, add per element plus the read's address)
+  // slice of the exp work (fma, exp, add per element)
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
     __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
     __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer + 3, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer + 2, 0);
   }
 }
 
-// pass A slice: the two tile maxima first, then the 32 exponentials spread over
-// the remaining MFMA pairs.
-template <class C>
-__device__ __forceinline__ void lse_half(f32x16 (&acc_new)[2], const f32x16 (&acc_old)[2], float (&m)[2],
-                                         float (&l)[2], u32x4 (&fr)[C::kSteps / 2],
+// pass A slice: exponentials against the lane's fixed reference m (no running
+// maximum: fp32 has the range for any sum whose terms stay below 2^100 or so;
+// the caller checks the sums and re-bases m in the rare case they do not).
+template <class C, int CUR, int NEXT>
+__device__ __forceinline__ void lse_half(f32x16 (&acc_new)[2], const f32x16 (&acc_old)[2],
+                                         const float (&m)[2], float (&sum)[2], u32x4 (&fr)[C::kSteps / 2],
                                          const u32x4 (&qf0)[C::kSteps], const u32x4 (&qf1)[C::kSteps],
-                                         const char* cur, const char* next, int off0, float c) {
+                                         const char* lds_base, const int (&fo)[C::kSteps], float c) {
   constexpr int kRing = C::kSteps / 2;
+  constexpr int kPer = 32 / C::kSteps;
   zero_acc(acc_new);
-  float mnew[2], sum[2] = {0.0f, 0.0f};
+  sum[0] = sum[1] = 0.0f;
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
     mma_step<true>(acc_new[0], fr[s % kRing], qf0[s]);
     mma_step<true>(acc_new[1], fr[s % kRing], qf1[s]);
-    ring_refill<C>(fr, s, cur, next, off0);
-    if (s == 0) {
+    ring_refill<C, CUR, NEXT>(fr, s, lds_base, fo);
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        float mx = acc_old[t][0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc_old[t][r]);
-        mnew[t] = fmaxf(m[t], mx * c);
-      }
-    } else {
-      constexpr int kSlices = C::kSteps - 1;
-      const int e0 = (s - 1) * 32 / kSlices, e1 = s * 32 / kSlices;
-#pragma unroll
-      for (int e = e0; e < e1; ++e) {
-        const int t = e >> 4, r = e & 15;
-        sum[t] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc_old[t][r], c, -mnew[t]));
-      }
+    for (int e = s * kPer; e < (s + 1) * kPer; ++e) {
+      const int t = e >> 4, r = e & 15;
+      sum[t] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc_old[t][r], c, -m[t]));
     }
   }
-#pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    l[t] = l[t] * __builtin_amdgcn_exp2f(m[t] - mnew[t]) + sum[t];
-    m[t] = mnew[t];
-  }
-  // issue order for the machine scheduler: per MFMA pair, its refill read and an
-  // even share of the ~130 VALU instructions of the block
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
     __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
     __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(kSchedValu, 136 / C::kSteps, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer + 2, 0);
   }
 }
+
+// Adds a block's sums to the running (m, l) pair; re-bases on the block's own
+// maximum when a sum left the safe range (wave-uniform, rare).
+__device__ __forceinline__ void lse_commit(const f32x16 (&acc)[2], float (&m)[2], float (&l)[2],
+                                           const float (&sum)[2], float c) {
+  constexpr float kSafe = 1.0e30f;
+  const bool bad = !(l[0] + sum[0] < kSafe) || !(l[1] + sum[1] < kSafe);
+  if (__builtin_expect(__any(bad), 0)) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x16 a = acc[t];
+      softmax_update<false>(a, m[t], l[t], c, 0);
+    }
+  } else {
+    l[0] += sum[0];
+    l[1] += sum[1];
+  }
+}
+
+template <int N>
+struct IntC { static constexpr int value = N; };
 
 // ------------------------------------------------------------- pass A ------
 // Workgroup = 4 waves sharing one stream of K tiles.  Each wave keeps 64 query
@@ -363,61 +378,75 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   // tiles whose keys all precede every query of the workgroup
   const int n_full = C::kPipelined ? wg_q0 / C::kTile : 0;
   const int off0 = lds_frag_offset0<C>(lane);
+  uint32_t rel[C::kLoadsPerWave];
+  tile_lane_offsets<C>(rel, wave, lane);
 
   float m[2] = {kNegBig, kNegBig}, l[2] = {0.0f, 0.0f};
   const float c = p.scale_log2;
 
   if constexpr (C::kPipelined) {
     if (n_full > 0) {
-      tile_load_async<C>(kh, 0, S, lds[0], wave, lane);
-      if (n_full > 1) tile_load_async<C>(kh, C::kTile, S, lds[1], wave, lane);
+      tile_load_async<C>(kh, 0, S, lds[0], rel, wave);
+      tile_load_async<C>(kh, min(1, n_full - 1) * C::kTile, S, lds[1], rel, wave);
       wait_async_loads();
       __syncthreads();
       // tile t lives in lds[t % 3]: while iteration `it` multiplies tiles it and
-      // it + 1, tile it + 2 lands in the buffer tile it - 1 has left.
+      // it + 1, tile it + 2 lands in the buffer tile it - 1 has left.  The loop
+      // is unrolled three times so that every buffer address is an immediate.
+      const char* lds_base = &lds[0][0];
+      int fo[C::kSteps];
+#pragma unroll
+      for (int s = 0; s < C::kSteps; ++s) fo[s] = off0 ^ (s << 4);
       f32x16 acc0[2], acc1[2];
       u32x4 fr[C::kSteps / 2];
       mma_pair<C, BF16, true>(acc0, lds[0], off0, 0, qf[0], qf[1]);
 #pragma unroll
       for (int s = 0; s < C::kSteps / 2; ++s) fr[s] = lds_frag<C>(lds[0], off0, 1, s);
-#ifdef KVC_PROFILE
-      unsigned long long pw = 0, pb = 0;
-      KVC_T(t_begin);
-#endif
-      for (int it = 0; it < n_full; ++it) {
-        if (it + 2 < n_full) tile_load_async<C>(kh, (it + 2) * C::kTile, S, lds[(it + 2) % 3], wave, lane);
-        const char* cur = lds[it % 3];
-        const char* nxt = lds[(it + 1) % 3];
-        lse_half<C>(acc1, acc0, m, l, fr, qf[0], qf[1], cur + C::kSubBytes, nxt, off0, c);
-        lse_half<C>(acc0, acc1, m, l, fr, qf[0], qf[1], nxt, nxt + C::kSubBytes, off0, c);
-        KVC_T(ta);
-        wait_async_loads();
-        KVC_T(tb);
-        __syncthreads();
-#ifdef KVC_PROFILE
-        KVC_T(tc);
-        pw += tb - ta;
-        pb += tc - tb;
-#endif
+      // reference for the exponentials: the first block's own maximum
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        float mx = acc0[t][0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc0[t][r]);
+        m[t] = mx * c;
       }
-#ifdef KVC_PROFILE
-      KVC_T(t_end);
-      KVC_ACC(0, t_end - t_begin);
-      KVC_ACC(1, pw);
-      KVC_ACC(2, pb);
-      KVC_ACC(3, n_full);
-#endif
+      // The trip count is rounded up to a multiple of three; the padding
+      // iterations run on the last tile again with an infinite reference, so
+      // every exponential they produce is exactly zero.
+      auto body = [&](auto P, int it) {
+        constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
+        constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
+        tile_load_async<C>(kh, min(it + 2, n_full - 1) * C::kTile, S, lds[ld], rel, wave);
+        const bool live = it < n_full;
+        float sum[2], mref[2];
+        // block (it, sub 1) goes through the MFMAs while block (it, sub 0) is summed
+        mref[0] = live ? m[0] : INFINITY;
+        mref[1] = live ? m[1] : INFINITY;
+        lse_half<C, cur * kT + kU, nxt * kT>(acc1, acc0, mref, sum, fr, qf[0], qf[1], lds_base, fo, c);
+        lse_commit(acc0, m, l, sum, c);
+        mref[0] = live ? m[0] : INFINITY;
+        mref[1] = live ? m[1] : INFINITY;
+        lse_half<C, nxt * kT, nxt * kT + kU>(acc0, acc1, mref, sum, fr, qf[0], qf[1], lds_base, fo, c);
+        lse_commit(acc1, m, l, sum, c);
+        wait_async_loads();
+        __syncthreads();
+      };
+      for (int it = 0; it < n_full; it += 3) {
+        body(IntC<0>{}, it);
+        body(IntC<1>{}, it + 1);
+        body(IntC<2>{}, it + 2);
+      }
     }
   }
 
   if (n_tiles > n_full) {
-    tile_load_async<C>(kh, n_full * C::kTile, S, lds[0], wave, lane);
+    tile_load_async<C>(kh, n_full * C::kTile, S, lds[0], rel, wave);
     wait_async_loads();
     __syncthreads();
     for (int it = n_full; it < n_tiles; ++it) {
       const int kt = it * C::kTile;
       const char* buf = lds[(it - n_full) & 1];
-      if (it + 1 < n_tiles) tile_load_async<C>(kh, kt + C::kTile, S, lds[(it - n_full + 1) & 1], wave, lane);
+      if (it + 1 < n_tiles) tile_load_async<C>(kh, kt + C::kTile, S, lds[(it - n_full + 1) & 1], rel, wave);
 #pragma unroll
       for (int ks = 0; ks < C::kTileSub; ++ks) {
         const int kmin = kt + 32 * ks, kmax = kmin + 31;
@@ -512,6 +541,8 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   const int n_diagt = max(0, d_last - t_first + 1);
   const float c = p.scale_log2;
   const int off0 = lds_frag_offset0<C>(lane);
+  uint32_t rel[C::kLoadsPerWave];
+  tile_lane_offsets<C>(rel, wave, lane);
 
   f32x16 col[2];
   zero_acc(col);
@@ -536,38 +567,48 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       };
       int head, qt;
       tile_of(0, head, qt);
-      tile_load_async<C>(q_head(head), qt, S, lds[0], wave, lane);
+      tile_load_async<C>(q_head(head), qt, S, lds[0], rel, wave);
       lds_lse[0][tid] = load_lse(head, qt);
-      if (n_fast > 1) {
-        tile_of(1, head, qt);
-        tile_load_async<C>(q_head(head), qt, S, lds[1], wave, lane);
-        lds_lse[1][tid] = load_lse(head, qt);
+      tile_of(min(1, n_fast - 1), head, qt);
+      tile_load_async<C>(q_head(head), qt, S, lds[1], rel, wave);
+      {
+        const float v = load_lse(head, qt);
+        lds_lse[1][tid] = n_fast > 1 ? v : INFINITY;
       }
       wait_async_loads();
       __syncthreads();
       // tile t (and its lse) lives in buffer t % 3, as in pass A
+      const char* lds_base = &lds[0][0];
+      int fo[C::kSteps];
+#pragma unroll
+      for (int s = 0; s < C::kSteps; ++s) fo[s] = off0 ^ (s << 4);
       f32x16 acc0[2], acc1[2];
       u32x4 fr[C::kSteps / 2];
       mma_pair<C, BF16, false>(acc0, lds[0], off0, 0, kf[0], kf[1]);
 #pragma unroll
       for (int s = 0; s < C::kSteps / 2; ++s) fr[s] = lds_frag<C>(lds[0], off0, 1, s);
-      for (int it = 0; it < n_fast; ++it) {
-        float st_lse = INFINITY;
-        if (it + 2 < n_fast) {
-          tile_of(it + 2, head, qt);
-          tile_load_async<C>(q_head(head), qt, S, lds[(it + 2) % 3], wave, lane);
-          st_lse = load_lse(head, qt);
-        }
-        const float* lv = lds_lse[it % 3];
-        const float lse_a = lv[lane & 31], lse_b = lv[32 + (lane & 31)];
+      // The trip count is rounded up to a multiple of three; the padding
+      // iterations run on the last tile again with lse = +inf, so every
+      // probability they produce is exactly zero.
+      auto body = [&](auto P, int it) {
+        constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
+        constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
+        tile_of(min(it + 2, n_fast - 1), head, qt);
+        tile_load_async<C>(q_head(head), qt, S, lds[ld], rel, wave);
+        const float ld_lse = load_lse(head, qt);
+        const float st_lse = it + 2 < n_fast ? ld_lse : INFINITY;
+        const float lse_a = lds_lse[cur][lane & 31], lse_b = lds_lse[cur][32 + (lane & 31)];
         __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);  // the two lse reads lead the block
-        const char* cur = lds[it % 3];
-        const char* nxt = lds[(it + 1) % 3];
-        colsum_half<C>(acc1, acc0, col, fr, kf[0], kf[1], cur + C::kSubBytes, nxt, off0, c, lse_a);
-        colsum_half<C>(acc0, acc1, col, fr, kf[0], kf[1], nxt, nxt + C::kSubBytes, off0, c, lse_b);
-        lds_lse[(it + 2) % 3][tid] = st_lse;  // unconditional: keeps the block free of exec changes
+        colsum_half<C, cur * kT + kU, nxt * kT>(acc1, acc0, col, fr, kf[0], kf[1], lds_base, fo, c, lse_a);
+        colsum_half<C, nxt * kT, nxt * kT + kU>(acc0, acc1, col, fr, kf[0], kf[1], lds_base, fo, c, lse_b);
+        lds_lse[ld][tid] = st_lse;  // unconditional: keeps the block free of exec changes
         wait_async_loads();
         __syncthreads();
+      };
+      for (int it = 0; it < n_fast; it += 3) {
+        body(IntC<0>{}, it);
+        body(IntC<1>{}, it + 1);
+        body(IntC<2>{}, it + 2);
       }
     }
   }
@@ -581,7 +622,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
     };
     int head, qt;
     tile_of(0, head, qt);
-    tile_load_async<C>(q_head(head), qt, S, lds[0], wave, lane);
+    tile_load_async<C>(q_head(head), qt, S, lds[0], rel, wave);
     lds_lse[0][tid] = load_lse(head, qt);
     wait_async_loads();
     __syncthreads();
@@ -592,7 +633,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       float st_lse = 0.0f;
       if (it + 1 < n_slow) {
         tile_of(it + 1, head, qt);
-        tile_load_async<C>(q_head(head), qt, S, lds[(it + 1) & 1], wave, lane);
+        tile_load_async<C>(q_head(head), qt, S, lds[(it + 1) & 1], rel, wave);
         st_lse = load_lse(head, qt);
       }
 #pragma unroll
@@ -811,13 +852,3 @@ extern "C" const char* kvcrush_status_string(kvcrush_status status) {
 
 extern "C" int32_t kvcrush_version(void) { return 100; }
 
-#ifdef KVC_PROFILE
-extern "C" int kvcrush_debug_prof(unsigned long long* out16, int reset) {
-  if (hipMemcpyFromSymbol(out16, HIP_SYMBOL(kvc_prof), sizeof(unsigned long long) * 16) != hipSuccess) return 1;
-  if (reset) {
-    unsigned long long z[16] = {0};
-    if (hipMemcpyToSymbol(HIP_SYMBOL(kvc_prof), z, sizeof(z)) != hipSuccess) return 1;
-  }
-  return 0;
-}
-#endif
