@@ -716,7 +716,10 @@ ColsumPlan colsum_plan(int S, int tile, int chunk_tiles_wanted) {
   return pl;
 }
 
-constexpr int kChunkQueries = 1024;  // queries per pass-B work piece
+#ifndef KVC_CHUNK_QUERIES
+#define KVC_CHUNK_QUERIES 1024
+#endif
+constexpr int kChunkQueries = KVC_CHUNK_QUERIES;  // queries per pass-B work piece
 
 template <bool BF16, int D>
 kvcrush_status launch_lse(const ScoreParams& base, hipStream_t stream) {

@@ -168,11 +168,38 @@ def check_scores(kv, oracle, w, seed, reduce_groups, check_lse=True):
     (1, 1, 1, 1, 128, "bf16", False),
     (1, 2, 2, 31, 64, "bf16", False),
     (1, 8, 4, 1024, 128, "bf16", True),
+    (1, 4, 2, 2100, 64, "bf16", True),       # several query chunks, D = 64 pipeline
+    (1, 2, 2, 1333, 128, "bf16", False),     # several query chunks, ragged tail, one head per row
+    (2, 2, 1, 1100, 128, "f32", True),       # fp32 path with partial sums
 ])
 def test_scores_small(kv, oracle, B, Hq, Hkv, S, D, dtype, rg):
     say(f"scores B={B} Hq={Hq} Hkv={Hkv} S={S} D={D} {dtype} reduce_groups={rg}")
     w = inputs.Workload("t", B, Hq, Hkv, S, D, dtype, max(1, S // 4), 0.5, "alternating", rg, sink_bias=True)
     check_scores(kv, oracle, w, seed=S + Hq, reduce_groups=rg)
+
+
+def test_scores_extreme_logits(kv, oracle):
+    """Logits that grow by hundreds along the sequence: the exponentials' fixed
+    reference has to be re-based on the fly (and early keys underflow to zero)."""
+    say("scores with logits spanning several hundred")
+    S, D = 1500, 128
+    g = torch.Generator().manual_seed(77)
+    q = torch.randn(1, 2, S, D, generator=g)
+    k = torch.randn(1, 1, S, D, generator=g)
+    ramp = torch.linspace(0.01, 40.0, S)
+    ramp[700:] = ramp[700:].flip(0)                      # up, then down again
+    k = k * ramp[None, None, :, None]
+    q, k = q.to(torch.bfloat16), k.to(torch.bfloat16)
+    for rg in (True, False):
+        sc, _ = kv.kvcrush_scores(q.cuda(), k.cuda(), rg)
+        torch.cuda.synchronize()
+        ref = oracle.scores(q, k, rg, threads=THREADS)
+        assert torch.isfinite(sc).all()
+        # tokens that receive essentially nothing are compared absolutely
+        got, want = sc.cpu().double(), ref.double()
+        big = want > 1e-30
+        assert ((got[big] - want[big]).abs() / want[big]).max().item() <= SCORE_RTOL
+        assert got[~big].abs().max().item() <= 1e-30 if (~big).any() else True
 
 
 def test_scores_deterministic(kv):
