@@ -24,6 +24,15 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak, vendor figure
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak, vendor figure
 
+# HBM bytes per launch of the score kernels, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script (summary and commands: profiles/hbm_traffic_bench_cfg3.md; FETCH_SIZE scaled x2.0 and
+# WRITE_SIZE x1.0 by what the same counters read for a plain 256 MiB copy).  Counters cannot be read
+# from inside the timed run, so the figure is carried here; None for workloads not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg3_llama3_8b_gqa_s16384", "colsum_kernel"): (183640.2 * 2.0 + 4352.1) * 1024.0,
+    ("cfg3_llama3_8b_gqa_s16384", "lse_kernel"): (116913.4 * 2.0 + 2048.0) * 1024.0,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -33,6 +42,8 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="workload id 1..5 (default: the S=16384 GQA layer)")
     ap.add_argument("--layers", type=int, default=0, help="resident layers (0: the workload's own count, capped at 32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -136,6 +147,13 @@ def main():
         if ev:
             ev[4].record()
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)       # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -163,7 +181,7 @@ def main():
     peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 157.3
     roofline = {
         "bound": "mfma", "kernel": dom_name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-        "frac": achieved / peak, "traffic": None,
+        "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom_name)),
         "flop_per_launch": flop_pass, "avg_launch_ms": dom_ms,
     }
     stages = {
