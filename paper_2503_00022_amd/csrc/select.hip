@@ -3,20 +3,22 @@
 // bucket (Alg. 2, Sec. 3.2), merged ascending index list.
 //
 // All integer / compare work on at most a few MiB, so the stage is bound by
-// latency, not bandwidth: four short launches on one stream, no host round
+// latency, not bandwidth: five short launches on one stream, no host round
 // trip, no floating-point atomics (every tie is broken by token index, so the
 // result is a pure function of the score tensor).
 //
 //   K1 topk_mask_kernel   one workgroup per (sequence, score row) plus one for
-//                         the importance row: exact k-th largest by an 8-bit
-//                         MSB-first radix select over order-preserving integer
-//                         keys held in LDS, then a 64-tokens-per-word bitmap of
-//                         the selected set (ties: lowest index first).
-//   K2 group_sort_kernel  one workgroup per sequence: packs the row bitmaps
-//                         into per-token words, builds the anchor, Hamming
-//                         distance by xor+popcount, and a stable counting sort
-//                         of the non-important tokens by distance (wave ballots
-//                         give each token its rank among equal distances).
+//                         the importance row: exact k-th largest by an MSB-first
+//                         radix select (11 + 11 + 10 bits) over order-preserving
+//                         integer keys held in LDS, then a 64-tokens-per-word
+//                         bitmap of the selected set (ties: lowest index first).
+//   K2 group_rank_kernel /  many small workgroups per sequence: pack the row
+//      group_scatter_kernel bitmaps into per-token words, build the anchor,
+//                         Hamming distance by xor+popcount, and a stable
+//                         counting sort of the non-important tokens by distance
+//                         (wave ballots give each token its rank among equal
+//                         distances inside its wave; a small count table turns
+//                         that into global ranks).
 //   K3 medoid_kernel      one wavefront per bucket: per-head counts by ballot,
 //                         integer cost, wave arg-min with token tie-break.
 //   K4 emit_kernel        ordered compaction of (important | representative)
@@ -85,17 +87,38 @@ struct TopkParams {
   int Hs, S, nw, kbit, n_important;
 };
 
+// Block-wide exclusive prefix sum of one int per thread, in thread order.
+// `wave_tot` is LDS scratch of kSelWaves ints; contains two barriers.
+__device__ __forceinline__ int block_excl_scan(int v, int* wave_tot) {
+  const int lane = lane_id(), wave = threadIdx.x / KVC_WAVE;
+  const int incl = wave_incl_scan(v);
+  if (lane == KVC_WAVE - 1) wave_tot[wave] = incl;
+  __syncthreads();
+  int before = 0;
+  for (int w = 0; w < wave; ++w) before += wave_tot[w];
+  __syncthreads();
+  return before + incl - v;
+}
+
+constexpr int kRadixBins = 2048;  // 11 + 11 + 10 bits over three passes
+constexpr int kBatch = 8;         // independent loads in flight per thread
+
+// KEYS_IN_LDS: the row's keys live in the dynamic LDS buffer (the usual case);
+// otherwise in the workspace.  Two instantiations rather than one generic
+// pointer, so that the compiler knows LDS traffic cannot alias global traffic
+// and keeps batches of loads in flight.
+template <bool KEYS_IN_LDS>
 __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   extern __shared__ uint32_t lds_keys[];
-  __shared__ uint32_t hist[256];
+  __shared__ uint32_t hist[kRadixBins];
   __shared__ uint32_t sh_digit, sh_remaining, sh_count;
-  __shared__ int wave_eq[kSelWaves];
+  __shared__ int wave_tot[kSelWaves];
 
   const int row = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
   const int S = p.S, Hs = p.Hs, nw = p.nw;
   const int k = row < Hs ? p.kbit : p.n_important;
-  uint64_t* mask_out = p.rowmask + ((size_t)b * (Hs + 1) + row) * nw;
+  uint64_t* __restrict__ mask_out = p.rowmask + ((size_t)b * (Hs + 1) + row) * nw;
 
   if (k == 0 || k == S) {  // nothing or everything: no search needed
     for (int c = tid; c < nw; c += kSelThreads) {
@@ -109,69 +132,105 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
     return;
   }
 
-  uint32_t* keys = p.keys_ws ? p.keys_ws + ((size_t)b * (Hs + 1) + row) * S : lds_keys;
-  const float* sc = p.scores + (size_t)b * Hs * S;
-  if (row < Hs) {
-    for (int t = tid; t < S; t += kSelThreads) keys[t] = float_key(sc[(size_t)row * S + t]);
-  } else {
-    // token importance: fp32 sum of the score rows, taken in row order
-    for (int t = tid; t < S; t += kSelThreads) {
-      float acc = 0.0f;
-      for (int r = 0; r < Hs; ++r) acc = acc + sc[(size_t)r * S + t];
-      keys[t] = float_key(acc);
+  uint32_t* __restrict__ gkeys = KEYS_IN_LDS ? nullptr : p.keys_ws + ((size_t)b * (Hs + 1) + row) * S;
+  auto key_at = [&](int t) -> uint32_t { return KEYS_IN_LDS ? lds_keys[t] : gkeys[t]; };
+  auto key_put = [&](int t, uint32_t v) {
+    if (KEYS_IN_LDS) lds_keys[t] = v; else gkeys[t] = v;
+  };
+  const float* __restrict__ sc = p.scores + (size_t)b * Hs * S;
+
+  for (int i = tid; i < kRadixBins; i += kSelThreads) hist[i] = 0;
+  // keys: kBatch tokens per thread at a time so that their loads overlap
+  for (int t0 = tid; t0 < S; t0 += kBatch * kSelThreads) {
+    float v[kBatch];
+    if (row < Hs) {
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int t = t0 + u * kSelThreads;
+        v[u] = t < S ? sc[(size_t)row * S + t] : 0.0f;
+      }
+    } else {
+      // token importance: fp32 sum of the score rows, taken in row order
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) v[u] = 0.0f;
+      // eight rows' loads in flight at a time; the additions stay in row order
+      int r = 0;
+      for (; r + 8 <= Hs; r += 8) {
+        float x[8][kBatch];
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+          for (int u = 0; u < kBatch; ++u) {
+            const int t = t0 + u * kSelThreads;
+            x[rr][u] = t < S ? sc[(size_t)(r + rr) * S + t] : 0.0f;
+          }
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+          for (int u = 0; u < kBatch; ++u) v[u] = v[u] + x[rr][u];
+      }
+      for (; r < Hs; ++r) {
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const int t = t0 + u * kSelThreads;
+          const float x = t < S ? sc[(size_t)r * S + t] : 0.0f;
+          v[u] = v[u] + x;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+      const int t = t0 + u * kSelThreads;
+      if (t < S) key_put(t, float_key(v[u]));
     }
   }
   __syncthreads();
 
-  // MSB-first radix select of the k-th largest key, 8 bits a pass.
+  // MSB-first radix select of the k-th largest key: 11, 11 and 10 bits a pass.
+  // One LDS histogram shared by the workgroup; only keys that still match the
+  // prefix found so far are counted, so passes two and three are nearly free.
   uint32_t prefix = 0, known = 0, remaining = (uint32_t)k;
-  const int s_round = nw * 64;
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    for (int base = wave * 64; base < s_round; base += kSelThreads) {
-      const int t = base + lane;
-      const uint32_t key = t < S ? keys[t] : 0u;
-      bool valid = t < S && (key & known) == prefix;
-      const uint32_t digit = (key >> shift) & 255u;
-      // Score exponents cluster, so most lanes of a wave share one or two
-      // digits: count those by ballot, the rest by plain LDS atomics.
-      uint64_t todo = __ballot(valid);
-      for (int it = 0; it < 2 && todo; ++it) {
-        const int leader = __ffsll((unsigned long long)todo) - 1;
-        const uint32_t dl = __shfl(digit, leader);
-        const uint64_t m = __ballot(valid && digit == dl);
-        if (lane == leader) atomicAdd(&hist[dl], (uint32_t)__popcll(m));
-        todo &= ~m;
-        valid = valid && digit != dl;
+#pragma unroll
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+    const int bins = pass == 2 ? 1024 : 2048;
+    for (int t0 = tid; t0 < S; t0 += kBatch * kSelThreads) {
+      uint32_t kk[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int t = t0 + u * kSelThreads;
+        kk[u] = t < S ? key_at(t) : 0u;
       }
-      if (valid) atomicAdd(&hist[digit], 1u);
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const int t = t0 + u * kSelThreads;
+        if (t < S && (kk[u] & known) == prefix)
+          atomicAdd(&hist[(kk[u] >> shift) & (uint32_t)(bins - 1)], 1u);
+      }
     }
     __syncthreads();
-    if (wave == 0) {
-      // lane l owns bins 255-4l .. 252-4l; `above` = keys with a larger digit
-      uint32_t c[4];
-      int local = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        c[j] = hist[255 - 4 * lane - j];
-        local += (int)c[j];
+    // thread i owns bins (bins-1 - per*i) downwards; `above` = keys with a larger digit
+    const int per = bins / kSelThreads;  // 2, 2, 1
+    uint32_t c[2] = {0u, 0u};
+    int local = 0;
+    for (int j = 0; j < per; ++j) {
+      const int bin = bins - 1 - per * tid - j;
+      c[j] = hist[bin];
+      hist[bin] = 0;  // ready for the next pass
+      local += (int)c[j];
+    }
+    uint32_t above = (uint32_t)block_excl_scan(local, wave_tot);
+    for (int j = 0; j < per; ++j) {
+      if (above < remaining && remaining <= above + c[j]) {
+        sh_digit = (uint32_t)(bins - 1 - per * tid - j);
+        sh_remaining = remaining - above;
+        sh_count = c[j];
       }
-      uint32_t above = (uint32_t)(wave_incl_scan(local) - local);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (above < remaining && remaining <= above + c[j]) {
-          sh_digit = 255 - 4 * lane - j;
-          sh_remaining = remaining - above;
-          sh_count = c[j];
-        }
-        above += c[j];
-      }
+      above += c[j];
     }
     __syncthreads();
     prefix |= sh_digit << shift;
-    known |= 255u << shift;
+    known |= (uint32_t)(bins - 1) << shift;
     remaining = sh_remaining;
   }
   const uint32_t T = prefix;          // key of the k-th largest element
@@ -185,16 +244,16 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
     int mine = 0;
     for (int c = c0; c < c1; ++c) {
       const int t = c * 64 + lane;
-      mine += (t < S && keys[t] == T) ? 1 : 0;
+      mine += (t < S && key_at(t) == T) ? 1 : 0;
     }
     mine = wave_sum(mine);
-    if (lane == 0) wave_eq[wave] = mine;
+    if (lane == 0) wave_tot[wave] = mine;
     __syncthreads();
-    for (int w = 0; w < wave; ++w) eq_before += wave_eq[w];
+    for (int w = 0; w < wave; ++w) eq_before += wave_tot[w];
   }
   for (int c = c0; c < c1; ++c) {
     const int t = c * 64 + lane;
-    const uint32_t key = t < S ? keys[t] : 0u;
+    const uint32_t key = t < S ? key_at(t) : 0u;
     bool sel = t < S && key >= T;
     if (ties) {
       const bool eq = t < S && key == T;
@@ -209,14 +268,27 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 }
 
 // ------------------------------------------------------------------ K2 ----
+// The grouping of one sequence is spread over many small workgroups: the token
+// range is dealt out in contiguous runs of 64-token chunks to "global waves"
+// (workgroup x wave); K2a leaves, per token, its distance and its rank among
+// the same-distance tokens of its own wave, plus a (distance, global wave)
+// count table; K2b turns the table into start ranks and scatters.
+constexpr int kGsThreads = 256;
+constexpr int kGsWaves = kGsThreads / KVC_WAVE;
+constexpr int kGsChunksPerWg = 16;  // 1024 tokens a workgroup
+constexpr uint32_t kNotGrouped = 0xFFFFFFFFu;
+
 struct GroupParams {
   const uint64_t* rowmask;      // [B,Hs+1,nw]
   uint64_t* bits;               // [B,S,W]
+  uint32_t* dist_rank;          // [B,S]: distance | rank-in-wave << 8, or kNotGrouped
+  int32_t* counts;              // [B,Hs+1,n_gw] tokens per (distance, global wave)
   int32_t* order;               // [B,S]: first N entries = grouped tokens by (d,t)
-  uint64_t* repmask;            // [B,nw], zeroed here
+  uint64_t* repmask;            // [B,nw], zeroed by K2a
   const uint64_t* anchor_bits;  // [B,W] explicit anchor or null
   uint64_t anchor_seed;
   int Hs, S, nw, W, N, anchor_mode, dbits;
+  int n_gw;                     // global waves per sequence = workgroups x kGsWaves
 };
 
 __device__ __forceinline__ uint64_t splitmix64_next(uint64_t& state) {
@@ -227,30 +299,40 @@ __device__ __forceinline__ uint64_t splitmix64_next(uint64_t& state) {
   return z ^ (z >> 31);
 }
 
-__global__ __launch_bounds__(kSelThreads) void group_sort_kernel(GroupParams p) {
-  __shared__ int wcount[(kMaxHs + 1) * kSelWaves];  // [distance][wave]
+__global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
+  extern __shared__ uint64_t lds_words[];       // this workgroup's slice [Hs+1][kGsChunksPerWg]
+  __shared__ int run[kGsWaves][kMaxHs + 1];     // per wave: tokens seen so far per distance
   __shared__ int head_cnt[kMaxHs];
   __shared__ uint64_t sh_anchor[kMaxW];
 
-  const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
+  const int b = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
   const int S = p.S, Hs = p.Hs, nw = p.nw, W = p.W;
-  const uint64_t* rm = p.rowmask + (size_t)b * (Hs + 1) * nw;
-  const uint64_t* impmask = rm + (size_t)Hs * nw;
+  const uint64_t* __restrict__ rm = p.rowmask + (size_t)b * (Hs + 1) * nw;
+  const int wg_c0 = blockIdx.x * kGsChunksPerWg;
+  const int wg_nc = min(kGsChunksPerWg, nw - wg_c0);
 
-  for (int c = tid; c < nw; c += kSelThreads) p.repmask[(size_t)b * nw + c] = 0ull;
-  for (int i = tid; i < (Hs + 1) * kSelWaves; i += kSelThreads) wcount[i] = 0;
+  // this workgroup's words of every row -> LDS (read many times below)
+  for (int i = tid; i < (Hs + 1) * kGsChunksPerWg; i += kGsThreads) {
+    const int r = i / kGsChunksPerWg, c = i % kGsChunksPerWg;
+    lds_words[i] = c < wg_nc ? rm[(size_t)r * nw + wg_c0 + c] : 0ull;
+  }
+  for (int c = tid; c < wg_nc; c += kGsThreads) p.repmask[(size_t)b * nw + wg_c0 + c] = 0ull;
+  for (int i = tid; i < kGsWaves * (kMaxHs + 1); i += kGsThreads) (&run[0][0])[i] = 0;
+  if (tid < kMaxHs) head_cnt[tid] = 0;
+  __syncthreads();
 
-  // ---- anchor (Alg. 2, first step)
+  // ---- anchor (Alg. 2, first step); every workgroup derives the same one
   if (p.anchor_mode == KVCRUSH_ANCHOR_MEAN) {
-    // bit r is set in more than half of the grouped tokens?
-    for (int r = wave; r < Hs; r += kSelWaves) {
+    // bit r set in more than half of the grouped tokens?  counts over the whole sequence
+    const uint64_t* __restrict__ imp = rm + (size_t)Hs * nw;
+    for (int r = wave; r < Hs; r += kGsWaves) {
       int cnt = 0;
-      for (int c = lane; c < nw; c += KVC_WAVE) cnt += __popcll(rm[(size_t)r * nw + c] & ~impmask[c]);
+      for (int c = lane; c < nw; c += KVC_WAVE) cnt += __popcll(rm[(size_t)r * nw + c] & ~imp[c]);
       cnt = wave_sum(cnt);
       if (lane == 0) head_cnt[r] = cnt;
     }
+    __syncthreads();
   }
-  __syncthreads();
   if (tid < W) {
     uint64_t a = 0;
     if (p.anchor_mode == KVCRUSH_ANCHOR_RANDOM) {
@@ -273,58 +355,74 @@ __global__ __launch_bounds__(kSelThreads) void group_sort_kernel(GroupParams p) 
 #pragma unroll
   for (int w = 0; w < kMaxW; ++w) anchor[w] = w < W ? sh_anchor[w] : 0ull;
 
-  // ---- pass 1: per-token bit words, distance histogram per wave
-  int c0, c1;
-  wave_chunk_range(nw, kSelWaves, wave, c0, c1);
+  // ---- this wave's chunks: bit words out, distance, stable rank inside the wave
+  const int gw = blockIdx.x * kGsWaves + wave;
+  constexpr int kPerWave = kGsChunksPerWg / kGsWaves;
+  const int c0 = min(nw, wg_c0 + wave * kPerWave), c1 = min(nw, c0 + kPerWave);
   for (int c = c0; c < c1; ++c) {
+    const int lc = c - wg_c0;
     const int t = c * 64 + lane;
     uint64_t bw[kMaxW] = {0ull, 0ull};
     for (int r = 0; r < Hs; ++r) {
-      const uint64_t word = rm[(size_t)r * nw + c];  // same address for the whole wave
+      const uint64_t word = lds_words[r * kGsChunksPerWg + lc];  // same address for the whole wave
       bw[r >> 6] |= ((word >> lane) & 1ull) << (r & 63);
     }
-    const bool grouped = t < S && !((impmask[c] >> lane) & 1ull);
+    const bool grouped = t < S && !((lds_words[Hs * kGsChunksPerWg + lc] >> lane) & 1ull);
     if (t < S) {
       for (int w = 0; w < W; ++w) p.bits[((size_t)b * S + t) * W + w] = bw[w];
     }
     const uint32_t d = (uint32_t)(__popcll(bw[0] ^ anchor[0]) + __popcll(bw[1] ^ anchor[1]));
     const uint64_t peers = match_peers(d, p.dbits, grouped);
-    if (grouped && lane == __ffsll((unsigned long long)peers) - 1)
-      wcount[d * kSelWaves + wave] += __popcll(peers);
+    uint32_t packed = kNotGrouped;
+    if (grouped) {
+      const int base = run[wave][d];
+      packed = d | ((uint32_t)(base + __popcll(peers & lanemask_lt())) << 8);
+      if (lane == __ffsll((unsigned long long)peers) - 1) run[wave][d] = base + __popcll(peers);
+    }
+    if (t < S) p.dist_rank[(size_t)b * S + t] = packed;
   }
-  __syncthreads();
+  // this wave's column of the count table
+  for (int d = lane; d <= Hs; d += KVC_WAVE)
+    p.counts[((size_t)b * (Hs + 1) + d) * p.n_gw + gw] = run[wave][d];
+}
 
-  // ---- exclusive scan over (distance, wave): start rank of each wave's run
-  if (wave == 0) {
-    const int total = (Hs + 1) * kSelWaves;
-    const int per = (total + KVC_WAVE - 1) / KVC_WAVE;
-    const int i0 = min(total, lane * per), i1 = min(total, i0 + per);
-    int local = 0;
-    for (int i = i0; i < i1; ++i) local += wcount[i];
-    int run = wave_incl_scan(local) - local;
+__global__ __launch_bounds__(kGsThreads) void group_scatter_kernel(GroupParams p) {
+  extern __shared__ int lds_base[];  // [(Hs+1) * n_gw] start rank of every (distance, global wave)
+  __shared__ int wave_tot[kGsWaves];
+
+  const int b = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
+  const int S = p.S, Hs = p.Hs, nw = p.nw;
+  const int total = (Hs + 1) * p.n_gw;
+  const int32_t* __restrict__ counts = p.counts + (size_t)b * total;
+
+  // exclusive scan of the table in (distance, wave) order; every workgroup does the whole
+  // (small) table itself rather than waiting for another launch
+  const int per = (total + kGsThreads - 1) / kGsThreads;
+  const int i0 = min(total, tid * per), i1 = min(total, i0 + per);
+  int local = 0;
+  for (int i = i0; i < i1; ++i) local += counts[i];
+  {
+    const int incl = wave_incl_scan(local);
+    if (lane == KVC_WAVE - 1) wave_tot[wave] = incl;
+    __syncthreads();
+    int run = incl - local;
+    for (int w = 0; w < wave; ++w) run += wave_tot[w];
     for (int i = i0; i < i1; ++i) {
-      const int v = wcount[i];
-      wcount[i] = run;
-      run += v;
+      lds_base[i] = run;
+      run += counts[i];
     }
   }
   __syncthreads();
 
-  // ---- pass 2: stable scatter into rank order
-  int32_t* order = p.order + (size_t)b * S;
+  const int gw = blockIdx.x * kGsWaves + wave;
+  constexpr int kPerWave = kGsChunksPerWg / kGsWaves;
+  const int c0 = min(nw, (int)blockIdx.x * kGsChunksPerWg + wave * kPerWave), c1 = min(nw, c0 + kPerWave);
+  int32_t* __restrict__ order = p.order + (size_t)b * S;
   for (int c = c0; c < c1; ++c) {
     const int t = c * 64 + lane;
-    const bool grouped = t < S && !((impmask[c] >> lane) & 1ull);
-    uint32_t d = 0;
     if (t < S) {
-      for (int w = 0; w < W; ++w) d += __popcll(p.bits[((size_t)b * S + t) * W + w] ^ anchor[w]);
-    }
-    const uint64_t peers = match_peers(d, p.dbits, grouped);
-    if (grouped) {
-      const int slot = d * kSelWaves + wave;
-      const int base = wcount[slot];
-      order[base + __popcll(peers & lanemask_lt())] = t;
-      if (lane == __ffsll((unsigned long long)peers) - 1) wcount[slot] = base + __popcll(peers);
+      const uint32_t packed = p.dist_rank[(size_t)b * S + t];
+      if (packed != kNotGrouped) order[lds_base[(packed & 255u) * p.n_gw + gw] + (int)(packed >> 8)] = t;
     }
   }
 }
@@ -407,35 +505,48 @@ struct EmitParams {
 
 __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
   __shared__ int wave_tot[kSelWaves];
-  const int b = blockIdx.x, lane = lane_id(), wave = threadIdx.x / KVC_WAVE;
+  __shared__ uint64_t sh_kept[kSelThreads], sh_rep[kSelThreads];
+  __shared__ int sh_base[kSelThreads];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
   const uint64_t* imp = p.impmask_base + (size_t)b * p.imp_stride;
   const uint64_t* rep = p.repmask + (size_t)b * p.nw;
-  int c0, c1;
-  wave_chunk_range(p.nw, kSelWaves, wave, c0, c1);
-  int mine = 0;
-  for (int c = c0 + lane; c < c1; c += KVC_WAVE) mine += __popcll(imp[c] | rep[c]);
-  mine = wave_sum(mine);
-  if (lane == 0) wave_tot[wave] = mine;
-  __syncthreads();
-  int base = 0;
-  for (int w = 0; w < wave; ++w) base += wave_tot[w];
-  for (int c = c0; c < c1; ++c) {
-    const uint64_t rw = rep[c], kept = imp[c] | rw;
-    if ((kept >> lane) & 1ull) {
-      const int o = base + __popcll(kept & lanemask_lt());
-      if (o < p.budget) {  // always true for consistent masks; keeps stores in bounds regardless
-        p.idx[(size_t)b * p.budget + o] = c * 64 + lane;
-        if (p.kind) p.kind[(size_t)b * p.budget + o] = (uint8_t)((rw >> lane) & 1ull);
+  int carried = 0;  // indices emitted by earlier tiles of 1024 words
+  for (int w0 = 0; w0 < p.nw; w0 += kSelThreads) {
+    // one bitmap word per thread: count, prefix-sum, park in LDS
+    const int c = w0 + tid;
+    uint64_t rw = 0, kept = 0;
+    if (c < p.nw) {
+      rw = rep[c];
+      kept = imp[c] | rw;
+    }
+    const int cnt = __popcll(kept);
+    const int before = block_excl_scan(cnt, wave_tot);
+    sh_kept[tid] = kept;
+    sh_rep[tid] = rw;
+    sh_base[tid] = carried + before;
+    __syncthreads();
+    const int tile_total = sh_base[kSelThreads - 1] + __popcll(sh_kept[kSelThreads - 1]) - carried;
+    // one word per wave at a time: lanes with their bit set write in order
+    const int n_here = min(kSelThreads, p.nw - w0);
+    for (int j = wave; j < n_here; j += kSelWaves) {
+      const uint64_t kw = sh_kept[j], rj = sh_rep[j];
+      if ((kw >> lane) & 1ull) {
+        const int o = sh_base[j] + __popcll(kw & lanemask_lt());
+        if (o < p.budget) {  // always true for consistent masks; keeps stores in bounds regardless
+          p.idx[(size_t)b * p.budget + o] = (w0 + j) * 64 + lane;
+          if (p.kind) p.kind[(size_t)b * p.budget + o] = (uint8_t)((rj >> lane) & 1ull);
+        }
       }
     }
-    base += __popcll(kept);
+    carried += tile_total;
+    __syncthreads();
   }
 }
 
 // ------------------------------------------------------------- host side ---
 struct SelectLayout {
-  size_t rowmask, repmask, bits, order, keys, total;
-  int nw, W;
+  size_t rowmask, repmask, bits, order, dist_rank, counts, keys, total;
+  int nw, W, n_wg, n_gw;  // grouping workgroups / global waves per sequence
   bool keys_in_lds;
 };
 
@@ -456,6 +567,12 @@ SelectLayout select_layout(const kvcrush_select_args* a, bool need_bits_ws) {
   off += kvc::align_up((size_t)a->B * L.nw * 8, 256);
   L.order = off;
   off += kvc::align_up((size_t)a->B * a->S * 4, 256);
+  L.n_wg = (L.nw + kGsChunksPerWg - 1) / kGsChunksPerWg;
+  L.n_gw = L.n_wg * kGsWaves;
+  L.dist_rank = off;
+  off += kvc::align_up((size_t)a->B * a->S * 4, 256);
+  L.counts = off;
+  off += kvc::align_up((size_t)a->B * (a->Hs + 1) * L.n_gw * 4, 256);
   L.bits = off;
   if (need_bits_ws) off += kvc::align_up((size_t)a->B * a->S * L.W * 8, 256);
   L.keys = off;
@@ -517,17 +634,22 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
     p.n_important = args->n_important;
     const size_t dyn = L.keys_in_lds ? (size_t)S * 4 : 0;
     if (dyn > 48 * 1024) {
-      if (hipFuncSetAttribute((const void*)topk_mask_kernel,
+      if (hipFuncSetAttribute((const void*)topk_mask_kernel<true>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn) != hipSuccess)
         return KVCRUSH_ERR_HIP;
     }
-    hipLaunchKernelGGL(topk_mask_kernel, dim3(Hs + 1, B), dim3(kSelThreads), dyn, stream, p);
+    if (L.keys_in_lds)
+      hipLaunchKernelGGL(topk_mask_kernel<true>, dim3(Hs + 1, B), dim3(kSelThreads), dyn, stream, p);
+    else
+      hipLaunchKernelGGL(topk_mask_kernel<false>, dim3(Hs + 1, B), dim3(kSelThreads), 0, stream, p);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
   {
     GroupParams p;
     p.rowmask = rowmask;
     p.bits = bits_buf;
+    p.dist_rank = (uint32_t*)(ws + L.dist_rank);
+    p.counts = (int32_t*)(ws + L.counts);
     p.order = order;
     p.repmask = repmask;
     p.anchor_bits = args->anchor_bits;
@@ -541,7 +663,18 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
     int dbits = 0;
     while ((1 << dbits) <= Hs) ++dbits;  // distances range over 0..Hs
     p.dbits = dbits;
-    hipLaunchKernelGGL(group_sort_kernel, dim3(B), dim3(kSelThreads), 0, stream, p);
+    p.n_gw = L.n_gw;
+    const size_t dyn_a = (size_t)(Hs + 1) * kGsChunksPerWg * 8;  // <= 16.5 KiB
+    hipLaunchKernelGGL(group_rank_kernel, dim3(L.n_wg, B), dim3(kGsThreads), dyn_a, stream, p);
+    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+    const size_t dyn_b = (size_t)(Hs + 1) * L.n_gw * 4;
+    if (dyn_b > 120 * 1024) return KVCRUSH_ERR_UNSUPPORTED;  // Hs * S beyond ~60M: table too large for LDS
+    if (dyn_b > 32 * 1024) {
+      if (hipFuncSetAttribute((const void*)group_scatter_kernel,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_b) != hipSuccess)
+        return KVCRUSH_ERR_HIP;
+    }
+    hipLaunchKernelGGL(group_scatter_kernel, dim3(L.n_wg, B), dim3(kGsThreads), dyn_b, stream, p);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
   if (Br > 0) {

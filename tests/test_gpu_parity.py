@@ -108,6 +108,7 @@ def check_select(kv, oracle, sc, budget, n_imp, kbit, anchor, seed=0, anchor_bit
     (1, 8, 32768, 1024, 768, 0, "alternating", True),
     (1, 4, 40000, 5000, 3000, 0, "random", True),  # rows too long for LDS: keys go through the workspace
     (8, 8, 8192, 2048, 1536, 0, "alternating", False),
+    (1, 128, 8192, 1000, 600, 0, "mean", True),    # row bitmaps too large for LDS staging
 ])
 def test_select_matches_oracle(kv, oracle, B, Hs, S, budget, n_imp, kbit, anchor, ties):
     say(f"select B={B} Hs={Hs} S={S} budget={budget} n_imp={n_imp} kbit={kbit} {anchor} ties={ties}")
