@@ -716,10 +716,7 @@ ColsumPlan colsum_plan(int S, int tile, int chunk_tiles_wanted) {
   return pl;
 }
 
-#ifndef KVC_CHUNK_QUERIES
-#define KVC_CHUNK_QUERIES 1024
-#endif
-constexpr int kChunkQueries = KVC_CHUNK_QUERIES;  // queries per pass-B work piece
+constexpr int kChunkQueries = 1152;  // queries per pass-B work piece: 18 tiles, a multiple of 3
 
 template <bool BF16, int D>
 kvcrush_status launch_lse(const ScoreParams& base, hipStream_t stream) {
