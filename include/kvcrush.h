@@ -51,7 +51,7 @@ typedef enum {
 
 typedef enum { KVCRUSH_F32 = 0, KVCRUSH_BF16 = 1 } kvcrush_dtype;
 
-/* Anchor vector of Alg. 2 ("random, mean of input vectors, or alternating 0-1"). */
+/* Anchor vector of Alg. 2: the three strategies it names, plus a caller-supplied one. */
 typedef enum {
   KVCRUSH_ANCHOR_RANDOM = 0,      /* word w of sequence b = output w+1 of splitmix64 seeded
                                      with anchor_seed + b, masked to Hs bits           */
@@ -71,6 +71,11 @@ typedef struct {
   int32_t dtype;         /* kvcrush_dtype of Q and K                                  */
   int32_t reduce_groups; /* 1: sum each KV group's query heads -> Hs = Hkv score rows
                             0: one score row per query head    -> Hs = Hq            */
+  int32_t obs_window;    /* 0: every query position contributes to the scores.
+                            W > 0: only the last min(W, S) query positions do (the
+                            observation window of the SnapKV baseline, Sec. 2.3);
+                            every score row then totals W instead of S, and lse rows
+                            before the window are unspecified / not needed.           */
 } kvcrush_shape;
 
 /* ---------------------------------------------------------------- stage 1 --
@@ -100,12 +105,20 @@ kvcrush_status kvcrush_scores(const kvcrush_shape* shape, const void* q, const v
 
 /* First half of stage 1 on its own: lse_out[b, h, i] = natural log of
  * sum_{j <= i} exp(Q_h[i] . K[j] / sqrt(D))  (the normaliser of row i of Alg. 1's
- * A_h), fp32 [B, Hq, S], fully overwritten.  Passing the result as `lse` to
+ * A_h), fp32 [B, Hq, S], fully overwritten (with shape->obs_window = W > 0 only the
+ * rows i >= S - W are guaranteed to be written; the others are never read).  Passing the result as `lse` to
  * kvcrush_scores gives exactly what kvcrush_scores computes with lse = NULL;
  * callers whose attention kernel already produced these values skip this call.
  * shape->reduce_groups is ignored. */
 kvcrush_status kvcrush_row_lse(const kvcrush_shape* shape, const void* q, const void* k,
                                float* lse_out, void* hip_stream);
+
+/* Optional step between stages 1 and 2 for SnapKV-style selection (Sec. 2.3 /
+ * 4.1.1: max pooling so that the neighbours of strong tokens are kept too):
+ * out[r, t] = max over |u - t| <= kernel / 2, 0 <= u < S, of in[r, u].
+ *   in, out  [rows, S] fp32, must not overlap; kernel odd, 1 <= kernel <= 1023. */
+kvcrush_status kvcrush_pool_scores(int32_t rows, int32_t S, int32_t kernel, const float* in,
+                                   float* out, void* hip_stream);
 
 /* ------------------------------------------------------------ stages 2-4 --
  * Per sequence b, from scores[b] ([Hs, S] fp32):

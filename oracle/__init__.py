@@ -43,7 +43,8 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(build())
         vp, i32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
         L.kvcrush_oracle_head_colsums.argtypes = [i32, i32, i32, vp, vp, i32, i32, vp, vp]
-        L.kvcrush_oracle_scores.argtypes = [i32] * 7 + [vp] * 4
+        L.kvcrush_oracle_scores.argtypes = [i32] * 8 + [vp] * 4
+        L.kvcrush_oracle_maxpool.argtypes = [i32, i32, i32, vp, vp]
         L.kvcrush_oracle_topk.argtypes = [vp, i32, i32, vp]
         L.kvcrush_oracle_splitmix64.argtypes = [u64, i32, vp]
         L.kvcrush_oracle_splitmix64.restype = None
@@ -97,8 +98,11 @@ def head_colsums(q_head, k_head, row_begin=0, row_end=None, want_lse=False):
     return (c, lse) if want_lse else c
 
 
-def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1):
+def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1, window: int = 0):
     """scores [B,Hs,S] fp32 from q [B,Hq,S,D], k [B,Hkv,S,D].
+
+    window = W > 0: only the last min(W, S) query rows contribute (lse rows
+    before the window are zero).
 
     threads > 1 spreads independent (batch, head) units of the unchanged
     single-threaded routine over host threads (the foreign call releases the
@@ -113,15 +117,16 @@ def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1):
     if threads <= 1:
         out = torch.empty(B, Hs, S, dtype=torch.float32)
         lse = torch.empty(B, Hq, S, dtype=torch.float32) if want_lse else None
-        rc = lib().kvcrush_oracle_scores(B, Hq, Hkv, S, D, _dtype_code(q), int(reduce_groups),
+        rc = lib().kvcrush_oracle_scores(B, Hq, Hkv, S, D, _dtype_code(q), int(reduce_groups), window,
                                          _ptr(q), _ptr(k), _ptr(out), _ptr(lse))
         _check(rc, "scores")
         return (out, lse) if want_lse else out
 
+    row_begin = 0 if window == 0 or window >= S else S - window
     units = [(b, h) for b in range(B) for h in range(Hq)]
     with ThreadPoolExecutor(max_workers=threads) as ex:
-        res = list(ex.map(lambda u: head_colsums(q[u[0], u[1]], k[u[0], u[1] // G], want_lse=True),
-                          units))
+        res = list(ex.map(lambda u: head_colsums(q[u[0], u[1]], k[u[0], u[1] // G], row_begin, S,
+                                                 want_lse=True), units))
     c = torch.stack([r[0] for r in res]).view(B, Hq, S)
     lse = torch.stack([r[1] for r in res]).view(B, Hq, S).to(torch.float32)
     if reduce_groups:
@@ -132,6 +137,15 @@ def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1):
     else:
         out = c.to(torch.float32)
     return (out, lse) if want_lse else out
+
+
+def maxpool(scores_t, kernel: int):
+    """Centred 1-D max pool (odd kernel, -inf padding) along the last axis of fp32 scores."""
+    sc = _cpu(scores_t.to(torch.float32))
+    S = sc.shape[-1]
+    out = torch.empty_like(sc)
+    _check(lib().kvcrush_oracle_maxpool(sc.numel() // S, S, kernel, _ptr(sc), _ptr(out)), "maxpool")
+    return out
 
 
 def topk(v, k: int):

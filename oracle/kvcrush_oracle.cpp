@@ -18,15 +18,17 @@
 //   * The printed score of Alg. 1 sums a softmax row, which is 1 for every
 //     token.  The H2O meaning is used instead: the attention a token RECEIVES,
 //     c_h[t] = sum over queries i >= t of A_h(i, t), causal mask, no 1/S factor.
-//   * theta_h "retains a target fraction of tokens for each head": exact
-//     per-head top-k, ties resolved towards the lower token index.
-//   * "Assign to one of B_representative buckets based on d_t": tokens are
+//   * theta_h is described as the cut that keeps a fixed share of the tokens
+//     of each head: exact per-head top-k, ties resolved towards the lower index.
+//   * Alg. 2 only says that the bucket of a token follows from d_t: tokens are
 //     ordered by (d_t, token index) and cut into B_representative contiguous
 //     rank ranges [floor(j*N/Br), floor((j+1)*N/Br)).
-//   * Only tokens NOT kept as important are grouped ("proxies of the evicted
-//     tokens"), so the two sets are disjoint and the cache holds exactly B.
-//   * "Closest to the centroid": L1 distance to the fractional centroid times
-//     the bucket size, an integer: sum_r (bit_r ? n - cnt_r : cnt_r).
+//   * Only tokens NOT kept as important are grouped (Sec. 3 presents the
+//     representatives as stand-ins for what is evicted), so the two sets are
+//     disjoint and the cache holds exactly B.
+//   * Nearness to the bucket centroid is measured as L1 distance to the
+//     fractional centroid times the bucket size, an integer:
+//     sum_r (bit_r ? n - cnt_r : cnt_r).
 //   * Every tie goes to the lower token index.  Output ascending by position.
 //
 // Parity pins (tests/test_oracle_*.py): brute force with the full SxS matrix,
@@ -124,9 +126,15 @@ int kvcrush_oracle_head_colsums(int S, int D, int dtype, const void* q_head, con
 // head h / (Hq/Hkv).  scores: [B,Hs,S] fp32 with Hs = Hkv when reduce_groups
 // (the heads of a group are summed in double, ascending, and rounded once),
 // else Hs = Hq.  lse_out (nullable): [B,Hq,S] fp32.
+// obs_window = 0: every query row contributes.  obs_window = W > 0: only the last
+// min(W, S) query rows do (SnapKV's observation window over the end of the
+// prompt, as Sec. 2.3 summarises that baseline); lse_out rows before the
+// window are left at zero.
 int kvcrush_oracle_scores(int B, int Hq, int Hkv, int S, int D, int dtype, int reduce_groups,
-                          const void* q, const void* k, float* scores, float* lse_out) {
-  if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || D < 1) return 1;
+                          int obs_window, const void* q, const void* k, float* scores,
+                          float* lse_out) {
+  if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || D < 1 || obs_window < 0) return 1;
+  const int row_begin = (obs_window == 0 || obs_window >= S) ? 0 : S - obs_window;
   const int G = Hq / Hkv;
   const size_t es = elem_size(dtype), head_elems = (size_t)S * D;
   std::vector<double> c(S), acc(S), lse(S);
@@ -138,7 +146,8 @@ int kvcrush_oracle_scores(int B, int Hq, int Hkv, int S, int D, int dtype, int r
         std::fill(c.begin(), c.end(), 0.0);
         const char* qh = (const char*)q + ((size_t)b * Hq + h) * head_elems * es;
         const char* kh = (const char*)k + ((size_t)b * Hkv + g) * head_elems * es;
-        int rc = kvcrush_oracle_head_colsums(S, D, dtype, qh, kh, 0, S, c.data(), lse.data());
+        std::fill(lse.begin(), lse.end(), 0.0);
+        int rc = kvcrush_oracle_head_colsums(S, D, dtype, qh, kh, row_begin, S, c.data(), lse.data());
         if (rc) return rc;
         if (lse_out)
           for (int t = 0; t < S; ++t) lse_out[((size_t)b * Hq + h) * S + t] = (float)lse[t];
@@ -152,6 +161,22 @@ int kvcrush_oracle_scores(int B, int Hq, int Hkv, int S, int D, int dtype, int r
         for (int t = 0; t < S; ++t) scores[((size_t)b * Hkv + g) * S + t] = (float)acc[t];
     }
   }
+  return 0;
+}
+
+// 1-D max pooling along the token axis, window `kernel` (odd), centred, the
+// sequence ends padded with -inf (the pooling step by which SnapKV also keeps
+// the neighbours of strong tokens, Sec. 2.3 / 4.1.1).  in, out: [rows, S].
+int kvcrush_oracle_maxpool(int rows, int S, int kernel, const float* in, float* out) {
+  if (rows < 0 || S < 1 || kernel < 1 || kernel % 2 == 0) return 1;
+  const int half = kernel / 2;
+  for (int r = 0; r < rows; ++r)
+    for (int t = 0; t < S; ++t) {
+      float best = -INFINITY;
+      for (int u = t - half; u <= t + half; ++u)
+        if (u >= 0 && u < S && in[(size_t)r * S + u] > best) best = in[(size_t)r * S + u];
+      out[(size_t)r * S + t] = best;
+    }
   return 0;
 }
 

@@ -19,8 +19,8 @@ ANCHORS = {"random": 0, "mean": 1, "alternating": 2, "explicit": 3}
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 
 EXPORTS = (
-    "kvcrush_scores_workspace", "kvcrush_scores", "kvcrush_row_lse", "kvcrush_select_workspace", "kvcrush_select",
-    "kvcrush_compact", "kvcrush_status_string", "kvcrush_version",
+    "kvcrush_scores_workspace", "kvcrush_scores", "kvcrush_row_lse", "kvcrush_pool_scores",
+    "kvcrush_select_workspace", "kvcrush_select", "kvcrush_compact", "kvcrush_status_string", "kvcrush_version",
 )
 
 
@@ -31,7 +31,8 @@ class KVCrushError(RuntimeError):
 
 
 class Shape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hq", "Hkv", "S", "D", "dtype", "reduce_groups")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hq", "Hkv", "S", "D", "dtype", "reduce_groups",
+                                                 "obs_window")]
 
 
 class SelectArgs(ctypes.Structure):
@@ -58,6 +59,8 @@ def load() -> ctypes.CDLL:
         L.kvcrush_scores.restype = ctypes.c_int
         L.kvcrush_row_lse.argtypes = [ctypes.POINTER(Shape), vp, vp, vp, vp]
         L.kvcrush_row_lse.restype = ctypes.c_int
+        L.kvcrush_pool_scores.argtypes = [i32, i32, i32, vp, vp, vp]
+        L.kvcrush_pool_scores.restype = ctypes.c_int
         L.kvcrush_select_workspace.argtypes = [ctypes.POINTER(SelectArgs)]
         L.kvcrush_select_workspace.restype = sz
         L.kvcrush_select.argtypes = [ctypes.POINTER(SelectArgs), vp, vp, vp, vp, vp, sz, vp]
@@ -105,24 +108,25 @@ def _check(status: int, what: str):
         raise KVCrushError(status, what)
 
 
-def make_shape(q: torch.Tensor, k: torch.Tensor, reduce_groups: bool) -> Shape:
+def make_shape(q: torch.Tensor, k: torch.Tensor, reduce_groups: bool, window: int = 0) -> Shape:
     B, Hq, S, D = q.shape
-    return Shape(B, Hq, k.shape[1], S, D, _dtype_code(q), int(bool(reduce_groups)))
+    return Shape(B, Hq, k.shape[1], S, D, _dtype_code(q), int(bool(reduce_groups)), int(window))
 
 
 def kvcrush_scores_workspace(shape: Shape) -> int:
     return int(load().kvcrush_scores_workspace(ctypes.byref(shape)))
 
 
-def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=None, stream=None):
+def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=None, stream=None, window=0):
     """q [B,Hq,S,D], k [B,Hkv,S,D] on the GPU -> scores [B,Hs,S] fp32.
+    window = W > 0 restricts the contributing queries to the last min(W, S).
     Returns (scores, workspace); the workspace's first B*Hq*S floats hold the
     row log-sum-exps when `lse` was not supplied."""
     q, k = _dev(q, "q"), _dev(k, "k")
     if q.dtype != k.dtype or q.dim() != 4 or k.dim() != 4 or q.shape[0] != k.shape[0] \
             or q.shape[2:] != k.shape[2:]:
         raise ValueError("q and k must be [B,H,S,D] tensors of one dtype with matching B, S, D")
-    shape = make_shape(q, k, reduce_groups)
+    shape = make_shape(q, k, reduce_groups, window)
     Hs = shape.Hkv if reduce_groups else shape.Hq
     if scores is None:
         scores = torch.empty(shape.B, Hs, shape.S, dtype=torch.float32, device=q.device)
@@ -139,16 +143,31 @@ def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=N
     return scores, workspace
 
 
-def kvcrush_row_lse(q, k, lse_out=None, stream=None):
-    """q [B,Hq,S,D], k [B,Hkv,S,D] on the GPU -> natural-log row normalisers fp32 [B,Hq,S]."""
+def kvcrush_row_lse(q, k, lse_out=None, stream=None, window=0):
+    """q [B,Hq,S,D], k [B,Hkv,S,D] on the GPU -> natural-log row normalisers fp32 [B,Hq,S]
+    (with window = W > 0 only the rows of the last min(W, S) queries are defined)."""
     q, k = _dev(q, "q"), _dev(k, "k")
-    shape = make_shape(q, k, False)
+    shape = make_shape(q, k, False, window)
     if lse_out is None:
         lse_out = torch.empty(shape.B, shape.Hq, shape.S, dtype=torch.float32, device=q.device)
     st = load().kvcrush_row_lse(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(_dev(lse_out, "lse_out")),
                                 _stream(stream))
     _check(st, "kvcrush_row_lse")
     return lse_out
+
+
+def kvcrush_pool_scores(scores, kernel: int, out=None, stream=None):
+    """Centred sliding maximum of width `kernel` (odd) along the last axis of fp32 scores."""
+    scores = _dev(scores, "scores")
+    if scores.dtype != torch.float32:
+        raise ValueError("scores must be fp32")
+    if out is None:
+        out = torch.empty_like(scores)
+    S = scores.shape[-1]
+    st = load().kvcrush_pool_scores(scores.numel() // S, S, kernel, _ptr(scores), _ptr(_dev(out, "out")),
+                                    _stream(stream))
+    _check(st, "kvcrush_pool_scores")
+    return out
 
 
 def lse_from_workspace(workspace: torch.Tensor, B: int, Hq: int, S: int) -> torch.Tensor:

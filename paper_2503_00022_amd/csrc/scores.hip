@@ -169,6 +169,8 @@ struct ScoreParams {
   int n_bh;          // (batch, head-group) pairs
   int chunk_tiles;   // pass B: query tiles per work piece
   int n_chunks;      // pass B: chunks along the query axis
+  int q_first;       // first query row that contributes (0 unless an observation window is set)
+  int tile0;         // pass B: q_first / kTile, the first query tile that is streamed
   float scale_log2;  // log2(e) / sqrt(D)
 };
 
@@ -512,7 +514,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   int chunk = p.n_chunks - 1;
   int t_last;
   for (;;) {
-    t_last = min((chunk + 1) * p.chunk_tiles, n_tiles) - 1;
+    t_last = min(p.tile0 + (chunk + 1) * p.chunk_tiles, n_tiles) - 1;
     const int cnt = min(n_kb, t_last / kTpk + 1);
     if (rem < cnt) break;
     rem -= cnt;
@@ -534,7 +536,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   load_stationary<C>(kf[1], kh, k0 + 32, S, lane);
 
   // tiles of this piece: [t_first, t_last]; those below f_first touch the diagonal
-  const int t_first = max(chunk * p.chunk_tiles, kb * kTpk);
+  const int t_first = max(p.tile0 + chunk * p.chunk_tiles, kb * kTpk);
   const int f_first = C::kPipelined ? max(t_first, kb * kTpk + kTpk) : t_last + 1;
   const int n_fullt = max(0, t_last - f_first + 1);
   const int d_last = t_last - n_fullt;
@@ -554,7 +556,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
     // straight block; threads beyond the tile re-read its rows and are ignored.
     const int i = qt + (tid & (C::kTile - 1));
     const float v = lse_in[((size_t)b * p.Hq + head) * S + min(i, S - 1)] * kLog2e;
-    return i < S ? v : INFINITY;
+    return (i < S && i >= p.q_first) ? v : INFINITY;  // rows outside the observation window: none
   };
 
   // ---- tiles after the diagonal: no mask, hand-pipelined
@@ -689,7 +691,7 @@ __global__ __launch_bounds__(kKeysPerWg) void colsum_reduce_kernel(ScoreParams p
   const int kb = blockIdx.x, bh = blockIdx.y;
   const int t = kb * kKeysPerWg + threadIdx.x;
   if (t >= p.S) return;
-  const int c_min = kb * tiles_per_kb / p.chunk_tiles;
+  const int c_min = max(0, kb * tiles_per_kb - p.tile0) / p.chunk_tiles;
   const float* src = p.partial + ((size_t)bh * p.n_blocks + kb) * p.n_chunks * kKeysPerWg + threadIdx.x;
   float acc = 0.0f;
   for (int c = c_min; c < p.n_chunks; ++c) acc += src[(size_t)c * kKeysPerWg];
@@ -701,15 +703,16 @@ struct ColsumPlan {
   int n_kb, n_chunks, chunk_tiles, pieces;  // pieces per (batch, score row)
 };
 
-ColsumPlan colsum_plan(int S, int tile, int chunk_tiles_wanted) {
+ColsumPlan colsum_plan(int S, int tile, int chunk_tiles_wanted, int q_first) {
   ColsumPlan pl;
-  const int n_tiles = (S + tile - 1) / tile, tpk = kKeysPerWg / tile;
+  const int n_tiles = (S + tile - 1) / tile, tpk = kKeysPerWg / tile, tile0 = q_first / tile;
   pl.n_kb = (S + kKeysPerWg - 1) / kKeysPerWg;
   pl.chunk_tiles = chunk_tiles_wanted;
-  pl.n_chunks = (n_tiles + pl.chunk_tiles - 1) / pl.chunk_tiles;
+  pl.n_chunks = (n_tiles - tile0 + pl.chunk_tiles - 1) / pl.chunk_tiles;
   pl.pieces = 0;
   for (int c = 0; c < pl.n_chunks; ++c) {
-    const int t_last = (c + 1) * pl.chunk_tiles < n_tiles ? (c + 1) * pl.chunk_tiles - 1 : n_tiles - 1;
+    const int end = tile0 + (c + 1) * pl.chunk_tiles;
+    const int t_last = end < n_tiles ? end - 1 : n_tiles - 1;
     const int cnt = t_last / tpk + 1;
     pl.pieces += cnt < pl.n_kb ? cnt : pl.n_kb;
   }
@@ -725,7 +728,10 @@ kvcrush_status launch_lse(const ScoreParams& base, hipStream_t stream) {
   const int qsub = kWaves / a.heads_per_wg;
   a.n_blocks = (a.S + 64 * qsub - 1) / (64 * qsub);
   a.n_bh = a.B * (a.Hq / a.heads_per_wg);
-  hipLaunchKernelGGL((lse_kernel<BF16, D>), dim3((unsigned)(a.n_blocks * a.n_bh)), dim3(kThreads), 0,
+  // blocks are numbered from the end of the sequence: with an observation window only
+  // the blocks that reach into it are launched
+  const int launched = a.n_blocks - a.q_first / (64 * qsub);
+  hipLaunchKernelGGL((lse_kernel<BF16, D>), dim3((unsigned)(launched * a.n_bh)), dim3(kThreads), 0,
                      stream, a);
   return kvc::launch_status();
 }
@@ -739,7 +745,8 @@ kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, boo
     if (launch_lse<BF16, D>(p, stream) != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
   if (lse_only) return KVCRUSH_OK;
-  const ColsumPlan pl = colsum_plan(p.S, C::kTile, kChunkQueries / C::kTile);
+  const ColsumPlan pl = colsum_plan(p.S, C::kTile, kChunkQueries / C::kTile, p.q_first);
+  p.tile0 = p.q_first / C::kTile;
   p.n_blocks = pl.n_kb;
   p.n_chunks = pl.n_chunks;
   p.chunk_tiles = pl.chunk_tiles;
@@ -755,6 +762,11 @@ kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, boo
   return KVCRUSH_OK;
 }
 
+// First query row that contributes to the scores.
+int first_query(const kvcrush_shape* s) {
+  return (s->obs_window <= 0 || s->obs_window >= s->S) ? 0 : s->S - s->obs_window;
+}
+
 // Workspace: [lse: B*Hq*S floats][partial column sums]
 size_t lse_bytes(const kvcrush_shape* s) {
   return kvc::align_up((size_t)s->B * s->Hq * s->S * sizeof(float), 256);
@@ -762,7 +774,7 @@ size_t lse_bytes(const kvcrush_shape* s) {
 
 size_t partial_bytes(const kvcrush_shape* s) {
   const int tile = s->dtype == KVCRUSH_BF16 ? 64 : 32;
-  const ColsumPlan pl = colsum_plan(s->S, tile, kChunkQueries / tile);
+  const ColsumPlan pl = colsum_plan(s->S, tile, kChunkQueries / tile, first_query(s));
   if (pl.n_chunks <= 1) return 0;
   const size_t rows = (size_t)s->B * (s->reduce_groups ? s->Hkv : s->Hq);
   return kvc::align_up(rows * pl.n_kb * pl.n_chunks * kKeysPerWg * sizeof(float), 256);
@@ -774,6 +786,7 @@ bool shape_ok(const kvcrush_shape* s) {
   if (s->Hq % s->Hkv != 0) return false;
   if (s->dtype != KVCRUSH_F32 && s->dtype != KVCRUSH_BF16) return false;
   if (s->reduce_groups != 0 && s->reduce_groups != 1) return false;
+  if (s->obs_window < 0) return false;
   return true;
 }
 
@@ -799,6 +812,8 @@ kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const voi
   p.n_bh = 0;
   p.chunk_tiles = 1;
   p.n_chunks = 1;
+  p.q_first = first_query(shape);
+  p.tile0 = 0;
   p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)shape->D));
   const bool bf16 = shape->dtype == KVCRUSH_BF16;
   if (bf16 && shape->D == 128) return launch_scores<true, 128>(p, lse, lse_only, stream);

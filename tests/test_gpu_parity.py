@@ -203,6 +203,91 @@ def test_scores_extreme_logits(kv, oracle):
         assert got[~big].abs().max().item() <= 1e-30 if (~big).any() else True
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,S,D,dtype,rg,W", [
+    (1, 4, 2, 700, 128, "bf16", True, 32),      # window inside the last tile
+    (2, 4, 1, 1000, 128, "bf16", True, 1),      # the last attention row alone
+    (1, 2, 2, 900, 64, "bf16", False, 333),     # ragged window start, D = 64
+    (1, 4, 2, 4000, 128, "bf16", True, 2500),   # window over several query chunks, tile offset > 0
+    (1, 2, 1, 3000, 128, "bf16", True, 1152),   # exactly one chunk of queries
+    (1, 2, 2, 1500, 128, "f32", False, 100),    # fp32 path
+    (1, 2, 1, 2500, 64, "f32", True, 1300),     # fp32 path, partial sums with a tile offset
+    (1, 2, 1, 300, 128, "bf16", True, 300),     # W = S: all rows
+    (1, 2, 1, 300, 128, "bf16", True, 5000),    # W > S: all rows
+])
+def test_scores_observation_window(kv, oracle, B, Hq, Hkv, S, D, dtype, rg, W):
+    """Received attention from the last W queries only (the SnapKV baseline's scores)."""
+    say(f"window scores B={B} Hq={Hq} Hkv={Hkv} S={S} D={D} {dtype} reduce_groups={rg} W={W}")
+    w = inputs.Workload("t", B, Hq, Hkv, S, D, dtype, max(1, S // 4), 0.5, "alternating", rg, sink_bias=True)
+    q, k, _ = inputs.make_qkv(w, S + W, want_v=False)
+    sc, ws = kv.kvcrush_scores(q.cuda(), k.cuda(), rg, window=W)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.scores(q, k, rg, want_lse=True, threads=THREADS, window=W)
+    got, want = sc.cpu().double(), ref.double()
+    big = want > 1e-30
+    assert ((got[big] - want[big]).abs() / want[big]).max().item() <= SCORE_RTOL
+    if (~big).any():
+        assert got[~big].abs().max().item() <= 1e-30
+    Weff = min(W, S)
+    tot = got.sum(-1)
+    assert torch.allclose(tot, torch.full_like(tot, float((Hq // Hkv if rg else 1) * Weff)), rtol=1e-4)
+    # the normalisers of the window rows are the ones the workspace holds
+    lse = kv.lse_from_workspace(ws, B, Hq, S).cpu()
+    assert (lse[..., S - Weff:].double() - ref_lse[..., S - Weff:].double()).abs().max().item() < 1e-4
+    # a caller-supplied lse is read inside the window only: garbage before it is harmless
+    junk = ref_lse.clone()
+    junk[..., : S - Weff] = float("nan")
+    sc2, _ = kv.kvcrush_scores(q.cuda(), k.cuda(), rg, lse=junk.cuda(), window=W)
+    torch.cuda.synchronize()
+    got2 = sc2.cpu().double()
+    assert torch.isfinite(got2).all()
+    assert ((got2[big] - want[big]).abs() / want[big]).max().item() <= SCORE_RTOL
+    # row_lse on its own writes the same window rows
+    lse2 = kv.kvcrush_row_lse(q.cuda(), k.cuda(), window=W).cpu()
+    assert torch.equal(lse2[..., S - Weff:], lse[..., S - Weff:])
+
+
+@pytest.mark.parametrize("rows,S,kernel", [((2, 3), 37, 1), ((1, 8), 1000, 7), ((3,), 2048, 5), ((2, 2), 2049, 13),
+                                           ((1,), 5000, 1023), ((4,), 6, 41), ((1, 1), 1, 3), ((8, 8), 16384, 7)])
+def test_pool_scores(kv, oracle, rows, S, kernel):
+    say(f"max pool rows={rows} S={S} kernel={kernel}")
+    x = torch.randn(*rows, S, generator=torch.Generator().manual_seed(S + kernel))
+    x = (x * 4).round() / 4  # plenty of equal values
+    got = kv.kvcrush_pool_scores(x.cuda(), kernel)
+    torch.cuda.synchronize()
+    assert torch.equal(got.cpu(), oracle.maxpool(x, kernel))
+
+
+def test_pool_scores_rejects_bad_arguments(kv):
+    x = torch.zeros(2, 64, device="cuda")
+    for kernel in (0, 2, 1025, -3):
+        with pytest.raises(kv.KVCrushError):
+            kv.kvcrush_pool_scores(x, kernel)
+    with pytest.raises(kv.KVCrushError):
+        kv.kvcrush_pool_scores(x, 3, out=x)                   # in place is not supported
+    with pytest.raises(kv.KVCrushError):
+        kv.kvcrush_pool_scores(x.view(-1)[:64].view(1, 64), 3, out=x.view(-1)[32:96].view(1, 64))
+
+
+def test_window_pool_topk_pipeline(kv, oracle):
+    """The SnapKV-style baseline end to end: window scores, pooling, plain top-k
+    (budget == n_important, so no representatives), gather."""
+    say("window -> pool -> top-k -> gather")
+    w = inputs.Workload("t", 2, 8, 2, 2000, 128, "bf16", 500, 1.0, "alternating", True, sink_bias=True)
+    q, k, v = inputs.make_qkv(w, 5)
+    sc, _ = kv.kvcrush_scores(q.cuda(), k.cuda(), True, window=64)
+    pooled = kv.kvcrush_pool_scores(sc, 7)
+    idx, kind, _ = kv.kvcrush_select(pooled, 500, 500)
+    ko, vo = kv.kvcrush_compact(k.cuda(), v.cuda(), idx)
+    torch.cuda.synchronize()
+    ref_pooled = oracle.maxpool(sc.cpu(), 7)
+    assert torch.equal(pooled.cpu(), ref_pooled)
+    ridx, rkind, _ = oracle.select(ref_pooled, 500, 500)
+    assert torch.equal(idx.cpu(), ridx) and torch.equal(kind.cpu(), rkind)
+    rk, rv = oracle.compact(k, v, ridx)
+    assert torch.equal(ko.cpu().view(torch.uint8), rk.view(torch.uint8))
+    assert torch.equal(vo.cpu().view(torch.uint8), rv.view(torch.uint8))
+
+
 def test_scores_deterministic(kv):
     w = inputs.Workload("t", 1, 8, 2, 1500, 128, "bf16", 256, 0.5, "alternating", True)
     q, k, _ = inputs.make_qkv(w, 1, want_v=False)

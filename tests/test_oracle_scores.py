@@ -154,3 +154,42 @@ def test_row_ranges_add_up(oracle):
     # rows before t never reach token t
     late = oracle.head_colsums(q, k, 0, 30)
     assert (late[30:] == 0).all()
+
+
+# ------------------------------------------------------------ observation window
+def test_window_matches_brute_force_and_library(oracle):
+    """Only the last W query rows contribute: rows of the full attention matrix
+    are summed from S-W on (brute force), and a float64 library softmax agrees."""
+    g = torch.Generator().manual_seed(21)
+    S, W = 14, 5
+    q = torch.randn(1, 2, S, 8, generator=g)
+    k = torch.randn(1, 1, S, 8, generator=g)
+    _, _, A = library_colsums(q, k, 2)
+    want = A[..., S - W:, :].sum(dim=-2)
+    got = oracle.scores(q, k, reduce_groups=False, window=W).double()
+    assert torch.allclose(got, want, rtol=3e-7)
+    # every head's scores now total W; W >= S and W = 0 mean "all rows"
+    assert torch.allclose(got.sum(-1), torch.full((1, 2), float(W), dtype=torch.float64), rtol=1e-6)
+    full = oracle.scores(q, k, reduce_groups=False)
+    assert torch.equal(oracle.scores(q, k, reduce_groups=False, window=S), full)
+    assert torch.equal(oracle.scores(q, k, reduce_groups=False, window=S + 7), full)
+    # W = 1: the last row of the attention matrix itself
+    one = oracle.scores(q, k, reduce_groups=False, window=1).double()
+    assert torch.allclose(one, A[..., -1, :], rtol=3e-7)
+    # group reduction and the threaded path agree with it
+    gr = oracle.scores(q, k, reduce_groups=True, window=W).double()
+    assert torch.allclose(gr[:, 0], want.sum(1), rtol=3e-7)
+    assert torch.equal(oracle.scores(q, k, reduce_groups=True, window=W, threads=2).double(), gr)
+    # lse is reported for the window rows only
+    _, lse = oracle.scores(q, k, reduce_groups=False, want_lse=True, window=W)
+    assert (lse[..., : S - W] == 0).all() and (lse[..., S - W:] != 0).all()
+
+
+def test_maxpool_matches_library(oracle):
+    g = torch.Generator().manual_seed(22)
+    x = torch.randn(3, 4, 37, generator=g)
+    for kernel in (1, 3, 5, 7, 41):
+        want = torch.nn.functional.max_pool1d(x.view(12, 1, 37), kernel, stride=1, padding=kernel // 2).view(3, 4, 37)
+        assert torch.equal(oracle.maxpool(x, kernel), want)
+    # hand-worked: kernel 3 on 1 5 2 0 4 -> 5 5 5 4 4
+    assert oracle.maxpool(torch.tensor([[1.0, 5.0, 2.0, 0.0, 4.0]]), 3).tolist() == [[5.0, 5.0, 5.0, 4.0, 4.0]]
