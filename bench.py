@@ -41,13 +41,16 @@ def parse():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", type=int, default=3, help="workload id 1..5 (default: the S=16384 GQA layer)")
     ap.add_argument("--layers", type=int, default=0, help="resident layers (0: the workload's own count, capped at 32)")
+    ap.add_argument("--window", type=int, default=0,
+                    help="observation window W: only the last W queries score the tokens (SnapKV-style scoring)")
+    ap.add_argument("--pool", type=int, default=0, help="max-pool the scores with this odd kernel before selection")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     return ap.parse_args()
 
 
-def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer):
+def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer, row_begin=0, pool=0):
     """The oracle as it stands, single-threaded, on a bounded sample: every query
     row of ONE query head of layer 0 (1/Hq of the layer's score work), plus the
     full selection and gather of that layer.  Extrapolated to a whole layer."""
@@ -58,10 +61,12 @@ def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer):
     q_h = q0[0, 0].cpu()
     k_h = k0[0, 0].cpu()
     t0 = time.perf_counter()
-    oracle.head_colsums(q_h, k_h)
+    oracle.head_colsums(q_h, k_h, row_begin, w.S)
     t_head = time.perf_counter() - t0
     sc = sc_gpu_layer0.cpu()
     t0 = time.perf_counter()
+    if pool:
+        sc = oracle.maxpool(sc, pool)
     idx, _, _ = oracle.select(sc, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(layer))
     t_sel = time.perf_counter() - t0
     kc, vc = k0.cpu(), v0.cpu()
@@ -71,7 +76,7 @@ def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer):
     t_layer = t_head * w.Hq * w.B + t_sel + t_cmp
     return {
         "value": w.B * w.S / t_layer, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-        "sample": (f"layer 0: all {w.S} query rows of 1 of {w.B * w.Hq} (sequence, query head) pairs timed "
+        "sample": (f"layer 0: query rows {row_begin}..{w.S - 1} of 1 of {w.B * w.Hq} (sequence, query head) pairs timed "
                    f"({t_head:.2f} s) and scaled by {w.B * w.Hq}; selection ({t_sel:.3f} s) and gather "
                    f"({t_cmp:.3f} s) timed in full"),
         "seconds_per_layer_extrapolated": t_layer,
@@ -115,8 +120,13 @@ def main():
         layers.append(ent)
     torch.cuda.synchronize()
 
-    shape = kv.make_shape(layers[0]["q"], layers[0]["k"], w.reduce_groups)
+    W = args.window if 0 < args.window < w.S else 0
+    q_first = w.S - W if W else 0
+    pooled = torch.empty(w.B, Hs, w.S, dtype=torch.float32, device=dev) if args.pool else None
     lse = torch.empty(w.B, w.Hq, w.S, dtype=torch.float32, device=dev)
+    shape = kv.make_shape(layers[0]["q"], layers[0]["k"], w.reduce_groups, W)
+    lse_ws = torch.empty(max(kv.kvcrush_row_lse_workspace(shape), 16), dtype=torch.uint8, device=dev)
+    sc_ws = torch.empty(max(kv.kvcrush_scores_workspace(shape), 16), dtype=torch.uint8, device=dev)
     scores = torch.empty(w.B, Hs, w.S, dtype=torch.float32, device=dev)
     idx = torch.empty(w.B, w.budget, dtype=torch.int32, device=dev)
     sel_ws = torch.empty(kv.kvcrush_select_workspace(
@@ -129,14 +139,16 @@ def main():
         ent = layers[L]
         if ev:
             ev[0].record()
-        kv.kvcrush_row_lse(ent["q"], ent["k"], lse_out=lse)
+        kv.kvcrush_row_lse(ent["q"], ent["k"], lse_out=lse, window=W, workspace=lse_ws)
         if ev:
             ev[1].record()
-        kv.kvcrush_scores(ent["q"], ent["k"], w.reduce_groups, lse=lse, scores=scores)
+        kv.kvcrush_scores(ent["q"], ent["k"], w.reduce_groups, lse=lse, scores=scores, window=W, workspace=sc_ws)
         if ev:
             ev[2].record()
-        kv.kvcrush_select(scores, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(L), want_kind=False,
-                          idx=idx, workspace=sel_ws)
+        if pooled is not None:
+            kv.kvcrush_pool_scores(scores, args.pool, out=pooled)
+        kv.kvcrush_select(scores if pooled is None else pooled, w.budget, w.n_important, 0, w.anchor,
+                          inputs.anchor_seed(L), want_kind=False, idx=idx, workspace=sel_ws)
         if ev:
             ev[3].record()
         if w.paged:
@@ -171,7 +183,7 @@ def main():
     tokens = w.B * w.S
 
     # algorithmic work (what the method must compute / move, not what a kernel happens to do)
-    pairs = w.S * (w.S + 1) // 2                                  # causal (query, key) pairs per head
+    pairs = w.S * (w.S + 1) // 2 - q_first * (q_first + 1) // 2   # causal (query, key) pairs per head
     flop_pass = 2.0 * w.D * pairs * w.Hq * w.B                    # one sweep of Q K^T
     esz = 2 if w.dtype == "bf16" else 4
     bytes_sel = 4.0 * Hs * w.S * w.B + 4.0 * w.budget * w.B
@@ -179,9 +191,10 @@ def main():
     dom_name, dom_ms = ("colsum_kernel", t_col) if t_col >= t_lse else ("lse_kernel", t_lse)
     achieved = flop_pass / (dom_ms * 1e-3) / 1e12
     peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 157.3
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom_name)) if not W else None
     roofline = {
         "bound": "mfma", "kernel": dom_name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-        "frac": achieved / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom_name)),
+        "frac": achieved / peak, "traffic": traffic,
         "flop_per_launch": flop_pass, "avg_launch_ms": dom_ms,
     }
     stages = {
@@ -195,7 +208,7 @@ def main():
 
     # cheap sanity check of the last step's scores: every row totals (group size) x S
     tot = scores.double().sum(-1)
-    want = float((G if w.reduce_groups else 1) * w.S)
+    want = float((G if w.reduce_groups else 1) * (w.S - q_first))
     ok = bool(torch.allclose(tot, torch.full_like(tot, want), rtol=1e-4))
 
     out = {
@@ -206,14 +219,15 @@ def main():
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "S": w.S, "D": w.D,
                    "budget": w.budget, "n_important": w.n_important, "n_representative": w.n_rep,
                    "anchor": w.anchor, "reduce_groups": w.reduce_groups, "paged": w.paged,
-                   "resident_layers": n_layers},
+                   "resident_layers": n_layers, "obs_window": W, "pool_kernel": args.pool},
         "roofline": roofline, "stages": stages, "row_sum_check": ok,
     }
     if not args.no_cpu_baseline:
         # layer 0 again, so that its scores are the ones handed to the oracle's selection
         step(0)
         torch.cuda.synchronize()
-        out["cpu_baseline"] = cpu_baseline(w, layers[0]["q"], layers[0]["k"], layers[0]["v"], scores, 0)
+        out["cpu_baseline"] = cpu_baseline(w, layers[0]["q"], layers[0]["k"], layers[0]["v"], scores, 0,
+                                           q_first, args.pool)
     print(json.dumps(out), flush=True)
 
 

@@ -105,13 +105,25 @@ kvcrush_status kvcrush_scores(const kvcrush_shape* shape, const void* q, const v
 
 /* First half of stage 1 on its own: lse_out[b, h, i] = natural log of
  * sum_{j <= i} exp(Q_h[i] . K[j] / sqrt(D))  (the normaliser of row i of Alg. 1's
- * A_h), fp32 [B, Hq, S], fully overwritten (with shape->obs_window = W > 0 only the
- * rows i >= S - W are guaranteed to be written; the others are never read).  Passing the result as `lse` to
- * kvcrush_scores gives exactly what kvcrush_scores computes with lse = NULL;
- * callers whose attention kernel already produced these values skip this call.
- * shape->reduce_groups is ignored. */
+ * A_h), fp32 [B, Hq, S], fully overwritten (with shape->obs_window = W > 0 only
+ * the rows i >= S - W are guaranteed to be written; the others are never read).
+ * Callers whose attention kernel already produced these values skip this call
+ * and hand them to kvcrush_scores as `lse`.  shape->reduce_groups is ignored.
+ *
+ *   workspace  device scratch of kvcrush_row_lse_workspace(shape) bytes (may be 0),
+ *              16-byte aligned, or NULL.  With it, launches that would leave most
+ *              of the chip idle (short observation windows, few heads) cut each
+ *              row's keys into slices handled by separate workgroups and merge the
+ *              slices' sums afterwards; without it every row's keys are walked by
+ *              one workgroup.  Both are deterministic; they differ by rounding, and
+ *              kvcrush_scores with lse = NULL computes exactly what this call
+ *              computes WITH a workspace.
+ * Errors: as kvcrush_scores; KVCRUSH_ERR_WORKSPACE if a workspace is given but is
+ * too small or misaligned. */
+size_t kvcrush_row_lse_workspace(const kvcrush_shape* shape);
 kvcrush_status kvcrush_row_lse(const kvcrush_shape* shape, const void* q, const void* k,
-                               float* lse_out, void* hip_stream);
+                               float* lse_out, void* workspace, size_t workspace_bytes,
+                               void* hip_stream);
 
 /* Optional step between stages 1 and 2 for SnapKV-style selection (Sec. 2.3 /
  * 4.1.1: max pooling so that the neighbours of strong tokens are kept too):

@@ -19,7 +19,8 @@ ANCHORS = {"random": 0, "mean": 1, "alternating": 2, "explicit": 3}
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 
 EXPORTS = (
-    "kvcrush_scores_workspace", "kvcrush_scores", "kvcrush_row_lse", "kvcrush_pool_scores",
+    "kvcrush_scores_workspace", "kvcrush_scores", "kvcrush_row_lse_workspace", "kvcrush_row_lse",
+    "kvcrush_pool_scores",
     "kvcrush_select_workspace", "kvcrush_select", "kvcrush_compact", "kvcrush_status_string", "kvcrush_version",
 )
 
@@ -57,7 +58,9 @@ def load() -> ctypes.CDLL:
         L.kvcrush_scores_workspace.restype = sz
         L.kvcrush_scores.argtypes = [ctypes.POINTER(Shape), vp, vp, vp, vp, vp, sz, vp]
         L.kvcrush_scores.restype = ctypes.c_int
-        L.kvcrush_row_lse.argtypes = [ctypes.POINTER(Shape), vp, vp, vp, vp]
+        L.kvcrush_row_lse_workspace.argtypes = [ctypes.POINTER(Shape)]
+        L.kvcrush_row_lse_workspace.restype = sz
+        L.kvcrush_row_lse.argtypes = [ctypes.POINTER(Shape), vp, vp, vp, vp, sz, vp]
         L.kvcrush_row_lse.restype = ctypes.c_int
         L.kvcrush_pool_scores.argtypes = [i32, i32, i32, vp, vp, vp]
         L.kvcrush_pool_scores.restype = ctypes.c_int
@@ -143,14 +146,23 @@ def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=N
     return scores, workspace
 
 
-def kvcrush_row_lse(q, k, lse_out=None, stream=None, window=0):
+def kvcrush_row_lse_workspace(shape: Shape) -> int:
+    return int(load().kvcrush_row_lse_workspace(ctypes.byref(shape)))
+
+
+def kvcrush_row_lse(q, k, lse_out=None, stream=None, window=0, workspace="auto"):
     """q [B,Hq,S,D], k [B,Hkv,S,D] on the GPU -> natural-log row normalisers fp32 [B,Hq,S]
-    (with window = W > 0 only the rows of the last min(W, S) queries are defined)."""
+    (with window = W > 0 only the rows of the last min(W, S) queries are defined).
+    workspace: a uint8 tensor, None (run without scratch memory) or "auto" (allocate what
+    kvcrush_row_lse_workspace asks for)."""
     q, k = _dev(q, "q"), _dev(k, "k")
     shape = make_shape(q, k, False, window)
     if lse_out is None:
         lse_out = torch.empty(shape.B, shape.Hq, shape.S, dtype=torch.float32, device=q.device)
+    if isinstance(workspace, str):
+        workspace = torch.empty(max(kvcrush_row_lse_workspace(shape), 16), dtype=torch.uint8, device=q.device)
     st = load().kvcrush_row_lse(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(_dev(lse_out, "lse_out")),
+                                _ptr(workspace), 0 if workspace is None else workspace.numel(),
                                 _stream(stream))
     _check(st, "kvcrush_row_lse")
     return lse_out

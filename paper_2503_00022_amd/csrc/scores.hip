@@ -34,6 +34,8 @@
 // (so LDS latency is hidden behind a whole block of work) and by a slice of the
 // exp / max / sum work on the PREVIOUS block's accumulators (so the matrix core
 // and the VALU run side by side inside one wave).
+#include <algorithm>
+
 #include "common.h"
 
 namespace {
@@ -169,6 +171,10 @@ struct ScoreParams {
   int n_bh;          // (batch, head-group) pairs
   int chunk_tiles;   // pass B: query tiles per work piece
   int n_chunks;      // pass B: chunks along the query axis
+  int n_split;       // pass A: key slices per query block (1: the block's workgroup sees all its keys)
+  int split_q0;      // pass A, n_split > 1: first query row held by split_ml
+  int split_rows;    // pass A, n_split > 1: query rows held per head (S - split_q0)
+  float2* split_ml;  // pass A, n_split > 1: [B*Hq, n_split, split_rows] (reference, sum) pairs
   int q_first;       // first query row that contributes (0 unless an observation window is set)
   int tile0;         // pass B: q_first / kTile, the first query tile that is streamed
   float scale_log2;  // log2(e) / sqrt(D)
@@ -358,8 +364,10 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   const int tid = threadIdx.x, lane = kvc::lane_id(), wave = tid / KVC_WAVE;
   const int S = p.S;
   // heavy (late) query blocks first; same head group -> same blockIdx residue
-  const int blk = p.n_blocks - 1 - (int)(blockIdx.x / p.n_bh);
   const int bh = (int)(blockIdx.x % p.n_bh);
+  const int piece = (int)(blockIdx.x / p.n_bh);
+  const int slice = piece % p.n_split;  // key slice of the unmasked tiles; the last also takes the diagonal
+  const int blk = p.n_blocks - 1 - piece / p.n_split;
   const int hpw = p.heads_per_wg, qsub = kWaves / hpw;
   const int groups_per_b = p.Hq / hpw;
   const int b = bh / groups_per_b, hg = bh % groups_per_b;
@@ -377,8 +385,11 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
 
   const int wg_qmax = min(S, wg_q0 + 64 * qsub) - 1;
   const int n_tiles = wg_qmax / C::kTile + 1;
-  // tiles whose keys all precede every query of the workgroup
-  const int n_full = C::kPipelined ? wg_q0 / C::kTile : 0;
+  // tiles whose keys all precede every query of the workgroup; this workgroup's
+  // slice of them is [f_begin, f_begin + n_full)
+  const int n_before = C::kPipelined ? wg_q0 / C::kTile : 0;
+  const int f_begin = n_before * slice / p.n_split;
+  const int n_full = n_before * (slice + 1) / p.n_split - f_begin;
   const int off0 = lds_frag_offset0<C>(lane);
   uint32_t rel[C::kLoadsPerWave];
   tile_lane_offsets<C>(rel, wave, lane);
@@ -388,8 +399,8 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
 
   if constexpr (C::kPipelined) {
     if (n_full > 0) {
-      tile_load_async<C>(kh, 0, S, lds[0], rel, wave);
-      tile_load_async<C>(kh, min(1, n_full - 1) * C::kTile, S, lds[1], rel, wave);
+      tile_load_async<C>(kh, f_begin * C::kTile, S, lds[0], rel, wave);
+      tile_load_async<C>(kh, (f_begin + min(1, n_full - 1)) * C::kTile, S, lds[1], rel, wave);
       wait_async_loads();
       __syncthreads();
       // tile t lives in lds[t % 3]: while iteration `it` multiplies tiles it and
@@ -418,7 +429,7 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
       auto body = [&](auto P, int it) {
         constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
         constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
-        tile_load_async<C>(kh, min(it + 2, n_full - 1) * C::kTile, S, lds[ld], rel, wave);
+        tile_load_async<C>(kh, (f_begin + min(it + 2, n_full - 1)) * C::kTile, S, lds[ld], rel, wave);
         const bool live = it < n_full;
         float sum[2], mref[2];
         // block (it, sub 1) goes through the MFMAs while block (it, sub 0) is summed
@@ -441,14 +452,14 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
     }
   }
 
-  if (n_tiles > n_full) {
-    tile_load_async<C>(kh, n_full * C::kTile, S, lds[0], rel, wave);
+  if (n_tiles > n_before && slice == p.n_split - 1) {
+    tile_load_async<C>(kh, n_before * C::kTile, S, lds[0], rel, wave);
     wait_async_loads();
     __syncthreads();
-    for (int it = n_full; it < n_tiles; ++it) {
+    for (int it = n_before; it < n_tiles; ++it) {
       const int kt = it * C::kTile;
-      const char* buf = lds[(it - n_full) & 1];
-      if (it + 1 < n_tiles) tile_load_async<C>(kh, kt + C::kTile, S, lds[(it - n_full + 1) & 1], rel, wave);
+      const char* buf = lds[(it - n_before) & 1];
+      if (it + 1 < n_tiles) tile_load_async<C>(kh, kt + C::kTile, S, lds[(it - n_before + 1) & 1], rel, wave);
 #pragma unroll
       for (int ks = 0; ks < C::kTileSub; ++ks) {
         const int kmin = kt + 32 * ks, kmax = kmin + 31;
@@ -479,9 +490,30 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
     const float mt = fmaxf(m[ns], mo);
     const float lt = l[ns] * __builtin_amdgcn_exp2f(m[ns] - mt) + lo * __builtin_amdgcn_exp2f(mo - mt);
     const int qi = q0 + 32 * ns + (lane & 31);
-    if (lane < 32 && qi < S)
-      p.lse[((size_t)b * p.Hq + head) * S + qi] = (mt + __builtin_amdgcn_logf(lt)) * kLn2;
+    if (lane < 32 && qi < S) {
+      if (p.n_split == 1)
+        p.lse[((size_t)b * p.Hq + head) * S + qi] = (mt + __builtin_amdgcn_logf(lt)) * kLn2;
+      else
+        p.split_ml[(((size_t)b * p.Hq + head) * p.n_split + slice) * p.split_rows + (qi - p.split_q0)] =
+            make_float2(mt, lt);
+    }
   }
+}
+
+// lse of the rows whose keys were cut into slices: the slices' (reference, sum)
+// pairs stand for sum * 2^reference; added up in slice order.
+__global__ __launch_bounds__(256) void lse_combine_kernel(ScoreParams p) {
+  const int r = blockIdx.x * 256 + threadIdx.x, bh = blockIdx.y;  // bh = b * Hq + head
+  if (r >= p.split_rows) return;
+  const float2* src = p.split_ml + (size_t)bh * p.n_split * p.split_rows + r;
+  float mt = kNegBig;
+  for (int s = 0; s < p.n_split; ++s) mt = fmaxf(mt, src[(size_t)s * p.split_rows].x);
+  float lt = 0.0f;
+  for (int s = 0; s < p.n_split; ++s) {
+    const float2 ml = src[(size_t)s * p.split_rows];
+    lt += ml.y * __builtin_amdgcn_exp2f(ml.x - mt);
+  }
+  p.lse[(size_t)bh * p.S + p.split_q0 + r] = (mt + __builtin_amdgcn_logf(lt)) * kLn2;
 }
 
 // ------------------------------------------------------------- pass B ------
@@ -550,13 +582,16 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   zero_acc(col);
 
   auto q_head = [&](int head) { return p.q + ((size_t)b * p.Hq + head) * S * C::kRowBytes; };
+  const unsigned n_live = (unsigned)(S - p.q_first);
   auto load_lse = [&](int head, int qt) -> float {
     // +inf for rows past the end makes their probabilities exactly zero.  Branch
     // free (clamped address, select) so that the caller's loop body stays one
     // straight block; threads beyond the tile re-read its rows and are ignored.
     const int i = qt + (tid & (C::kTile - 1));
     const float v = lse_in[((size_t)b * p.Hq + head) * S + min(i, S - 1)] * kLog2e;
-    return (i < S && i >= p.q_first) ? v : INFINITY;  // rows outside the observation window: none
+    // one unsigned compare covers both ends: q_first <= i < S (rows before an
+    // observation window contribute nothing either)
+    return (unsigned)(i - p.q_first) < n_live ? v : INFINITY;
   };
 
   // ---- tiles after the diagonal: no mask, hand-pipelined
@@ -721,28 +756,75 @@ ColsumPlan colsum_plan(int S, int tile, int chunk_tiles_wanted, int q_first) {
 
 constexpr int kChunkQueries = 1152;  // queries per pass-B work piece: 18 tiles, a multiple of 3
 
-template <bool BF16, int D>
-kvcrush_status launch_lse(const ScoreParams& base, hipStream_t stream) {
-  ScoreParams a = base;
-  a.heads_per_wg = (a.G % 4 == 0) ? 4 : (a.G % 2 == 0 ? 2 : 1);
-  const int qsub = kWaves / a.heads_per_wg;
-  a.n_blocks = (a.S + 64 * qsub - 1) / (64 * qsub);
-  a.n_bh = a.B * (a.Hq / a.heads_per_wg);
-  // blocks are numbered from the end of the sequence: with an observation window only
-  // the blocks that reach into it are launched
-  const int launched = a.n_blocks - a.q_first / (64 * qsub);
-  hipLaunchKernelGGL((lse_kernel<BF16, D>), dim3((unsigned)(launched * a.n_bh)), dim3(kThreads), 0,
-                     stream, a);
-  return kvc::launch_status();
+// Launch shape of pass A.  Query blocks are numbered from the end of the
+// sequence: with an observation window only the blocks that reach into it are
+// launched.  When that leaves the chip short of workgroups (short windows, few
+// heads) and the caller gave scratch memory, the unmasked key tiles of every
+// block are cut into n_split slices, one workgroup each.
+struct LsePlan {
+  int heads_per_wg, n_blocks, n_bh, launched, n_split, split_q0, split_rows;
+};
+
+constexpr int kWantedWorkgroups = 1024;  // four per compute unit
+constexpr int kMinTilesPerSlice = 4;
+constexpr int kMaxSplit = 64;
+
+LsePlan lse_plan(int B, int Hq, int Hkv, int S, bool bf16, int q_first, bool may_split) {
+  LsePlan pl;
+  const int G = Hq / Hkv;
+  pl.heads_per_wg = (G % 4 == 0) ? 4 : (G % 2 == 0 ? 2 : 1);
+  const int qb = 64 * (kWaves / pl.heads_per_wg);  // query rows per workgroup
+  pl.n_blocks = (S + qb - 1) / qb;
+  pl.n_bh = B * (Hq / pl.heads_per_wg);
+  const int first_blk = q_first / qb;
+  pl.launched = pl.n_blocks - first_blk;
+  pl.n_split = 1;
+  pl.split_q0 = first_blk * qb;
+  pl.split_rows = S - pl.split_q0;
+  const long long wgs = (long long)pl.launched * pl.n_bh;
+  if (may_split && bf16 && wgs < kWantedWorkgroups) {
+    const int tiles_last = (pl.n_blocks - 1) * qb / 64;  // unmasked key tiles of the last block
+    int n = (int)((kWantedWorkgroups + wgs - 1) / wgs);
+    n = std::min(n, std::min(kMaxSplit, tiles_last / kMinTilesPerSlice));
+    pl.n_split = std::max(n, 1);
+  }
+  return pl;
+}
+
+size_t split_bytes(const LsePlan& pl, int B, int Hq) {
+  if (pl.n_split <= 1) return 0;
+  return kvc::align_up((size_t)B * Hq * pl.n_split * pl.split_rows * sizeof(float2), 256);
 }
 
 template <bool BF16, int D>
-kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, bool lse_only,
-                             hipStream_t stream) {
+kvcrush_status launch_lse(const ScoreParams& base, float2* split_ml, hipStream_t stream) {
+  ScoreParams a = base;
+  const LsePlan pl = lse_plan(a.B, a.Hq, a.Hkv, a.S, BF16, a.q_first, split_ml != nullptr);
+  a.heads_per_wg = pl.heads_per_wg;
+  a.n_blocks = pl.n_blocks;
+  a.n_bh = pl.n_bh;
+  a.n_split = pl.n_split;
+  a.split_q0 = pl.split_q0;
+  a.split_rows = pl.split_rows;
+  a.split_ml = split_ml;
+  hipLaunchKernelGGL((lse_kernel<BF16, D>), dim3((unsigned)(pl.launched * pl.n_split * pl.n_bh)),
+                     dim3(kThreads), 0, stream, a);
+  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  if (pl.n_split > 1) {
+    hipLaunchKernelGGL(lse_combine_kernel, dim3((pl.split_rows + 255) / 256, a.B * a.Hq), dim3(256), 0,
+                       stream, a);
+    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  }
+  return KVCRUSH_OK;
+}
+
+template <bool BF16, int D>
+kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, float2* split_ml,
+                             bool lse_only, hipStream_t stream) {
   using C = Cfg<BF16, D>;
   ScoreParams p = base;
   if (!lse_user) {
-    if (launch_lse<BF16, D>(p, stream) != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+    if (launch_lse<BF16, D>(p, split_ml, stream) != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
   if (lse_only) return KVCRUSH_OK;
   const ColsumPlan pl = colsum_plan(p.S, C::kTile, kChunkQueries / C::kTile, p.q_first);
@@ -780,6 +862,11 @@ size_t partial_bytes(const kvcrush_shape* s) {
   return kvc::align_up(rows * pl.n_kb * pl.n_chunks * kKeysPerWg * sizeof(float), 256);
 }
 
+size_t split_bytes(const kvcrush_shape* s) {
+  return split_bytes(lse_plan(s->B, s->Hq, s->Hkv, s->S, s->dtype == KVCRUSH_BF16, first_query(s), true),
+                     s->B, s->Hq);
+}
+
 bool shape_ok(const kvcrush_shape* s) {
   if (!s) return false;
   if (s->B < 1 || s->Hq < 1 || s->Hkv < 1 || s->S < 1 || s->D < 1) return false;
@@ -791,8 +878,8 @@ bool shape_ok(const kvcrush_shape* s) {
 }
 
 kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const void* k,
-                            const float* lse, float* lse_out, float* partial, float* scores,
-                            bool lse_only, hipStream_t stream) {
+                            const float* lse, float* lse_out, float* partial, float2* split_ml,
+                            float* scores, bool lse_only, hipStream_t stream) {
   const long long blocks_a = (long long)shape->B * shape->Hq * ((shape->S + 63) / 64);
   if (blocks_a > 0x3FFFFFFFll) return KVCRUSH_ERR_UNSUPPORTED;
   ScoreParams p;
@@ -812,21 +899,30 @@ kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const voi
   p.n_bh = 0;
   p.chunk_tiles = 1;
   p.n_chunks = 1;
+  p.n_split = 1;
+  p.split_q0 = 0;
+  p.split_rows = 0;
+  p.split_ml = nullptr;
   p.q_first = first_query(shape);
   p.tile0 = 0;
   p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)shape->D));
   const bool bf16 = shape->dtype == KVCRUSH_BF16;
-  if (bf16 && shape->D == 128) return launch_scores<true, 128>(p, lse, lse_only, stream);
-  if (bf16 && shape->D == 64) return launch_scores<true, 64>(p, lse, lse_only, stream);
-  if (!bf16 && shape->D == 128) return launch_scores<false, 128>(p, lse, lse_only, stream);
-  return launch_scores<false, 64>(p, lse, lse_only, stream);
+  if (bf16 && shape->D == 128) return launch_scores<true, 128>(p, lse, split_ml, lse_only, stream);
+  if (bf16 && shape->D == 64) return launch_scores<true, 64>(p, lse, split_ml, lse_only, stream);
+  if (!bf16 && shape->D == 128) return launch_scores<false, 128>(p, lse, split_ml, lse_only, stream);
+  return launch_scores<false, 64>(p, lse, split_ml, lse_only, stream);
 }
 
 }  // namespace
 
 extern "C" size_t kvcrush_scores_workspace(const kvcrush_shape* shape) {
   if (!shape_ok(shape)) return 0;
-  return lse_bytes(shape) + partial_bytes(shape);
+  return lse_bytes(shape) + partial_bytes(shape) + split_bytes(shape);
+}
+
+extern "C" size_t kvcrush_row_lse_workspace(const kvcrush_shape* shape) {
+  if (!shape_ok(shape)) return 0;
+  return split_bytes(shape);
 }
 
 extern "C" kvcrush_status kvcrush_scores(const kvcrush_shape* shape, const void* q, const void* k,
@@ -840,18 +936,27 @@ extern "C" kvcrush_status kvcrush_scores(const kvcrush_shape* shape, const void*
   if (!workspace || !kvc::aligned16(workspace) || workspace_bytes < kvcrush_scores_workspace(shape))
     return KVCRUSH_ERR_WORKSPACE;
   float* partial = (float*)((char*)workspace + lse_bytes(shape));
-  return scores_entry(shape, q, k, lse, (float*)workspace, partial, scores, false,
+  float2* split_ml =
+      split_bytes(shape) ? (float2*)((char*)workspace + lse_bytes(shape) + partial_bytes(shape)) : nullptr;
+  return scores_entry(shape, q, k, lse, (float*)workspace, partial, split_ml, scores, false,
                       (hipStream_t)hip_stream);
 }
 
 extern "C" kvcrush_status kvcrush_row_lse(const kvcrush_shape* shape, const void* q, const void* k,
-                                          float* lse_out, void* hip_stream) {
+                                          float* lse_out, void* workspace, size_t workspace_bytes,
+                                          void* hip_stream) {
   if (!shape_ok(shape)) return KVCRUSH_ERR_INVALID_ARG;
   if (shape->D != 64 && shape->D != 128) return KVCRUSH_ERR_UNSUPPORTED;
   if (!q || !k || !lse_out) return KVCRUSH_ERR_INVALID_ARG;
   if (!kvc::aligned16(q) || !kvc::aligned16(k) || !kvc::aligned16(lse_out))
     return KVCRUSH_ERR_INVALID_ARG;
-  return scores_entry(shape, q, k, nullptr, lse_out, nullptr, nullptr, true, (hipStream_t)hip_stream);
+  float2* split_ml = nullptr;
+  if (workspace) {
+    if (!kvc::aligned16(workspace) || workspace_bytes < split_bytes(shape)) return KVCRUSH_ERR_WORKSPACE;
+    if (split_bytes(shape)) split_ml = (float2*)workspace;
+  }
+  return scores_entry(shape, q, k, nullptr, lse_out, nullptr, split_ml, nullptr, true,
+                      (hipStream_t)hip_stream);
 }
 
 extern "C" const char* kvcrush_status_string(kvcrush_status status) {

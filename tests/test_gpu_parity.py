@@ -155,6 +155,11 @@ def check_scores(kv, oracle, w, seed, reduce_groups, check_lse=True):
     sc2, _ = kv.kvcrush_scores(q.cuda(), k.cuda(), reduce_groups, lse=ref_lse.cuda())
     torch.cuda.synchronize()
     assert rel_err(sc2, ref) <= SCORE_RTOL
+    # the normalisers on their own, with and without scratch memory for key slices
+    if check_lse:
+        for ws_arg in ("auto", None):
+            lse_alone = kv.kvcrush_row_lse(q.cuda(), k.cuda(), workspace=ws_arg).cpu()
+            assert (lse_alone.double() - ref_lse.double()).abs().max().item() < 1e-4
     return sc
 
 
@@ -244,6 +249,9 @@ def test_scores_observation_window(kv, oracle, B, Hq, Hkv, S, D, dtype, rg, W):
     # row_lse on its own writes the same window rows
     lse2 = kv.kvcrush_row_lse(q.cuda(), k.cuda(), window=W).cpu()
     assert torch.equal(lse2[..., S - Weff:], lse[..., S - Weff:])
+    # ... and without scratch memory (keys not cut into slices) agrees to rounding
+    lse3 = kv.kvcrush_row_lse(q.cuda(), k.cuda(), window=W, workspace=None).cpu()
+    assert (lse3[..., S - Weff:].double() - ref_lse[..., S - Weff:].double()).abs().max().item() < 1e-4
 
 
 @pytest.mark.parametrize("rows,S,kernel", [((2, 3), 37, 1), ((1, 8), 1000, 7), ((3,), 2048, 5), ((2, 2), 2049, 13),
