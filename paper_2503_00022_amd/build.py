@@ -39,5 +39,33 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
     return LIB_PATH
 
 
+def resource_usage(source: str) -> dict:
+    """Compile one csrc file (device code only, no output kept) and return the compiler's
+    per-kernel resource report: {mangled kernel name: {"VGPRs": n, "VGPRs Spill": n, ...}}.
+
+    The hand-scheduled score kernels sit close to the register file's limit; a spill there
+    costs a multiple of their run time, so the test suite checks this report."""
+    import re
+    import tempfile
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [hipcc, *flags, "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage", "-I",
+               os.path.join(ROOT, "include"), "-I", CSRC, "-c", os.path.join(CSRC, source), "-o",
+               os.path.join(tmp, "dev.o")]
+        out = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+    report, cur = {}, None
+    for line in out.splitlines():
+        m = re.search(r"remark:\s+(.+?):\s+(\S+)\s+\[-Rpass", line)
+        if not m:
+            continue
+        key, val = re.sub(r"\s*\[.*\]$", "", m.group(1).strip()), m.group(2)
+        if key == "Function Name":
+            cur = report.setdefault(val, {})
+        elif cur is not None and val.lstrip("-").isdigit():
+            cur[key] = int(val)
+    return report
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True, extra_flags=sys.argv[1:]))

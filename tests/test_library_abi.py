@@ -107,3 +107,17 @@ def test_compact_rejects_bad_arguments(lib):
     assert call(ko=ctypes.c_void_p(0x1008)) == binding.ERR_INVALID_ARG
     assert call(S=70, bt=FAKE, bs=16) == binding.ERR_INVALID_ARG  # S not a multiple of the block size
     assert call(budget=0, k=None, v=None, idx=None, ko=None, vo=None) == binding.OK   # nothing to do
+
+
+def test_score_kernels_keep_their_registers():
+    """The hand-scheduled kernels of stage 1 are built for two waves per SIMD with
+    no register spills; either one slipping costs a multiple of their run time
+    and no numerical test would notice."""
+    from paper_2503_00022_amd import build
+    report = build.resource_usage("scores.hip")
+    hot = {name: r for name, r in report.items() if "lse_kernel" in name or "colsum_kernel" in name}
+    assert len(hot) == 8, sorted(report)           # {lse, colsum} x {bf16, fp32} x {D = 64, 128}
+    for name, r in hot.items():
+        assert r["VGPRs Spill"] == 0 and r["SGPRs Spill"] == 0 and r["ScratchSize"] == 0, (name, r)
+        assert r["Occupancy"] >= 2, (name, r)
+        assert r["LDS Size"] <= 80 * 1024, (name, r)   # two workgroups share a compute unit's 160 KiB
