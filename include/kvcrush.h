@@ -155,6 +155,13 @@ typedef struct {
   int32_t n_important;     /* 0 <= n_important <= budget; the rest are representatives */
   int32_t bit_topk;        /* per-head top-k that sets a bit; 0 means `budget`         */
   int32_t anchor;          /* kvcrush_anchor                                           */
+  int32_t n_sink;          /* protected ends (the cache layout of Table 1: initial +   */
+  int32_t n_recent;        /* middle + recent tokens): the first n_sink and the last   */
+                           /* n_recent tokens are always kept, n_sink + n_recent <=    */
+                           /* budget.  The tokens between them are compressed to       */
+                           /* budget - n_sink - n_recent tokens exactly as a sequence  */
+                           /* of their own: n_important <= that number, bit_topk = 0   */
+                           /* means that number, bit_topk <= middle length.  0, 0: off */
   uint64_t anchor_seed;    /* RANDOM only                                              */
   const uint64_t* anchor_bits; /* EXPLICIT only: device [B, W], W = ceil(Hs / 64)      */
 } kvcrush_select_args;
@@ -162,8 +169,10 @@ typedef struct {
 size_t kvcrush_select_workspace(const kvcrush_select_args* args);
 /*   scores  [B, Hs, S] fp32
  *   idx     [B, budget] int32, ascending token positions
- *   kind    nullable [B, budget] uint8: 0 kept as important, 1 as representative
- *   bits    nullable [B, S, W] uint64: head r is bit r % 64 of word r / 64
+ *   kind    nullable [B, budget] uint8: 0 kept as important, 1 as representative,
+ *           2 protected (n_sink / n_recent)
+ *   bits    nullable [B, S, W] uint64: head r is bit r % 64 of word r / 64; zero
+ *           words for protected tokens
  */
 kvcrush_status kvcrush_select(const kvcrush_select_args* args, const float* scores, int32_t* idx,
                               uint8_t* kind, uint64_t* bits, void* workspace,

@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
         L.kvcrush_oracle_bits.argtypes = [i32, i32, i32, vp, vp]
         L.kvcrush_oracle_group.argtypes = [i32, i32, vp, vp, i32, i32, u64, i32, vp, vp, vp]
         L.kvcrush_oracle_select.argtypes = [i32] * 7 + [u64, vp, vp, vp, vp, vp]
+        L.kvcrush_oracle_select_protected.argtypes = [i32] * 9 + [u64, vp, vp, vp, vp, vp]
         L.kvcrush_oracle_compact.argtypes = [i32] * 6 + [vp, vp, vp, vp, i32, vp, vp]
         _lib = L
     return _lib
@@ -188,8 +189,10 @@ def group(Hs, bits_1seq, is_important, Br, anchor="alternating", anchor_seed=0, 
 
 
 def select(scores_t, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
-           anchor_bits=None):
-    """Stages 2-4.  scores_t [B,Hs,S] fp32 -> (idx int32 [B,budget], kind uint8, bits int64 [B,S,W])."""
+           anchor_bits=None, n_sink=0, n_recent=0):
+    """Stages 2-4.  scores_t [B,Hs,S] fp32 -> (idx int32 [B,budget], kind uint8, bits int64 [B,S,W]).
+    n_sink / n_recent: tokens at the two ends that are always kept (kind 2); the
+    middle is compressed to budget - n_sink - n_recent tokens."""
     sc = _cpu(scores_t.to(torch.float32))
     B, Hs, S = sc.shape
     W = words_for(Hs)
@@ -197,9 +200,14 @@ def select(scores_t, budget, n_important, bit_topk=0, anchor="alternating", anch
     kind = torch.empty(B, budget, dtype=torch.uint8)
     bw = torch.empty(B, S, W, dtype=torch.int64)
     ab = None if anchor_bits is None else _cpu(anchor_bits.to(torch.int64))
-    rc = lib().kvcrush_oracle_select(B, Hs, S, budget, n_important, bit_topk, ANCHORS[anchor],
-                                     ctypes.c_uint64(anchor_seed & (2**64 - 1)), _ptr(ab), _ptr(sc),
-                                     _ptr(idx), _ptr(kind), _ptr(bw))
+    if n_sink or n_recent:
+        rc = lib().kvcrush_oracle_select_protected(B, Hs, S, budget, n_important, bit_topk, n_sink, n_recent,
+                                                   ANCHORS[anchor], ctypes.c_uint64(anchor_seed & (2**64 - 1)),
+                                                   _ptr(ab), _ptr(sc), _ptr(idx), _ptr(kind), _ptr(bw))
+    else:
+        rc = lib().kvcrush_oracle_select(B, Hs, S, budget, n_important, bit_topk, ANCHORS[anchor],
+                                         ctypes.c_uint64(anchor_seed & (2**64 - 1)), _ptr(ab), _ptr(sc),
+                                         _ptr(idx), _ptr(kind), _ptr(bw))
     _check(rc, "select")
     return idx, kind, bw
 

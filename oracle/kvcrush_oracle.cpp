@@ -283,56 +283,87 @@ int kvcrush_oracle_group(int Hs, int S, const uint64_t* bits, const uint8_t* is_
   return 0;
 }
 
-// Stages 2-4 for a batch.  scores: [B,Hs,S] fp32.  Outputs: idx [B,budget]
-// ascending token ids; kind (nullable) [B,budget]: 0 = kept as important,
-// 1 = kept as representative; bits (nullable) [B,S,W].
+// Stages 2-4 for a batch, with protected ends (the cache layout of the paper's
+// lm-eval-harness runs, Table 1: initial tokens + compressed middle + recent
+// tokens).  scores: [B,Hs,S] fp32.  The first n_sink and the last n_recent
+// tokens are always kept; the middle tokens [n_sink, S - n_recent) are
+// compressed to budget - n_sink - n_recent tokens exactly as a sequence of their
+// own would be: per-row top-bit_topk (0 = the middle's budget), importance
+// top-n_important, grouping of the rest (Alg. 1, Alg. 2).
+// Outputs: idx [B,budget] ascending token ids; kind (nullable) [B,budget]:
+// 0 = kept as important, 1 = kept as representative, 2 = protected; bits
+// (nullable) [B,S,W], zero for protected tokens.
 // Token importance is the fp32 sum of the Hs rows taken in row order.
-int kvcrush_oracle_select(int B, int Hs, int S, int budget, int n_important, int bit_topk,
-                          int anchor_mode, uint64_t anchor_seed, const uint64_t* anchor_bits,
-                          const float* scores, int32_t* idx, uint8_t* kind, uint64_t* bits_out) {
-  if (B < 1 || Hs < 1 || S < 1 || budget < 0 || budget > S || n_important < 0 ||
-      n_important > budget)
+int kvcrush_oracle_select_protected(int B, int Hs, int S, int budget, int n_important,
+                                    int bit_topk, int n_sink, int n_recent, int anchor_mode,
+                                    uint64_t anchor_seed, const uint64_t* anchor_bits,
+                                    const float* scores, int32_t* idx, uint8_t* kind,
+                                    uint64_t* bits_out) {
+  if (B < 1 || Hs < 1 || S < 1 || budget < 0 || budget > S || n_sink < 0 || n_recent < 0 ||
+      n_sink + n_recent > budget)
     return 1;
-  const int kbit = bit_topk == 0 ? budget : bit_topk;
-  if (kbit < 0 || kbit > S) return 1;
-  const int W = words_for(Hs), Br = budget - n_important;
-  std::vector<uint64_t> bits((size_t)S * W);
-  std::vector<float> imp(S);
-  std::vector<uint8_t> is_imp(S), is_rep(S);
+  const int Sm = S - n_sink - n_recent;        // middle tokens
+  const int Bm = budget - n_sink - n_recent;   // their budget
+  if (n_important < 0 || n_important > Bm) return 1;
+  const int kbit = bit_topk == 0 ? Bm : bit_topk;
+  if (kbit < 0 || kbit > Sm) return 1;
+  const int W = words_for(Hs), Br = Bm - n_important;
+  std::vector<float> mid((size_t)Hs * (Sm > 0 ? Sm : 1));
+  std::vector<uint64_t> bits((size_t)(Sm > 0 ? Sm : 1) * W);
+  std::vector<float> imp(Sm > 0 ? Sm : 1);
+  std::vector<uint8_t> is_imp(Sm > 0 ? Sm : 1), is_rep(Sm > 0 ? Sm : 1);
   std::vector<int32_t> reps(Br > 0 ? Br : 1);
   for (int b = 0; b < B; ++b) {
     const float* sc = scores + (size_t)b * Hs * S;
-    int rc = kvcrush_oracle_bits(Hs, S, kbit, sc, bits.data());
-    if (rc) return rc;
-    for (int t = 0; t < S; ++t) {
-      float acc = 0.0f;
-      for (int r = 0; r < Hs; ++r) acc = acc + sc[(size_t)r * S + t];
-      imp[t] = acc;
-    }
     std::fill(is_imp.begin(), is_imp.end(), 0);
     std::fill(is_rep.begin(), is_rep.end(), 0);
-    for (int t : topk_indices(imp.data(), S, n_important)) is_imp[t] = 1;
-    rc = kvcrush_oracle_group(Hs, S, bits.data(), is_imp.data(), Br, anchor_mode, anchor_seed, b,
-                              anchor_bits ? anchor_bits + (size_t)b * W : nullptr, reps.data(),
-                              nullptr);
-    if (rc) return rc;
-    for (int j = 0; j < Br; ++j) {
-      if (is_imp[reps[j]] || is_rep[reps[j]]) return 2;  // must be disjoint and distinct
-      is_rep[reps[j]] = 1;
+    if (Sm > 0) {
+      for (int r = 0; r < Hs; ++r)
+        for (int u = 0; u < Sm; ++u) mid[(size_t)r * Sm + u] = sc[(size_t)r * S + n_sink + u];
+      int rc = kvcrush_oracle_bits(Hs, Sm, kbit, mid.data(), bits.data());
+      if (rc) return rc;
+      for (int u = 0; u < Sm; ++u) {
+        float acc = 0.0f;
+        for (int r = 0; r < Hs; ++r) acc = acc + mid[(size_t)r * Sm + u];
+        imp[u] = acc;
+      }
+      for (int u : topk_indices(imp.data(), Sm, n_important)) is_imp[u] = 1;
+      rc = kvcrush_oracle_group(Hs, Sm, bits.data(), is_imp.data(), Br, anchor_mode, anchor_seed, b,
+                                anchor_bits ? anchor_bits + (size_t)b * W : nullptr, reps.data(),
+                                nullptr);
+      if (rc) return rc;
+      for (int j = 0; j < Br; ++j) {
+        if (is_imp[reps[j]] || is_rep[reps[j]]) return 2;  // must be disjoint and distinct
+        is_rep[reps[j]] = 1;
+      }
     }
     int o = 0;
     for (int t = 0; t < S; ++t) {
-      if (is_imp[t] || is_rep[t]) {
+      const bool prot = t < n_sink || t >= S - n_recent;
+      const int u = t - n_sink;
+      if (prot || is_imp[u] || is_rep[u]) {
         if (o >= budget) return 2;
         idx[(size_t)b * budget + o] = t;
-        if (kind) kind[(size_t)b * budget + o] = is_rep[t] ? 1 : 0;
+        if (kind) kind[(size_t)b * budget + o] = prot ? 2 : (is_rep[u] ? 1 : 0);
         ++o;
       }
     }
     if (o != budget) return 2;
-    if (bits_out) std::memcpy(bits_out + (size_t)b * S * W, bits.data(), sizeof(uint64_t) * S * W);
+    if (bits_out) {
+      uint64_t* dst = bits_out + (size_t)b * S * W;
+      std::fill(dst, dst + (size_t)S * W, 0ull);
+      if (Sm > 0) std::memcpy(dst + (size_t)n_sink * W, bits.data(), sizeof(uint64_t) * Sm * W);
+    }
   }
   return 0;
+}
+
+// Stages 2-4 for a batch without protected tokens.
+int kvcrush_oracle_select(int B, int Hs, int S, int budget, int n_important, int bit_topk,
+                          int anchor_mode, uint64_t anchor_seed, const uint64_t* anchor_bits,
+                          const float* scores, int32_t* idx, uint8_t* kind, uint64_t* bits_out) {
+  return kvcrush_oracle_select_protected(B, Hs, S, budget, n_important, bit_topk, 0, 0, anchor_mode,
+                                         anchor_seed, anchor_bits, scores, idx, kind, bits_out);
 }
 
 // Stage 5.  Dense source: k, v [B,Hkv,S,D].  Paged source (block_table

@@ -37,7 +37,8 @@ class Shape(ctypes.Structure):
 
 
 class SelectArgs(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hs", "S", "budget", "n_important", "bit_topk", "anchor")] + [
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hs", "S", "budget", "n_important", "bit_topk", "anchor",
+                                                 "n_sink", "n_recent")] + [
         ("anchor_seed", ctypes.c_uint64), ("anchor_bits", ctypes.c_void_p)]
 
 
@@ -187,9 +188,10 @@ def lse_from_workspace(workspace: torch.Tensor, B: int, Hq: int, S: int) -> torc
 
 
 def make_select_args(B, Hs, S, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
-                     anchor_bits=None) -> SelectArgs:
+                     anchor_bits=None, n_sink=0, n_recent=0) -> SelectArgs:
     return SelectArgs(B, Hs, S, budget, n_important, bit_topk, ANCHORS[anchor] if isinstance(anchor, str) else anchor,
-                      anchor_seed & (2**64 - 1), None if anchor_bits is None else anchor_bits.data_ptr())
+                      n_sink, n_recent, anchor_seed & (2**64 - 1),
+                      None if anchor_bits is None else anchor_bits.data_ptr())
 
 
 def kvcrush_select_workspace(args: SelectArgs) -> int:
@@ -197,15 +199,18 @@ def kvcrush_select_workspace(args: SelectArgs) -> int:
 
 
 def kvcrush_select(scores, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
-                   anchor_bits=None, want_kind=True, want_bits=False, idx=None, workspace=None, stream=None):
-    """scores [B,Hs,S] fp32 on the GPU -> (idx int32 [B,budget], kind uint8 | None, bits int64 [B,S,W] | None)."""
+                   anchor_bits=None, want_kind=True, want_bits=False, idx=None, workspace=None, stream=None,
+                   n_sink=0, n_recent=0):
+    """scores [B,Hs,S] fp32 on the GPU -> (idx int32 [B,budget], kind uint8 | None, bits int64 [B,S,W] | None).
+    n_sink / n_recent tokens at the two ends are always kept; the rest of the budget goes to the middle."""
     scores = _dev(scores, "scores")
     if scores.dtype != torch.float32 or scores.dim() != 3:
         raise ValueError("scores must be fp32 [B,Hs,S]")
     B, Hs, S = scores.shape
     if anchor_bits is not None:
         anchor_bits = _dev(anchor_bits, "anchor_bits")
-    args = make_select_args(B, Hs, S, budget, n_important, bit_topk, anchor, anchor_seed, anchor_bits)
+    args = make_select_args(B, Hs, S, budget, n_important, bit_topk, anchor, anchor_seed, anchor_bits,
+                            n_sink, n_recent)
     dev = scores.device
     if idx is None:
         idx = torch.empty(B, budget, dtype=torch.int32, device=dev)

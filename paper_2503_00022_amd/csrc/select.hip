@@ -81,10 +81,11 @@ __device__ __forceinline__ void wave_chunk_range(int nw, int nwaves, int wave, i
 
 // ------------------------------------------------------------------ K1 ----
 struct TopkParams {
-  const float* scores;  // [B,Hs,S]
+  const float* scores;  // first selectable token of row 0 of sequence 0; rows are `ld` floats apart
   uint64_t* rowmask;    // [B,Hs+1,nw]; row Hs = important tokens
   uint32_t* keys_ws;    // [B,Hs+1,S] when the row does not fit LDS, else null
-  int Hs, S, nw, kbit, n_important;
+  int Hs, S, nw, kbit, n_important;  // S = selectable tokens per row (the middle, when ends are protected)
+  int ld;               // row stride of `scores` in floats (the full sequence length)
 };
 
 // Block-wide exclusive prefix sum of one int per thread, in thread order.
@@ -137,7 +138,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   auto key_put = [&](int t, uint32_t v) {
     if (KEYS_IN_LDS) lds_keys[t] = v; else gkeys[t] = v;
   };
-  const float* __restrict__ sc = p.scores + (size_t)b * Hs * S;
+  const float* __restrict__ sc = p.scores + (size_t)b * Hs * p.ld;
+  const size_t ld = (size_t)p.ld;
 
   for (int i = tid; i < kRadixBins; i += kSelThreads) hist[i] = 0;
   // keys: kBatch tokens per thread at a time so that their loads overlap
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int t = t0 + u * kSelThreads;
-        v[u] = t < S ? sc[(size_t)row * S + t] : 0.0f;
+        v[u] = t < S ? sc[(size_t)row * ld + t] : 0.0f;
       }
     } else {
       // token importance: fp32 sum of the score rows, taken in row order
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
           for (int u = 0; u < kBatch; ++u) {
             const int t = t0 + u * kSelThreads;
-            x[rr][u] = t < S ? sc[(size_t)(r + rr) * S + t] : 0.0f;
+            x[rr][u] = t < S ? sc[(size_t)(r + rr) * ld + t] : 0.0f;
           }
 #pragma unroll
         for (int rr = 0; rr < 8; ++rr)
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
           const int t = t0 + u * kSelThreads;
-          const float x = t < S ? sc[(size_t)r * S + t] : 0.0f;
+          const float x = t < S ? sc[(size_t)r * ld + t] : 0.0f;
           v[u] = v[u] + x;
         }
       }
@@ -280,7 +282,8 @@ constexpr uint32_t kNotGrouped = 0xFFFFFFFFu;
 
 struct GroupParams {
   const uint64_t* rowmask;      // [B,Hs+1,nw]
-  uint64_t* bits;               // [B,S,W]
+  uint64_t* bits;               // words of token 0 of sequence 0; sequences are bits_stride tokens apart
+  size_t bits_stride;
   uint32_t* dist_rank;          // [B,S]: distance | rank-in-wave << 8, or kNotGrouped
   int32_t* counts;              // [B,Hs+1,n_gw] tokens per (distance, global wave)
   int32_t* order;               // [B,S]: first N entries = grouped tokens by (d,t)
@@ -369,7 +372,7 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
     }
     const bool grouped = t < S && !((lds_words[Hs * kGsChunksPerWg + lc] >> lane) & 1ull);
     if (t < S) {
-      for (int w = 0; w < W; ++w) p.bits[((size_t)b * S + t) * W + w] = bw[w];
+      for (int w = 0; w < W; ++w) p.bits[((size_t)b * p.bits_stride + t) * W + w] = bw[w];
     }
     const uint32_t d = (uint32_t)(__popcll(bw[0] ^ anchor[0]) + __popcll(bw[1] ^ anchor[1]));
     const uint64_t peers = match_peers(d, p.dbits, grouped);
@@ -429,7 +432,8 @@ __global__ __launch_bounds__(kGsThreads) void group_scatter_kernel(GroupParams p
 
 // ------------------------------------------------------------------ K3 ----
 struct MedoidParams {
-  const uint64_t* bits;   // [B,S,W]
+  const uint64_t* bits;   // as in GroupParams
+  size_t bits_stride;
   const int32_t* order;   // [B,S]
   uint64_t* repmask;      // [B,nw]
   int Hs, S, nw, W, N, Br;
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(kMedoidThreads) void medoid_kernel(MedoidParams p) 
   const long long lo = (long long)j * p.N / p.Br, hi = (long long)(j + 1) * p.N / p.Br;
   const int n = (int)(hi - lo);
   const int32_t* order = p.order + (size_t)b * p.S + lo;
-  const uint64_t* bits = p.bits + (size_t)b * p.S * W;
+  const uint64_t* bits = p.bits + (size_t)b * p.bits_stride * W;
 
   // per-head member counts: lane l keeps heads l and l+64
   int cnt[kMaxW] = {0, 0};
@@ -500,7 +504,12 @@ struct EmitParams {
   int32_t* idx;                  // [B,budget]
   uint8_t* kind;                 // nullable
   size_t imp_stride;
-  int S, nw, budget;
+  int S, nw, budget;     // of the selectable (middle) tokens
+  // protected ends: tokens [0, n_sink) and the last n_recent of the S_full tokens are kept
+  // as they are; middle token u is token u + n_sink of the sequence
+  int n_sink, n_recent, S_full, budget_full;
+  uint64_t* bits_user;   // caller's bit words [B,S_full,W] or null: protected tokens get zero words
+  int W;
 };
 
 __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
@@ -510,6 +519,19 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
   const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
   const uint64_t* imp = p.impmask_base + (size_t)b * p.imp_stride;
   const uint64_t* rep = p.repmask + (size_t)b * p.nw;
+  int32_t* idx_out = p.idx + (size_t)b * p.budget_full;
+  uint8_t* kind_out = p.kind ? p.kind + (size_t)b * p.budget_full : nullptr;
+  for (int i = tid; i < p.n_sink + p.n_recent; i += kSelThreads) {
+    const bool head = i < p.n_sink;
+    const int o = head ? i : p.budget_full - p.n_recent + (i - p.n_sink);
+    const int t = head ? i : p.S_full - p.n_recent + (i - p.n_sink);
+    idx_out[o] = t;
+    if (kind_out) kind_out[o] = 2;
+    if (p.bits_user)
+      for (int w = 0; w < p.W; ++w) p.bits_user[((size_t)b * p.S_full + t) * p.W + w] = 0ull;
+  }
+  idx_out += p.n_sink;
+  if (kind_out) kind_out += p.n_sink;
   int carried = 0;  // indices emitted by earlier tiles of 1024 words
   for (int w0 = 0; w0 < p.nw; w0 += kSelThreads) {
     // one bitmap word per thread: count, prefix-sum, park in LDS
@@ -533,8 +555,8 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
       if ((kw >> lane) & 1ull) {
         const int o = sh_base[j] + __popcll(kw & lanemask_lt());
         if (o < p.budget) {  // always true for consistent masks; keeps stores in bounds regardless
-          p.idx[(size_t)b * p.budget + o] = (w0 + j) * 64 + lane;
-          if (p.kind) p.kind[(size_t)b * p.budget + o] = (uint8_t)((rj >> lane) & 1ull);
+          idx_out[o] = (w0 + j) * 64 + lane + p.n_sink;
+          if (kind_out) kind_out[o] = (uint8_t)((rj >> lane) & 1ull);
         }
       }
     }
@@ -585,11 +607,23 @@ bool select_args_ok(const kvcrush_select_args* a) {
   if (!a) return false;
   if (a->B < 1 || a->Hs < 1 || a->S < 1) return false;
   if (a->budget < 0 || a->budget > a->S) return false;
-  if (a->n_important < 0 || a->n_important > a->budget) return false;
-  if (a->bit_topk < 0 || a->bit_topk > a->S) return false;
+  if (a->n_sink < 0 || a->n_recent < 0 || (long long)a->n_sink + a->n_recent > a->budget) return false;
+  const int prot = a->n_sink + a->n_recent;
+  if (a->n_important < 0 || a->n_important > a->budget - prot) return false;
+  if (a->bit_topk < 0 || a->bit_topk > a->S - prot) return false;
   if (a->anchor < KVCRUSH_ANCHOR_RANDOM || a->anchor > KVCRUSH_ANCHOR_EXPLICIT) return false;
   if (a->anchor == KVCRUSH_ANCHOR_EXPLICIT && !a->anchor_bits) return false;
   return true;
+}
+
+// The selection proper runs on the tokens between the protected ends, as on a
+// sequence of its own.
+kvcrush_select_args middle_args(const kvcrush_select_args* a) {
+  kvcrush_select_args m = *a;
+  m.S = a->S - a->n_sink - a->n_recent;
+  m.budget = a->budget - a->n_sink - a->n_recent;
+  m.n_sink = m.n_recent = 0;
+  return m;
 }
 
 }  // namespace
@@ -597,7 +631,8 @@ bool select_args_ok(const kvcrush_select_args* a) {
 extern "C" size_t kvcrush_select_workspace(const kvcrush_select_args* args) {
   if (!select_args_ok(args) || args->Hs > kMaxHs) return 0;
   // sized for the case where the caller does not ask for the bit words
-  return select_layout(args, true).total;
+  const kvcrush_select_args m = middle_args(args);
+  return select_layout(&m, true).total;
 }
 
 extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const float* scores,
@@ -609,22 +644,26 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
   if (!scores || (!idx && args->budget > 0)) return KVCRUSH_ERR_INVALID_ARG;
   if (!kvc::aligned16(scores) || !kvc::aligned16(workspace) || (bits && !kvc::aligned16(bits)))
     return KVCRUSH_ERR_INVALID_ARG;
-  const SelectLayout L = select_layout(args, bits == nullptr);
-  if (!workspace || workspace_bytes < L.total) return KVCRUSH_ERR_WORKSPACE;
+  const kvcrush_select_args mid = middle_args(args);
+  const SelectLayout L = select_layout(&mid, bits == nullptr);
+  if (L.total > 0 && (!workspace || workspace_bytes < L.total)) return KVCRUSH_ERR_WORKSPACE;
 
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  const int B = args->B, Hs = args->Hs, S = args->S;
-  const int Br = args->budget - args->n_important, N = S - args->n_important;
-  const int kbit = args->bit_topk == 0 ? args->budget : args->bit_topk;
+  // from here on S, budget are those of the middle; S_full is the row length
+  const int B = args->B, Hs = args->Hs, S = mid.S, S_full = args->S, budget = mid.budget;
+  const int Br = budget - args->n_important, N = S - args->n_important;
+  const int kbit = args->bit_topk == 0 ? budget : args->bit_topk;
   uint64_t* rowmask = (uint64_t*)(ws + L.rowmask);
   uint64_t* repmask = (uint64_t*)(ws + L.repmask);
   int32_t* order = (int32_t*)(ws + L.order);
-  uint64_t* bits_buf = bits ? bits : (uint64_t*)(ws + L.bits);
+  uint64_t* bits_buf = bits ? bits + (size_t)args->n_sink * L.W : (uint64_t*)(ws + L.bits);
+  const size_t bits_stride = bits ? (size_t)S_full : (size_t)S;
 
-  {
+  if (S > 0) {
     TopkParams p;
-    p.scores = scores;
+    p.scores = scores + args->n_sink;
+    p.ld = S_full;
     p.rowmask = rowmask;
     p.keys_ws = L.keys_in_lds ? nullptr : (uint32_t*)(ws + L.keys);
     p.Hs = Hs;
@@ -644,10 +683,11 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
       hipLaunchKernelGGL(topk_mask_kernel<false>, dim3(Hs + 1, B), dim3(kSelThreads), 0, stream, p);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
-  {
+  if (S > 0) {
     GroupParams p;
     p.rowmask = rowmask;
     p.bits = bits_buf;
+    p.bits_stride = bits_stride;
     p.dist_rank = (uint32_t*)(ws + L.dist_rank);
     p.counts = (int32_t*)(ws + L.counts);
     p.order = order;
@@ -680,6 +720,7 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
   if (Br > 0) {
     MedoidParams p;
     p.bits = bits_buf;
+    p.bits_stride = bits_stride;
     p.order = order;
     p.repmask = repmask;
     p.Hs = Hs;
@@ -701,7 +742,13 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
     p.imp_stride = (size_t)(Hs + 1) * L.nw;
     p.S = S;
     p.nw = L.nw;
-    p.budget = args->budget;
+    p.budget = budget;
+    p.n_sink = args->n_sink;
+    p.n_recent = args->n_recent;
+    p.S_full = S_full;
+    p.budget_full = args->budget;
+    p.bits_user = bits;
+    p.W = L.W;
     hipLaunchKernelGGL(emit_kernel, dim3(B), dim3(kSelThreads), 0, stream, p);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }

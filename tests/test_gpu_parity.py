@@ -72,20 +72,57 @@ def test_compact_paged(kv, oracle, B, Hkv, S, D, budget, bs):
 
 
 # --------------------------------------------------------------- stages 2-4
-def check_select(kv, oracle, sc, budget, n_imp, kbit, anchor, seed=0, anchor_bits=None):
+def check_select(kv, oracle, sc, budget, n_imp, kbit, anchor, seed=0, anchor_bits=None, n_sink=0, n_recent=0):
+    ends = dict(n_sink=n_sink, n_recent=n_recent)
     idx, kind, bits = kv.kvcrush_select(sc.cuda(), budget, n_imp, kbit, anchor, seed,
-                                        None if anchor_bits is None else anchor_bits.cuda(), want_bits=True)
+                                        None if anchor_bits is None else anchor_bits.cuda(), want_bits=True, **ends)
     torch.cuda.synchronize()
-    ridx, rkind, rbits = oracle.select(sc, budget, n_imp, kbit, anchor, seed, anchor_bits)
+    ridx, rkind, rbits = oracle.select(sc, budget, n_imp, kbit, anchor, seed, anchor_bits, **ends)
     assert torch.equal(bits.cpu(), rbits), "head-behaviour bit words differ"
     assert torch.equal(idx.cpu(), ridx), "retained indices differ"
     assert torch.equal(kind.cpu(), rkind), "important/representative labels differ"
     # same result when the caller does not ask for kinds or bits (bits then live in the workspace)
     idx2, kind2, bits2 = kv.kvcrush_select(sc.cuda(), budget, n_imp, kbit, anchor, seed,
                                            None if anchor_bits is None else anchor_bits.cuda(),
-                                           want_kind=False, want_bits=False)
+                                           want_kind=False, want_bits=False, **ends)
     torch.cuda.synchronize()
     assert kind2 is None and bits2 is None and torch.equal(idx2.cpu(), ridx)
+
+
+@pytest.mark.parametrize("B,Hs,S,budget,n_imp,kbit,sink,recent,anchor", [
+    (1, 8, 2000, 672, 384, 0, 32, 128, "alternating"),   # 32 initial + 512 middle + 128 recent (Table 1's layout)
+    (2, 8, 1000, 300, 100, 0, 5, 17, "mean"),            # ragged ends: the middle starts off every alignment
+    (1, 32, 4096, 1024, 512, 0, 4, 64, "random"),
+    (2, 100, 700, 200, 50, 300, 3, 0, "mean"),           # sink only, two bit words, kbit > half the middle
+    (1, 8, 333, 100, 0, 0, 0, 33, "alternating"),        # recent only, nothing important
+    (1, 8, 16384, 4096, 2928, 0, 32, 128, "mean"),       # config-3 sizes
+    (1, 4, 40000, 5000, 3000, 0, 64, 500, "random"),     # keys through the workspace
+    (1, 8, 300, 300, 100, 0, 10, 20, "alternating"),     # budget == S
+    (2, 8, 300, 30, 0, 0, 10, 20, "alternating"),        # the middle is dropped entirely
+    (1, 8, 64, 64, 0, 0, 40, 24, "random"),              # there is no middle
+    (1, 8, 65, 65, 0, 0, 1, 0, "alternating"),
+])
+def test_select_protected_ends(kv, oracle, B, Hs, S, budget, n_imp, kbit, sink, recent, anchor):
+    say(f"select with protected ends B={B} Hs={Hs} S={S} budget={budget} n_imp={n_imp} sink={sink} recent={recent}")
+    sc = inputs.make_scores(B, Hs, S, seed=S + sink + recent, ties=True)
+    check_select(kv, oracle, sc, budget, n_imp, kbit, anchor, seed=11, n_sink=sink, n_recent=recent)
+
+
+def test_per_layer_budgets_share_one_workspace(kv, oracle):
+    """A pyramid of budgets over the layers (the PyramidKV pairing): budget and split
+    are per-call arguments and the workspace sized for one call serves them all."""
+    say("per-layer budgets, one workspace")
+    B, Hs, S = 2, 8, 3000
+    ws = torch.empty(kv.kvcrush_select_workspace(kv.make_select_args(B, Hs, S, S, S)), dtype=torch.uint8,
+                     device="cuda")
+    for layer, budget in enumerate([1200, 900, 600, 300, 64]):
+        need = kv.kvcrush_select_workspace(kv.make_select_args(B, Hs, S, budget, budget * 3 // 4))
+        assert need <= ws.numel()
+        sc = inputs.make_scores(B, Hs, S, seed=100 + layer, ties=True)
+        idx, kind, _ = kv.kvcrush_select(sc.cuda(), budget, budget * 3 // 4, 0, "mean", layer, workspace=ws)
+        torch.cuda.synchronize()
+        ridx, rkind, _ = oracle.select(sc, budget, budget * 3 // 4, 0, "mean", layer)
+        assert torch.equal(idx.cpu(), ridx) and torch.equal(kind.cpu(), rkind)
 
 
 @pytest.mark.parametrize("B,Hs,S,budget,n_imp,kbit,anchor,ties", [

@@ -121,3 +121,47 @@ def test_score_kernels_keep_their_registers():
         assert r["VGPRs Spill"] == 0 and r["SGPRs Spill"] == 0 and r["ScratchSize"] == 0, (name, r)
         assert r["Occupancy"] >= 2, (name, r)
         assert r["LDS Size"] <= 80 * 1024, (name, r)   # two workgroups share a compute unit's 160 KiB
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes mirrors of the header's structs have the C compiler's sizes and
+    field offsets (a C program that includes the header prints them)."""
+    import subprocess
+    structs = {"kvcrush_shape": binding.Shape, "kvcrush_select_args": binding.SelectArgs}
+    lines = []
+    for cname, cls in structs.items():
+        lines.append(f'printf("{cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in cls._fields_:
+            lines.append(f'printf("{cname}.{fname} %zu\\n", offsetof({cname}, {fname}));')
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "kvcrush.h"\nint main(void) {\n'
+                   + "\n".join(lines) + "\nreturn 0; }\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    out = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, cls in structs.items():
+        assert int(out[cname]) == ctypes.sizeof(cls)
+        for fname, _ in cls._fields_:
+            assert int(out[f"{cname}.{fname}"]) == getattr(cls, fname).offset, (cname, fname)
+    # and the header names no field the mirror lacks
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    for cname, cls in structs.items():
+        body = re.search(r"typedef struct \{([^{}]*)\} " + cname + ";", text).group(1)
+        names = re.findall(r"(\w+)\s*[,;]", body)
+        assert names == [f for f, _ in cls._fields_], (cname, names)
+
+
+def test_select_protected_ends_validation(lib):
+    def ws(**kw):
+        d = dict(B=1, Hs=8, S=1000, budget=200, n_important=100, n_sink=32, n_recent=64)
+        d.update(kw)
+        return binding.kvcrush_select_workspace(binding.make_select_args(
+            d["B"], d["Hs"], d["S"], d["budget"], d["n_important"], n_sink=d["n_sink"], n_recent=d["n_recent"]))
+    assert ws() > 0
+    assert ws(n_sink=150, n_recent=51) == 0        # protected tokens exceed the budget
+    assert ws(n_important=105) == 0                # more important tokens than the middle's budget
+    assert ws(n_sink=-1) == 0
+    assert ws(n_sink=100, n_recent=100, n_important=0) > 0   # budget == protected: legal
+    # the workspace is sized by the middle, which is never longer than the sequence
+    assert ws() <= ws(n_sink=0, n_recent=0)

@@ -303,3 +303,58 @@ def test_mean_anchor_is_zero_under_2x_compression(oracle):
     imp[idx[0][kind[0] == 0].long()] = 1
     _, a = oracle.group(8, bw[0], imp, 16, anchor="mean")
     assert words_to_int(a) == 0
+
+
+# ---------------------------------------------------------------- protected ends
+@pytest.mark.parametrize("B,Hs,S,budget,n_imp,kbit,sink,recent,anchor", [
+    (2, 8, 150, 60, 20, 0, 4, 16, "alternating"),
+    (1, 8, 672, 168, 96, 0, 32, 8, "random"),       # initial + middle + recent, as in Table 1's layout
+    (2, 5, 90, 50, 10, 30, 7, 0, "mean"),           # sink only; kbit > half of the middle
+    (1, 4, 64, 30, 0, 0, 0, 9, "alternating"),      # recent only, nothing important
+    (1, 3, 40, 40, 5, 0, 10, 10, "random"),         # budget == S: identity
+    (1, 3, 40, 12, 0, 0, 5, 7, "alternating"),      # budget == protected: the middle is dropped
+    (1, 3, 20, 20, 0, 0, 12, 8, "alternating"),     # no middle at all
+])
+def test_protected_ends_match_brute_force_on_the_middle(oracle, B, Hs, S, budget, n_imp, kbit, sink, recent, anchor):
+    """Tokens at the two ends are always kept; the middle is compressed as a
+    sequence of its own (independent Python implementation on the sliced scores)."""
+    sc = inputs.make_scores(B, Hs, S, seed=S + sink, ties=True)
+    idx, kind, bw = oracle.select(sc, budget, n_imp, kbit, anchor, anchor_seed=9, n_sink=sink, n_recent=recent)
+    Sm, Bm = S - sink - recent, budget - sink - recent
+    W = (Hs + 63) // 64
+    for b in range(B):
+        def anchor_fn(bits, important):
+            if anchor == "alternating":
+                return alternating(Hs)
+            if anchor == "random":
+                z = oracle.splitmix64(9 + b, W)
+                return sum(z[w] << (64 * w) for w in range(W)) & ((1 << Hs) - 1)
+            disc = [t for t in range(Sm) if t not in important]
+            return sum(1 << r for r in range(Hs) if 2 * sum((bits[t] >> r) & 1 for t in disc) > len(disc))
+        got_idx, got_kind = idx[b].tolist(), kind[b].tolist()
+        want_idx = list(range(sink))
+        want_kind = [2] * sink
+        want_bits = [0] * S
+        if Sm > 0:
+            mid = sc[b, :, sink:S - recent].tolist()
+            m_idx, m_kind, m_bits = py_select(mid, Bm, n_imp, kbit or Bm, anchor_fn)
+            want_idx += [u + sink for u in m_idx]
+            want_kind += m_kind
+            want_bits[sink:S - recent] = m_bits
+        want_idx += list(range(S - recent, S))
+        want_kind += [2] * recent
+        assert got_idx == want_idx and got_kind == want_kind
+        assert [words_to_int(bw[b, t]) for t in range(S)] == want_bits
+        assert len(got_idx) == budget and all(x < y for x, y in zip(got_idx, got_idx[1:]))
+    # no protected tokens: the plain selection, bit for bit
+    plain = oracle.select(sc, budget, min(n_imp, budget), 0, anchor, anchor_seed=9)
+    same = oracle.select(sc, budget, min(n_imp, budget), 0, anchor, anchor_seed=9, n_sink=0, n_recent=0)
+    assert all(torch.equal(x, y) for x, y in zip(plain, same))
+
+
+def test_protected_ends_reject_inconsistent_arguments(oracle):
+    sc = inputs.make_scores(1, 4, 50, seed=3)
+    for kw in (dict(n_sink=20, n_recent=20), dict(n_sink=-1), dict(n_sink=5, n_recent=5, n_important=25)):
+        n_imp = kw.pop("n_important", 5)
+        with pytest.raises(RuntimeError):
+            oracle.select(sc, 30, n_imp, 0, "alternating", **kw)
