@@ -45,6 +45,8 @@ def lib() -> ctypes.CDLL:
         L.kvcrush_oracle_head_colsums.argtypes = [i32, i32, i32, vp, vp, i32, i32, vp, vp]
         L.kvcrush_oracle_scores.argtypes = [i32] * 8 + [vp] * 4
         L.kvcrush_oracle_maxpool.argtypes = [i32, i32, i32, vp, vp]
+        L.kvcrush_oracle_scores_append.argtypes = [i32] * 8 + [vp, vp, vp]
+        L.kvcrush_oracle_compact_cache.argtypes = [i32] * 8 + [vp] * 7
         L.kvcrush_oracle_topk.argtypes = [vp, i32, i32, vp]
         L.kvcrush_oracle_splitmix64.argtypes = [u64, i32, vp]
         L.kvcrush_oracle_splitmix64.restype = None
@@ -138,6 +140,34 @@ def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1, window: 
     else:
         out = c.to(torch.float32)
     return (out, lse) if want_lse else out
+
+
+def scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool):
+    """One decoding step, in place on scores_cache [B,Hs,capacity] (fp32): the new token's
+    queries q_new [B,Hq,D] attend to the first S tokens of k_cache [B,Hkv,capacity,D]."""
+    q_new, k_cache = _cpu(q_new), _cpu(k_cache)
+    assert scores_cache.device.type == "cpu" and scores_cache.is_contiguous() and scores_cache.dtype == torch.float32
+    B, Hq, D = q_new.shape
+    Hkv, cap = k_cache.shape[1], k_cache.shape[2]
+    assert scores_cache.shape == (B, Hkv if reduce_groups else Hq, cap)
+    rc = lib().kvcrush_oracle_scores_append(B, Hq, Hkv, S, cap, D, _dtype_code(q_new), int(reduce_groups),
+                                            _ptr(q_new), _ptr(k_cache), _ptr(scores_cache))
+    _check(rc, "scores_append")
+    return scores_cache
+
+
+def compact_cache(k, v, scores_t, idx, k_out, v_out, scores_out):
+    """Eviction on capacity-strided caches: k, v [B,Hkv,cap_src,D], scores_t [B,Hs,cap_src] ->
+    first idx.shape[1] tokens of k_out, v_out [B,Hkv,cap_dst,D], scores_out [B,Hs,cap_dst] (in place)."""
+    k, v, sc, idx = _cpu(k), _cpu(v), _cpu(scores_t), _cpu(idx.to(torch.int32))
+    for t in (k_out, v_out, scores_out):
+        assert t.device.type == "cpu" and t.is_contiguous()
+    B, Hkv, cap_src, D = k.shape
+    rc = lib().kvcrush_oracle_compact_cache(B, Hkv, sc.shape[1], D, _dtype_code(k), cap_src, k_out.shape[2],
+                                            idx.shape[1], _ptr(k), _ptr(v), _ptr(sc), _ptr(idx), _ptr(k_out),
+                                            _ptr(v_out), _ptr(scores_out))
+    _check(rc, "compact_cache")
+    return k_out, v_out, scores_out
 
 
 def maxpool(scores_t, kernel: int):

@@ -164,6 +164,75 @@ int kvcrush_oracle_scores(int B, int Hq, int Hkv, int S, int D, int dtype, int r
   return 0;
 }
 
+// One decoding step (Sec. 1: the cache grows by one entry per generated token;
+// the H2O importance keeps accumulating over decoding steps, Sec. 2.3).  The
+// new token's query of every head attends to the S cached keys, its own (the
+// last, position S-1) included; the probabilities are added to the running
+// scores.  q_new: [B,Hq,D]; k: [B,Hkv,capacity,D] of which the first S tokens
+// are valid; scores: [B,Hs,capacity], updated in place for t < S-1, position
+// S-1 (the new token, which had no score yet) is overwritten; entries at or
+// beyond S are not touched.  With reduce_groups the probabilities of a
+// group's heads are summed in double, heads ascending, before the single
+// rounding to float of old + sum.
+int kvcrush_oracle_scores_append(int B, int Hq, int Hkv, int S, int capacity, int D, int dtype,
+                                 int reduce_groups, const void* q_new, const void* k,
+                                 float* scores) {
+  if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || capacity < S || D < 1) return 1;
+  const int G = Hq / Hkv, Hs = reduce_groups ? Hkv : Hq;
+  const double inv_sqrt_d = 1.0 / std::sqrt((double)D);
+  std::vector<double> logit(S), add(S);
+  for (int b = 0; b < B; ++b)
+    for (int r = 0; r < Hs; ++r) {
+      std::fill(add.begin(), add.end(), 0.0);
+      const int h0 = reduce_groups ? r * G : r, h1 = reduce_groups ? h0 + G : h0 + 1;
+      for (int h = h0; h < h1; ++h) {
+        const int g = h / G;
+        double m = -INFINITY;
+        for (int j = 0; j < S; ++j) {
+          double dot = 0.0;
+          for (int d = 0; d < D; ++d)
+            dot += widen(q_new, ((size_t)b * Hq + h) * D + d, dtype) *
+                   widen(k, (((size_t)b * Hkv + g) * capacity + j) * D + d, dtype);
+          logit[j] = dot * inv_sqrt_d;
+          if (logit[j] > m) m = logit[j];
+        }
+        double L = 0.0;
+        for (int j = 0; j < S; ++j) L += std::exp(logit[j] - m);
+        for (int j = 0; j < S; ++j) add[j] += std::exp(logit[j] - m) / L;
+      }
+      float* row = scores + ((size_t)b * Hs + r) * capacity;
+      for (int j = 0; j < S; ++j) row[j] = (float)((j == S - 1 ? 0.0 : (double)row[j]) + add[j]);
+    }
+  return 0;
+}
+
+// Eviction during decoding: the kept tokens of a capacity-strided cache and
+// their running scores move to the front of another one.
+// k, v: [B,Hkv,cap_src,D]; scores: [B,Hs,cap_src]; idx: [B,budget];
+// k_out, v_out: [B,Hkv,cap_dst,D]; scores_out: [B,Hs,cap_dst].  Only the first
+// `budget` tokens of every output row are written.
+int kvcrush_oracle_compact_cache(int B, int Hkv, int Hs, int D, int dtype, int cap_src, int cap_dst,
+                                 int budget, const void* k, const void* v, const float* scores,
+                                 const int32_t* idx, void* k_out, void* v_out, float* scores_out) {
+  if (B < 1 || Hkv < 1 || Hs < 1 || D < 1 || budget < 0 || budget > cap_src || budget > cap_dst)
+    return 1;
+  const size_t row = (size_t)D * elem_size(dtype);
+  for (int b = 0; b < B; ++b)
+    for (int j = 0; j < budget; ++j) {
+      const int t = idx[(size_t)b * budget + j];
+      if (t < 0 || t >= cap_src) return 2;
+      for (int h = 0; h < Hkv; ++h) {
+        const size_t src = (((size_t)b * Hkv + h) * cap_src + t) * row;
+        const size_t dst = (((size_t)b * Hkv + h) * cap_dst + j) * row;
+        std::memcpy((char*)k_out + dst, (const char*)k + src, row);
+        std::memcpy((char*)v_out + dst, (const char*)v + src, row);
+      }
+      for (int r = 0; r < Hs; ++r)
+        scores_out[((size_t)b * Hs + r) * cap_dst + j] = scores[((size_t)b * Hs + r) * cap_src + t];
+    }
+  return 0;
+}
+
 // 1-D max pooling along the token axis, window `kernel` (odd), centred, the
 // sequence ends padded with -inf (the pooling step by which SnapKV also keeps
 // the neighbours of strong tokens, Sec. 2.3 / 4.1.1).  in, out: [rows, S].
