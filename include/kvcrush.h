@@ -155,6 +155,8 @@ typedef struct {
   int32_t n_important;     /* 0 <= n_important <= budget; the rest are representatives */
   int32_t bit_topk;        /* per-head top-k that sets a bit; 0 means `budget`         */
   int32_t anchor;          /* kvcrush_anchor                                           */
+  int32_t score_stride;    /* floats between consecutive score rows; 0 means S (rows of */
+                           /* a capacity-strided decoding cache: capacity)              */
   int32_t n_sink;          /* protected ends (the cache layout of Table 1: initial +   */
   int32_t n_recent;        /* middle + recent tokens): the first n_sink and the last   */
                            /* n_recent tokens are always kept, n_sink + n_recent <=    */
@@ -167,7 +169,7 @@ typedef struct {
 } kvcrush_select_args;
 
 size_t kvcrush_select_workspace(const kvcrush_select_args* args);
-/*   scores  [B, Hs, S] fp32
+/*   scores  [B, Hs, S] fp32 (rows score_stride floats apart when that is set)
  *   idx     [B, budget] int32, ascending token positions
  *   kind    nullable [B, budget] uint8: 0 kept as important, 1 as representative,
  *           2 protected (n_sink / n_recent)
@@ -196,6 +198,46 @@ kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int32_t D, int
                                int32_t budget, const void* k, const void* v, const int32_t* idx,
                                const int32_t* block_table, int32_t block_size, void* k_out,
                                void* v_out, void* hip_stream);
+
+/* ------------------------------------------------------------- decoding --
+ * The cache of a sequence that is being generated grows by one token per step
+ * (Sec. 1) and the accumulated-attention importance keeps accumulating over
+ * those steps (H2O as summarised in Sec. 2.3).  Caches used here are
+ * capacity-strided: k, v [B, Hkv, capacity, D] and scores [B, Hs, capacity], of
+ * which the first S tokens are valid.
+ *
+ * kvcrush_scores_append: one decoding step.  shape->S counts the new token (its
+ * key is already at position S - 1 of k); q_new [B, Hq, D] holds its queries.
+ * For every score row the probabilities softmax_j(q_h . K[j] / sqrt(D)), j < S,
+ * of the row's head(s) are added to scores[b, r, 0 .. S-2]; scores[b, r, S-1]
+ * (the new token, which had no score) is overwritten with its probability;
+ * entries at or beyond S are not touched.  Appending tokens S0+1 .. S one by one
+ * to the scores of a prefix of length S0 gives kvcrush_scores of the whole
+ * sequence (to rounding).  shape->obs_window must be 0; D in {64, 128}.
+ *   workspace  kvcrush_scores_append_workspace(shape, capacity) bytes, 16-byte
+ *              aligned (base-2 logits and per-block partial normalisers).
+ * Errors as kvcrush_scores.
+ */
+size_t kvcrush_scores_append_workspace(const kvcrush_shape* shape, int32_t capacity);
+kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int32_t capacity,
+                                     const void* q_new, const void* k, float* scores,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Eviction while decoding: once kvcrush_select (run on the valid part of the
+ * score rows, see kvcrush_select_args.score_stride) has chosen `budget` tokens,
+ * they and their running scores move to the front of a second cache:
+ *   k_out[b, h, j, :] = k[b, h, idx[b, j], :]  (same for v),
+ *   scores_out[b, r, j] = scores[b, r, idx[b, j]],  j < budget.
+ * Sources have cap_src tokens per row, destinations cap_dst; only the first
+ * `budget` tokens of each destination row are written.  Not in place: outputs
+ * must not alias inputs.  0 <= idx < cap_src is the caller's responsibility, as
+ * in kvcrush_compact.
+ */
+kvcrush_status kvcrush_compact_cache(int32_t B, int32_t Hkv, int32_t Hs, int32_t D, int32_t dtype,
+                                     int32_t cap_src, int32_t cap_dst, int32_t budget,
+                                     const void* k, const void* v, const float* scores,
+                                     const int32_t* idx, void* k_out, void* v_out,
+                                     float* scores_out, void* hip_stream);
 
 const char* kvcrush_status_string(kvcrush_status status);
 

@@ -21,7 +21,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 EXPORTS = (
     "kvcrush_scores_workspace", "kvcrush_scores", "kvcrush_row_lse_workspace", "kvcrush_row_lse",
     "kvcrush_pool_scores",
-    "kvcrush_select_workspace", "kvcrush_select", "kvcrush_compact", "kvcrush_status_string", "kvcrush_version",
+    "kvcrush_select_workspace", "kvcrush_select", "kvcrush_compact", "kvcrush_scores_append_workspace",
+    "kvcrush_scores_append", "kvcrush_compact_cache", "kvcrush_status_string", "kvcrush_version",
 )
 
 
@@ -38,7 +39,7 @@ class Shape(ctypes.Structure):
 
 class SelectArgs(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hs", "S", "budget", "n_important", "bit_topk", "anchor",
-                                                 "n_sink", "n_recent")] + [
+                                                 "score_stride", "n_sink", "n_recent")] + [
         ("anchor_seed", ctypes.c_uint64), ("anchor_bits", ctypes.c_void_p)]
 
 
@@ -71,6 +72,12 @@ def load() -> ctypes.CDLL:
         L.kvcrush_select.restype = ctypes.c_int
         L.kvcrush_compact.argtypes = [i32] * 6 + [vp, vp, vp, vp, i32, vp, vp, vp]
         L.kvcrush_compact.restype = ctypes.c_int
+        L.kvcrush_scores_append_workspace.argtypes = [ctypes.POINTER(Shape), i32]
+        L.kvcrush_scores_append_workspace.restype = sz
+        L.kvcrush_scores_append.argtypes = [ctypes.POINTER(Shape), i32, vp, vp, vp, vp, sz, vp]
+        L.kvcrush_scores_append.restype = ctypes.c_int
+        L.kvcrush_compact_cache.argtypes = [i32] * 8 + [vp] * 8
+        L.kvcrush_compact_cache.restype = ctypes.c_int
         L.kvcrush_status_string.argtypes = [ctypes.c_int]
         L.kvcrush_status_string.restype = ctypes.c_char_p
         L.kvcrush_version.restype = i32
@@ -188,9 +195,9 @@ def lse_from_workspace(workspace: torch.Tensor, B: int, Hq: int, S: int) -> torc
 
 
 def make_select_args(B, Hs, S, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
-                     anchor_bits=None, n_sink=0, n_recent=0) -> SelectArgs:
+                     anchor_bits=None, n_sink=0, n_recent=0, score_stride=0) -> SelectArgs:
     return SelectArgs(B, Hs, S, budget, n_important, bit_topk, ANCHORS[anchor] if isinstance(anchor, str) else anchor,
-                      n_sink, n_recent, anchor_seed & (2**64 - 1),
+                      score_stride, n_sink, n_recent, anchor_seed & (2**64 - 1),
                       None if anchor_bits is None else anchor_bits.data_ptr())
 
 
@@ -200,17 +207,21 @@ def kvcrush_select_workspace(args: SelectArgs) -> int:
 
 def kvcrush_select(scores, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
                    anchor_bits=None, want_kind=True, want_bits=False, idx=None, workspace=None, stream=None,
-                   n_sink=0, n_recent=0):
+                   n_sink=0, n_recent=0, valid_len=None):
     """scores [B,Hs,S] fp32 on the GPU -> (idx int32 [B,budget], kind uint8 | None, bits int64 [B,S,W] | None).
-    n_sink / n_recent tokens at the two ends are always kept; the rest of the budget goes to the middle."""
+    n_sink / n_recent tokens at the two ends are always kept; the rest of the budget goes to the middle.
+    valid_len: scores is a capacity-strided cache [B,Hs,capacity] of which the first valid_len tokens count."""
     scores = _dev(scores, "scores")
     if scores.dtype != torch.float32 or scores.dim() != 3:
         raise ValueError("scores must be fp32 [B,Hs,S]")
     B, Hs, S = scores.shape
+    stride = 0
+    if valid_len is not None:
+        stride, S = S, int(valid_len)
     if anchor_bits is not None:
         anchor_bits = _dev(anchor_bits, "anchor_bits")
     args = make_select_args(B, Hs, S, budget, n_important, bit_topk, anchor, anchor_seed, anchor_bits,
-                            n_sink, n_recent)
+                            n_sink, n_recent, stride)
     dev = scores.device
     if idx is None:
         idx = torch.empty(B, budget, dtype=torch.int32, device=dev)
@@ -258,6 +269,53 @@ def kvcrush_compact(k, v, idx, block_table=None, block_size=16, dense_shape=None
                                 _ptr(_dev(v_out, "v_out")), _stream(stream))
     _check(st, "kvcrush_compact")
     return k_out, v_out
+
+
+def kvcrush_scores_append_workspace(shape: Shape, capacity: int) -> int:
+    return int(load().kvcrush_scores_append_workspace(ctypes.byref(shape), capacity))
+
+
+def kvcrush_scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool, workspace=None, stream=None):
+    """One decoding step, in place on scores_cache [B,Hs,capacity] fp32: the new token's queries
+    q_new [B,Hq,D] attend to the first S tokens of k_cache [B,Hkv,capacity,D] (the new key included)."""
+    q_new, k_cache, scores_cache = _dev(q_new, "q_new"), _dev(k_cache, "k_cache"), _dev(scores_cache, "scores_cache")
+    if q_new.dim() != 3 or k_cache.dim() != 4 or q_new.dtype != k_cache.dtype or scores_cache.dtype != torch.float32:
+        raise ValueError("q_new [B,Hq,D] and k_cache [B,Hkv,capacity,D] of one dtype, scores_cache fp32")
+    B, Hq, D = q_new.shape
+    Hkv, cap = k_cache.shape[1], k_cache.shape[2]
+    if k_cache.shape[0] != B or k_cache.shape[3] != D:
+        raise ValueError("q_new and k_cache disagree on B or D")
+    if tuple(scores_cache.shape) != (B, Hkv if reduce_groups else Hq, cap):
+        raise ValueError("scores_cache must be [B,Hs,capacity]")
+    shape = Shape(B, Hq, Hkv, int(S), D, _dtype_code(q_new), int(bool(reduce_groups)), 0)
+    if workspace is None:
+        workspace = torch.empty(max(kvcrush_scores_append_workspace(shape, cap), 16), dtype=torch.uint8,
+                                device=q_new.device)
+    st = load().kvcrush_scores_append(ctypes.byref(shape), cap, _ptr(q_new), _ptr(k_cache), _ptr(scores_cache),
+                                      _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "kvcrush_scores_append")
+    return scores_cache
+
+
+def kvcrush_compact_cache(k, v, scores, idx, k_out, v_out, scores_out, stream=None):
+    """Eviction on capacity-strided caches: the tokens idx [B,budget] of k, v [B,Hkv,cap_src,D] and of
+    scores [B,Hs,cap_src] move to the front of k_out, v_out [B,Hkv,cap_dst,D], scores_out [B,Hs,cap_dst]."""
+    for name, t in (("k", k), ("v", v), ("scores", scores), ("idx", idx), ("k_out", k_out), ("v_out", v_out),
+                    ("scores_out", scores_out)):
+        _dev(t, name)
+    if idx.dtype != torch.int32 or k.dtype != v.dtype or k.shape != v.shape or k_out.shape != v_out.shape \
+            or k_out.dtype != k.dtype or scores.dtype != torch.float32 or scores_out.dtype != torch.float32:
+        raise ValueError("idx int32; k, v, k_out, v_out of one dtype; scores fp32")
+    B, Hkv, cap_src, D = k.shape
+    cap_dst, Hs = k_out.shape[2], scores.shape[1]
+    if tuple(scores.shape) != (B, Hs, cap_src) or tuple(scores_out.shape) != (B, Hs, cap_dst) \
+            or tuple(k_out.shape) != (B, Hkv, cap_dst, D) or idx.shape[0] != B:
+        raise ValueError("shapes of the source and destination caches do not match")
+    st = load().kvcrush_compact_cache(B, Hkv, Hs, D, _dtype_code(k), cap_src, cap_dst, idx.shape[1], _ptr(k),
+                                      _ptr(v), _ptr(scores), _ptr(idx), _ptr(k_out), _ptr(v_out),
+                                      _ptr(scores_out), _stream(stream))
+    _check(st, "kvcrush_compact_cache")
+    return k_out, v_out, scores_out
 
 
 def kvcrush_version() -> int:

@@ -6,6 +6,8 @@
 // consecutive vectors of a row, consecutive rows follow in the same wave, so
 // the stores are fully contiguous and each load touches whole 128-byte lines.
 // idx is ascending, so the reads sweep the source forwards as well.
+#include <algorithm>
+
 #include "common.h"
 
 namespace {
@@ -19,7 +21,8 @@ struct CompactParams {
   vec16* v_out;
   const int32_t* idx;
   const int32_t* block_table;  // null: dense source
-  int B, Hkv, S, budget;
+  int B, Hkv, S, budget;       // S = tokens per head in the dense source (its stride)
+  int dst_tokens;              // tokens per head in the destination (its stride), >= budget
   int vec_per_row;             // D*sizeof / 16
   int block_size, blocks_per_seq;
   long long total_vec;         // B*Hkv*budget*vec_per_row
@@ -58,7 +61,7 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactParams 
         const long long src = src_row * p.vec_per_row + vec;
         kv[u] = __builtin_nontemporal_load(p.k + src);
         vv[u] = __builtin_nontemporal_load(p.v + src);
-        dst[u] = i;
+        dst[u] = (bh * p.dst_tokens + j) * p.vec_per_row + vec;
       }
     }
 #pragma unroll
@@ -69,6 +72,30 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactParams 
       }
     }
   }
+}
+
+// Running scores of the kept tokens, moved with them (decoding-time eviction).
+struct ScoreGatherParams {
+  const float* scores;   // [rows_per_seq * B, cap_src]
+  float* scores_out;     // [rows_per_seq * B, cap_dst]
+  const int32_t* idx;    // [B, budget]
+  int Hs, cap_src, cap_dst, budget;
+};
+
+__global__ __launch_bounds__(kCompactThreads) void score_gather_kernel(ScoreGatherParams p) {
+  const int row = blockIdx.y;  // b * Hs + r
+  const int b = row / p.Hs;
+  for (int j = blockIdx.x * kCompactThreads + threadIdx.x; j < p.budget; j += gridDim.x * kCompactThreads)
+    p.scores_out[(size_t)row * p.cap_dst + j] = p.scores[(size_t)row * p.cap_src + p.idx[(size_t)b * p.budget + j]];
+}
+
+kvcrush_status launch_compact(const CompactParams& p, hipStream_t stream) {
+  const long long per_block = (long long)kCompactThreads * kRowsInFlight;
+  long long blocks = (p.total_vec + per_block - 1) / per_block;
+  const long long max_blocks = 256 * 32;  // 256 CUs, several waves each; the rest grid-strides
+  if (blocks > max_blocks) blocks = max_blocks;
+  hipLaunchKernelGGL(compact_kernel, dim3((unsigned)blocks), dim3(kCompactThreads), 0, stream, p);
+  return kvc::launch_status();
 }
 
 }  // namespace
@@ -99,16 +126,61 @@ extern "C" kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int
   p.Hkv = Hkv;
   p.S = S;
   p.budget = budget;
+  p.dst_tokens = budget;
   p.vec_per_row = (int)(row_bytes / 16);
   p.block_size = block_table ? block_size : 1;
   p.blocks_per_seq = block_table ? S / block_size : 0;
   p.total_vec = (long long)B * Hkv * budget * p.vec_per_row;
 
-  const long long per_block = (long long)kCompactThreads * kRowsInFlight;
-  long long blocks = (p.total_vec + per_block - 1) / per_block;
-  const long long max_blocks = 256 * 32;  // 256 CUs, several waves each; the rest grid-strides
-  if (blocks > max_blocks) blocks = max_blocks;
-  hipLaunchKernelGGL(compact_kernel, dim3((unsigned)blocks), dim3(kCompactThreads), 0,
-                     (hipStream_t)hip_stream, p);
+  return launch_compact(p, (hipStream_t)hip_stream);
+}
+
+extern "C" kvcrush_status kvcrush_compact_cache(int32_t B, int32_t Hkv, int32_t Hs, int32_t D,
+                                                int32_t dtype, int32_t cap_src, int32_t cap_dst,
+                                                int32_t budget, const void* k, const void* v,
+                                                const float* scores, const int32_t* idx, void* k_out,
+                                                void* v_out, float* scores_out, void* hip_stream) {
+  if (B < 1 || Hkv < 1 || Hs < 1 || D < 1 || cap_src < 1 || cap_dst < 1 || budget < 0 ||
+      budget > cap_src || budget > cap_dst)
+    return KVCRUSH_ERR_INVALID_ARG;
+  if (dtype != KVCRUSH_F32 && dtype != KVCRUSH_BF16) return KVCRUSH_ERR_INVALID_ARG;
+  const size_t row_bytes = (size_t)D * (dtype == KVCRUSH_F32 ? 4 : 2);
+  if (row_bytes % 16 != 0) return KVCRUSH_ERR_UNSUPPORTED;
+  if (budget == 0) return KVCRUSH_OK;
+  if (!k || !v || !idx || !k_out || !v_out || !scores || !scores_out) return KVCRUSH_ERR_INVALID_ARG;
+  if (k == k_out || v == v_out || scores == scores_out) return KVCRUSH_ERR_INVALID_ARG;  // not in place
+  if (!kvc::aligned16(k) || !kvc::aligned16(v) || !kvc::aligned16(k_out) || !kvc::aligned16(v_out))
+    return KVCRUSH_ERR_INVALID_ARG;
+  if ((long long)B * Hs > 65535) return KVCRUSH_ERR_UNSUPPORTED;
+
+  CompactParams p;
+  p.k = (const vec16*)k;
+  p.v = (const vec16*)v;
+  p.k_out = (vec16*)k_out;
+  p.v_out = (vec16*)v_out;
+  p.idx = idx;
+  p.block_table = nullptr;
+  p.B = B;
+  p.Hkv = Hkv;
+  p.S = cap_src;
+  p.budget = budget;
+  p.dst_tokens = cap_dst;
+  p.vec_per_row = (int)(row_bytes / 16);
+  p.block_size = 1;
+  p.blocks_per_seq = 0;
+  p.total_vec = (long long)B * Hkv * budget * p.vec_per_row;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  if (launch_compact(p, stream) != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+
+  ScoreGatherParams g;
+  g.scores = scores;
+  g.scores_out = scores_out;
+  g.idx = idx;
+  g.Hs = Hs;
+  g.cap_src = cap_src;
+  g.cap_dst = cap_dst;
+  g.budget = budget;
+  const int gx = std::min(64, (budget + kCompactThreads - 1) / kCompactThreads);
+  hipLaunchKernelGGL(score_gather_kernel, dim3(gx, B * Hs), dim3(kCompactThreads), 0, stream, g);
   return kvc::launch_status();
 }

@@ -607,6 +607,7 @@ bool select_args_ok(const kvcrush_select_args* a) {
   if (!a) return false;
   if (a->B < 1 || a->Hs < 1 || a->S < 1) return false;
   if (a->budget < 0 || a->budget > a->S) return false;
+  if (a->score_stride != 0 && a->score_stride < a->S) return false;
   if (a->n_sink < 0 || a->n_recent < 0 || (long long)a->n_sink + a->n_recent > a->budget) return false;
   const int prot = a->n_sink + a->n_recent;
   if (a->n_important < 0 || a->n_important > a->budget - prot) return false;
@@ -663,7 +664,7 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
   if (S > 0) {
     TopkParams p;
     p.scores = scores + args->n_sink;
-    p.ld = S_full;
+    p.ld = args->score_stride ? args->score_stride : S_full;
     p.rowmask = rowmask;
     p.keys_ws = L.keys_in_lds ? nullptr : (uint32_t*)(ws + L.keys);
     p.Hs = Hs;

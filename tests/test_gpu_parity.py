@@ -423,3 +423,125 @@ def test_config4_batched(kv, oracle):
 def test_config5_long_paged(kv, oracle):
     say("config 5: S=32768, paged gather, one score row against the oracle")
     run_pipeline(kv, oracle, inputs.CONFIGS[5], 5, 0, [(0, 3)])
+
+
+# ------------------------------------------------------------------ decoding
+@pytest.mark.parametrize("B,Hq,Hkv,S,cap,D,dtype,rg", [
+    (2, 8, 2, 300, 320, 128, "bf16", True),
+    (1, 4, 4, 257, 257, 64, "bf16", False),       # ragged: one key in the last block, capacity == S
+    (3, 4, 1, 1, 16, 128, "bf16", True),          # the very first token
+    (1, 12, 1, 700, 1024, 128, "bf16", True),     # 12 heads share one KV head: two register chunks
+    (2, 2, 2, 513, 600, 128, "f32", False),
+    (1, 6, 3, 100, 128, 64, "f32", True),
+    (8, 32, 8, 2049, 2304, 128, "bf16", True),    # a compressed config-4 cache in mid-generation
+])
+def test_scores_append_matches_oracle(kv, oracle, B, Hq, Hkv, S, cap, D, dtype, rg):
+    say(f"append B={B} Hq={Hq} Hkv={Hkv} S={S} capacity={cap} D={D} {dtype} reduce_groups={rg}")
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(S + Hq)
+    qn = torch.randn(B, Hq, D, generator=g).to(td)
+    kc = torch.randn(B, Hkv, cap, D, generator=g).to(td)
+    kc[:, :, :4] *= 2.0                                    # a few strongly attended early tokens
+    Hs = Hkv if rg else Hq
+    old = torch.rand(B, Hs, cap, generator=g) * 3.0
+    got = kv.kvcrush_scores_append(qn.cuda(), kc.cuda(), old.clone().cuda(), S, rg)
+    torch.cuda.synchronize()
+    want = oracle.scores_append(qn, kc, old.clone(), S, rg)
+    assert torch.equal(got.cpu()[:, :, S:], old[:, :, S:]), "entries beyond the valid length were touched"
+    assert rel_err(got[:, :, :S], want[:, :, :S]) <= SCORE_RTOL
+    # what was added is one probability row per head
+    added = got.cpu().double()[:, :, :S].sum(-1) - old.double()[:, :, :S - 1].sum(-1)
+    assert torch.allclose(added, torch.full_like(added, float(Hq // Hkv if rg else 1)), rtol=1e-4)
+
+
+def test_prefix_plus_appends_equals_prefill(kv):
+    """Identity across the two score paths of the library itself: prefill scores of a prefix plus
+    one append per later token equal the prefill scores of the whole sequence."""
+    say("prefill(S0) + appends == prefill(S)")
+    w = inputs.Workload("t", 2, 8, 2, 400, 128, "bf16", 100, 0.5, "alternating", True, sink_bias=True)
+    q, k, _ = inputs.make_qkv(w, 3, want_v=False)
+    qd, kd = q.cuda(), k.cuda()
+    S0, S, cap = 330, 400, 448
+    whole, _ = kv.kvcrush_scores(qd, kd, True)
+    sc = torch.zeros(2, 2, cap, device="cuda")
+    sc[:, :, :S0] = kv.kvcrush_scores(qd[:, :, :S0].contiguous(), kd[:, :, :S0].contiguous(), True)[0]
+    kc = torch.zeros(2, 2, cap, 128, dtype=torch.bfloat16, device="cuda")
+    kc[:, :, :S] = kd
+    for n in range(S0 + 1, S + 1):
+        kv.kvcrush_scores_append(qd[:, :, n - 1].contiguous(), kc, sc, n, True)
+    torch.cuda.synchronize()
+    assert rel_err(sc[:, :, :S], whole.cpu()) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_compact_cache_matches_oracle(kv, oracle, dtype):
+    say(f"eviction gather on capacity-strided caches, {dtype}")
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    B, Hkv, Hs, D, cap_src, cap_dst, budget = 3, 4, 4, 128, 700, 520, 333
+    g = torch.Generator().manual_seed(8)
+    k = torch.randn(B, Hkv, cap_src, D, generator=g).to(td)
+    v = torch.randn(B, Hkv, cap_src, D, generator=g).to(td)
+    sc = torch.randn(B, Hs, cap_src, generator=g)
+    idx = torch.stack([torch.randperm(650, generator=g)[:budget].sort().values for _ in range(B)]).to(torch.int32)
+    outs = [torch.full((B, Hkv, cap_dst, D), 5.0, dtype=td), torch.full((B, Hkv, cap_dst, D), 6.0, dtype=td),
+            torch.full((B, Hs, cap_dst), 7.0)]
+    want = oracle.compact_cache(k, v, sc, idx, *[t.clone() for t in outs])
+    got = kv.kvcrush_compact_cache(k.cuda(), v.cuda(), sc.cuda(), idx.cuda(), *[t.clone().cuda() for t in outs])
+    torch.cuda.synchronize()
+    for a, b in zip(got, want):
+        assert torch.equal(a.cpu().view(torch.uint8), b.view(torch.uint8))
+
+
+def test_decode_loop_with_evictions(kv, oracle):
+    """Generation loop: compress after prefill (protected ends), then append token by token and
+    evict whenever the cache is full.  The oracle replays every step on its own state; each
+    eviction is compared on the GPU's own score tensor (bit-exact) and applied to both sides."""
+    say("decode loop: prefill -> compress -> 150 x append, eviction whenever the cache is full")
+    B, Hq, Hkv, D, S0 = 2, 8, 2, 128, 600
+    budget, n_imp, sink, recent, cap, steps = 200, 90, 8, 32, 256, 150
+    w = inputs.Workload("t", B, Hq, Hkv, S0 + steps, D, "bf16", budget, 0.5, "alternating", True, sink_bias=True)
+    q, k, v = inputs.make_qkv(w, 17)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+
+    def evict(sc_dev, valid, kc, vc, o_state):
+        idx, kind, _ = kv.kvcrush_select(sc_dev, budget, n_imp, 0, "mean", 3, n_sink=sink, n_recent=recent,
+                                         valid_len=valid)
+        torch.cuda.synchronize()
+        ridx, rkind, _ = oracle.select(sc_dev.cpu()[:, :, :valid].contiguous(), budget, n_imp, 0, "mean", 3,
+                                       n_sink=sink, n_recent=recent)
+        assert torch.equal(idx.cpu(), ridx) and torch.equal(kind.cpu(), rkind)
+        new = [torch.zeros_like(kc), torch.zeros_like(vc), torch.zeros_like(sc_dev)]
+        kv.kvcrush_compact_cache(kc, vc, sc_dev, idx, *new)
+        o_new = [torch.zeros_like(t) for t in o_state]
+        oracle.compact_cache(*o_state, ridx, *o_new)
+        return new, o_new
+
+    # prefill + first compression (dense tensors: capacity == S0)
+    sc0, _ = kv.kvcrush_scores(qd[:, :, :S0].contiguous(), kd[:, :, :S0].contiguous(), True)
+    o_sc0 = oracle.scores(q[:, :, :S0].contiguous(), k[:, :, :S0].contiguous(), True, threads=THREADS)
+    assert rel_err(sc0, o_sc0) <= SCORE_RTOL
+    pad = lambda t, n: torch.cat([t, torch.zeros(*t.shape[:2], n - t.shape[2], *t.shape[3:], dtype=t.dtype,
+                                                 device=t.device)], dim=2)
+    (kc, vc, sc), (o_k, o_v, o_sc) = evict(pad(sc0, S0), S0, kd[:, :, :S0].contiguous(), vd[:, :, :S0].contiguous(),
+                                           [k[:, :, :S0].contiguous(), v[:, :, :S0].contiguous(), o_sc0])
+    # move into capacity-sized caches
+    kc, vc, sc = [t[:, :, :cap].contiguous() for t in (kc, vc, sc)]
+    o_k, o_v, o_sc = [t[:, :, :cap].contiguous() for t in (o_k, o_v, o_sc)]
+    n, evictions = budget, 0
+    for step in range(steps):
+        pos = S0 + step
+        if n == cap:
+            (kc, vc, sc), (o_k, o_v, o_sc) = evict(sc, n, kc, vc, [o_k, o_v, o_sc])
+            n, evictions = budget, evictions + 1
+        kc[:, :, n] = kd[:, :, pos]
+        vc[:, :, n] = vd[:, :, pos]
+        o_k[:, :, n] = k[:, :, pos]
+        o_v[:, :, n] = v[:, :, pos]
+        n += 1
+        kv.kvcrush_scores_append(qd[:, :, pos].contiguous(), kc, sc, n, True)
+        oracle.scores_append(q[:, :, pos].contiguous(), o_k, o_sc, n, True)
+    torch.cuda.synchronize()
+    assert evictions == 2
+    assert torch.equal(kc.cpu()[:, :, :n].view(torch.uint8), o_k[:, :, :n].view(torch.uint8))
+    assert torch.equal(vc.cpu()[:, :, :n].view(torch.uint8), o_v[:, :, :n].view(torch.uint8))
+    assert rel_err(sc[:, :, :n], o_sc[:, :, :n]) <= SCORE_RTOL
