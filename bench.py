@@ -44,6 +44,10 @@ def parse():
     ap.add_argument("--window", type=int, default=0,
                     help="observation window W: only the last W queries score the tokens (SnapKV-style scoring)")
     ap.add_argument("--pool", type=int, default=0, help="max-pool the scores with this odd kernel before selection")
+    ap.add_argument("--decode", action="store_true",
+                    help="time the decoding-time score append on caches of --cache-len tokens instead of the "
+                         "per-layer compression step")
+    ap.add_argument("--cache-len", type=int, default=0, help="--decode: valid tokens per cache (0: the workload's budget)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
@@ -83,6 +87,57 @@ def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer, row_begin=0, pool=0):
     }
 
 
+def run_decode(args, torch, kv, inputs, dev):
+    """One step = one decoded token per sequence of the batch: kvcrush_scores_append on a cache of
+    --cache-len tokens.  Several caches are walked in turn so that the last-level cache cannot hold K."""
+    w = inputs.CONFIGS[args.config]
+    S = args.cache_len or w.budget
+    cap = S + 256
+    Hs = w.Hs
+    esz = 2 if w.dtype == "bf16" else 4
+    k_bytes = w.B * w.Hkv * S * w.D * esz
+    n_caches = max(2, min(32, int(1.5e9 // max(k_bytes, 1))))
+    g = torch.Generator(device=dev).manual_seed(inputs.BASE_SEED)
+    caches = []
+    for _ in range(n_caches):
+        kc = torch.randn(w.B, w.Hkv, cap, w.D, generator=g, device=dev).to(w.torch_dtype)
+        qn = torch.randn(w.B, w.Hq, w.D, generator=g, device=dev).to(w.torch_dtype)
+        sc = torch.rand(w.B, Hs, cap, generator=g, device=dev)
+        caches.append((qn, kc, sc))
+    shape = kv.Shape(w.B, w.Hq, w.Hkv, S, w.D, kv.BF16 if w.dtype == "bf16" else kv.F32, int(w.reduce_groups), 0)
+    ws = torch.empty(max(kv.kvcrush_scores_append_workspace(shape, cap), 16), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        qn, kc, sc = caches[i % n_caches]
+        kv.kvcrush_scores_append(qn, kc, sc, S, w.reduce_groups, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = e0.elapsed_time(e1) / args.steps
+    ms = wall * 1e3 / args.steps
+    out = {
+        "metric": "decode_score_append_tokens_per_sec", "value": w.B / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}_decode_cache{S}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "cache_len": S,
+                   "capacity": cap, "D": w.D, "reduce_groups": w.reduce_groups, "resident_caches": n_caches},
+        "roofline": {"bound": "hbm", "kernel": "append_logits_kernel + append_update_kernel",
+                     "achieved": k_bytes / (gpu_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": k_bytes / (gpu_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_step": k_bytes, "avg_step_gpu_ms": gpu_ms},
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -100,6 +155,8 @@ def main():
     kv.load()
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.decode:
+        return run_decode(args, torch, kv, inputs, dev)
     w = inputs.CONFIGS[args.config]
     n_layers = args.layers or min(w.layers, 32)
     # a single-layer workload still rotates over a few copies so that repeats miss the cache

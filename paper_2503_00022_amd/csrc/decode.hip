@@ -8,28 +8,33 @@
 // (B*Hkv*S*D*sizeof bytes); the exponentials and the fp32 dot products are far
 // below the VALU's rate at that pace.
 //
-//   append_logits_kernel   workgroup = 256 keys of one KV head.  A key row is
-//                          read as 16-byte vectors by neighbouring lanes (whole
-//                          cache lines per wave instruction); the queries of up
-//                          to 8 heads of the KV group sit in registers, so K is
-//                          read once for the group.  Leaves base-2 logits in the
-//                          workspace and one (max, sum) pair per workgroup, head.
+//   append_logits_mfma_kernel  (bf16) workgroup = 256 keys of one KV head: four
+//                          64-row K tiles go global -> LDS asynchronously, each
+//                          wave multiplies its tile with the query vectors of
+//                          the KV group's heads (the 32 columns of a 32x32x16
+//                          MFMA; unused columns are zero), so K is read once for
+//                          the whole group and the dot products cost the VALU
+//                          nothing.  Leaves base-2 logits in the workspace and
+//                          one (max, sum) pair per workgroup and head.
+//   append_logits_kernel   (fp32 inputs) the same on the VALU: a key row is read
+//                          as 16-byte vectors by neighbouring lanes, the queries
+//                          of up to 8 heads sit in registers.
 //   append_update_kernel   merges the pairs into the row normaliser, turns
 //                          logits into probabilities, sums the group's heads in
 //                          ascending order and updates the score row.
 #include <cmath>
 
 #include "common.h"
+#include "tiles.h"
 
 namespace {
 
+using namespace kvc::tiles;  // kThreads = 256, kWaves = 4, kNegBig, tile helpers
+
 typedef uint32_t vec16 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / KVC_WAVE;
 constexpr int kKeysPerWg = 256;
-constexpr int kHeadChunk = 8;  // query heads whose vectors are held in registers at once
-constexpr float kNegBig = -1.0e30f;
+constexpr int kHeadChunk = 8;  // VALU path: query heads whose vectors are held in registers at once
 
 struct AppendParams {
   const char* q_new;   // [B,Hq,D]
@@ -150,6 +155,93 @@ __global__ __launch_bounds__(kThreads) void append_logits_kernel(AppendParams p)
   }
 }
 
+// bf16: logits of 256 keys x up to 32 heads per pass on the matrix cores.
+template <int D>
+__global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendParams p) {
+  using C = Cfg<true, D>;
+  static_assert(C::kTile * kWaves == kKeysPerWg, "one 64-row tile per wave");
+  __shared__ __attribute__((aligned(1024))) char lds[kWaves][C::kTileBytes];
+  __shared__ float red[2][kWaves][32];
+
+  const int tid = threadIdx.x, lane = kvc::lane_id(), wave = tid / KVC_WAVE;
+  const int kb = blockIdx.x, bg = blockIdx.y;  // bg = b * Hkv + kv head
+  const int b = bg / p.Hkv, g = bg % p.Hkv;
+  const int S = p.S;
+  const int k0 = kb * kKeysPerWg;
+  const char* kh = p.k + (size_t)bg * p.capacity * C::kRowBytes;
+
+  uint32_t rel[C::kLoadsPerWave];
+  tile_lane_offsets<C>(rel, wave, lane);
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const int row0 = k0 + C::kTile * w;
+    if (row0 < S) tile_load_async<C>(kh, row0, S, lds[w], rel, wave);  // tiles past the end stay unread
+  }
+  wait_async_loads();
+  __syncthreads();
+
+  const int n = lane & 31;  // result column of this lane = head inside the chunk
+  const int off0 = lds_frag_offset0<C>(lane);
+  const int key_base = k0 + C::kTile * wave + 4 * (lane >> 5);  // + 32 * sub + 8 * (r / 4) + r % 4
+  for (int h0 = 0; h0 < p.G; h0 += 32) {
+    const int nh = min(32, p.G - h0);
+    const size_t bh = (size_t)b * p.Hq + g * p.G + h0 + min(n, nh - 1);
+    u32x4 qf[C::kSteps];
+#pragma unroll
+    for (int s = 0; s < C::kSteps; ++s) {
+      u32x4 v = *(const u32x4*)(p.q_new + bh * C::kRowBytes + (s + (lane >> 5) * C::kSteps) * 16);
+      if (n >= nh) v = u32x4{0u, 0u, 0u, 0u};
+      qf[s] = v;
+    }
+    f32x16 acc[2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[sub][r] = 0.0f;
+#pragma unroll
+      for (int s = 0; s < C::kSteps; ++s) mma_step<true>(acc[sub], lds_frag<C>(lds[wave], off0, sub, s), qf[s]);
+    }
+    // this lane: 32 keys of head n.  Keys past the end (and whole unread tiles) are masked here.
+    float m = kNegBig;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = key_base + 32 * sub + 8 * (r >> 2) + (r & 3);
+        const float x = key < S ? acc[sub][r] * p.scale_log2 : kNegBig;
+        acc[sub][r] = x;
+        m = fmaxf(m, x);
+      }
+    m = fmaxf(m, __shfl_xor(m, 32));
+    if (lane < 32) red[0][wave][n] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0][0][n], red[0][1][n]), fmaxf(red[0][2][n], red[0][3][n]));
+    float l = 0.0f;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) l += __builtin_amdgcn_exp2f(acc[sub][r] - m);  // masked keys: 2^-huge = 0
+    l += __shfl_xor(l, 32);
+    if (lane < 32) red[1][wave][n] = l;
+    __syncthreads();
+    if (tid < nh) {
+      const float lt = (red[1][0][tid] + red[1][1][tid]) + (red[1][2][tid] + red[1][3][tid]);
+      p.part[((size_t)b * p.Hq + g * p.G + h0 + tid) * p.n_kb + kb] = make_float2(m, lt);
+    }
+    if (n < nh) {
+      float* dst = p.logits + bh * S;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key_base + 32 * sub + 8 * (r >> 2) + (r & 3);
+          if (key < S) dst[key] = acc[sub][r];
+        }
+    }
+    __syncthreads();  // `red` is rewritten by the next chunk of heads
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void append_update_kernel(AppendParams p) {
   __shared__ float red[kWaves];
   const int tid = threadIdx.x;
@@ -202,7 +294,11 @@ bool append_shape_ok(const kvcrush_shape* s, int capacity) {
 
 template <bool BF16, int D>
 kvcrush_status launch_append(const AppendParams& p, hipStream_t stream) {
-  hipLaunchKernelGGL((append_logits_kernel<BF16, D>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
+  if constexpr (BF16) {
+    hipLaunchKernelGGL((append_logits_mfma_kernel<D>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
+  } else {
+    hipLaunchKernelGGL((append_logits_kernel<BF16, D>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
+  }
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   const int Hs = p.reduce_groups ? p.Hkv : p.Hq;
   hipLaunchKernelGGL(append_update_kernel, dim3(p.n_kb, p.B * Hs), dim3(kThreads), 0, stream, p);

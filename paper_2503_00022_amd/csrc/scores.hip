@@ -37,126 +37,13 @@
 #include <algorithm>
 
 #include "common.h"
+#include "tiles.h"
 
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+using namespace kvc::tiles;
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / KVC_WAVE;
 constexpr int kKeysPerWg = 64 * kWaves;  // pass B: keys held by one workgroup
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kNegBig = -1.0e30f;  // finite "no key seen yet": exp2(m_old - m_new) never sees inf - inf
-
-template <bool BF16, int D>
-struct Cfg {
-  static constexpr int kRowBytes = D * (BF16 ? 2 : 4);
-  static constexpr int kSteps = kRowBytes / 32;      // 16-byte fragments per lane and row
-  static constexpr int kChunksPerRow = kRowBytes / 16;
-  static constexpr int kTile = BF16 ? 64 : 32;       // streamed rows per LDS buffer
-  static constexpr int kTileSub = kTile / 32;
-  static constexpr int kTileBytes = kTile * kRowBytes;
-  static constexpr int kSubBytes = 32 * kRowBytes;
-  static constexpr int kLoadsPerWave = kTileBytes / 1024 / kWaves;  // 1 KiB per wave instruction
-  static constexpr bool kPipelined = BF16;           // hand-pipelined loop needs two sub-tiles a tile
-  static_assert(kTileBytes % (1024 * kWaves) == 0, "tile must split evenly over the waves");
-};
-
-// One MFMA "load step": C += A_frag . B_frag^T over this step's k-slice.
-template <bool BF16>
-__device__ __forceinline__ void mma_step(f32x16& acc, const u32x4& a, const u32x4& b) {
-  if constexpr (BF16) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                  __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[i]), __uint_as_float(b[i]), acc,
-                                                 0, 0, 0);
-  }
-}
-
-// Row of the 32x32 result that register r of this lane holds.
-__device__ __forceinline__ int acc_row(int r, int lane) {
-  return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-}
-
-// Byte offset, inside a tile buffer, of 16-byte chunk `cidx` of row `row`.
-template <class C>
-__device__ __forceinline__ int lds_chunk_offset(int row, int cidx) {
-  const int q = row * C::kChunksPerRow + cidx;
-  const int line = q >> 4, pos = q & 15;
-  return (line << 8) | ((pos ^ (line & 15)) << 4);
-}
-
-// Offset of this lane's step-0 fragment of sub-tile 0; step s is at (off0 ^ (s << 4)),
-// sub-tile u adds u * kSubBytes (neither changes the swizzle bits).
-template <class C>
-__device__ __forceinline__ int lds_frag_offset0(int lane) {
-  return lds_chunk_offset<C>(lane & 31, (lane >> 5) * C::kSteps);
-}
-
-template <class C>
-__device__ __forceinline__ u32x4 lds_frag(const char* buf, int off0, int sub, int step) {
-  return *(const u32x4*)(buf + sub * C::kSubBytes + (off0 ^ (step << 4)));
-}
-
-// Per-lane byte offsets, relative to a tile's first row, of the 16-byte chunks
-// this lane copies (one per wave instruction; see tile_load_async).
-template <class C>
-__device__ __forceinline__ void tile_lane_offsets(uint32_t (&rel)[C::kLoadsPerWave], int wave, int lane) {
-#pragma unroll
-  for (int j = 0; j < C::kLoadsPerWave; ++j) {
-    const int inst = wave + kWaves * j;
-    const int p = inst * 64 + lane;  // physical chunk this lane fills
-    const int line = p >> 4, pos = (p & 15) ^ (line & 15);
-    const int q = line * 16 + pos;   // logical chunk
-    rel[j] = (uint32_t)((q / C::kChunksPerRow) * C::kRowBytes + (q % C::kChunksPerRow) * 16);
-  }
-}
-
-// Asynchronous copy of tile rows [row0, row0 + kTile) of one head into an LDS
-// buffer: uniform tile address + per-lane offset, no vector address arithmetic.
-// Rows past the end of the sequence are clamped to the last row (the callers
-// mask or ignore them).  Completion: s_waitcnt vmcnt(0), then a barrier.
-template <class C>
-__device__ __forceinline__ void tile_load_async(const char* head_base, int row0, int S, char* buf,
-                                                const uint32_t (&rel)[C::kLoadsPerWave], int wave) {
-  const char* tile = head_base + (size_t)row0 * C::kRowBytes;
-  const int valid = S - row0;  // rows of this tile inside the sequence
-#pragma unroll
-  for (int j = 0; j < C::kLoadsPerWave; ++j) {
-    uint32_t off = rel[j];
-    if (valid < C::kTile) {  // ragged last tile (uniform branch)
-      const uint32_t row = off / C::kRowBytes, in_row = off % C::kRowBytes;
-      off = min(row, (uint32_t)(valid - 1)) * C::kRowBytes + in_row;
-    }
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile + off),
-                                     (__attribute__((address_space(3))) void*)(buf + (wave + kWaves * j) * 1024),
-                                     16, 0, 0);
-  }
-}
-
-__device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-
-// Fragments of 32 stationary rows, straight from global memory to registers
-// (zero rows past the end of the sequence).
-template <class C>
-__device__ __forceinline__ void load_stationary(u32x4 (&frag)[C::kSteps], const char* head_base,
-                                                int row0, int S, int lane) {
-  const int t = row0 + (lane & 31);
-#pragma unroll
-  for (int s = 0; s < C::kSteps; ++s) {
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (t < S)
-      v = *(const u32x4*)(head_base + (size_t)t * C::kRowBytes + (s + (lane >> 5) * C::kSteps) * 16);
-    frag[s] = v;
-  }
-}
 
 struct ScoreParams {
   const char* q;     // [B,Hq,S,D]
