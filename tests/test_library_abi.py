@@ -165,3 +165,64 @@ def test_select_protected_ends_validation(lib):
     assert ws(n_sink=100, n_recent=100, n_important=0) > 0   # budget == protected: legal
     # the workspace is sized by the middle, which is never longer than the sequence
     assert ws() <= ws(n_sink=0, n_recent=0)
+
+
+def make_shape(base, overrides):
+    d = dict(base, **overrides)
+    return binding.Shape(*[d[f] for f, _ in binding.Shape._fields_])
+
+
+def test_window_pool_and_row_lse_validation(lib):
+    sh = lambda **kw: make_shape(dict(B=1, Hq=4, Hkv=2, S=4096, D=128, dtype=1, reduce_groups=1, obs_window=0), kw)
+    # a window shrinks the partial-sum part of the workspace, never grows the total past the full one
+    assert 0 < binding.kvcrush_scores_workspace(sh(obs_window=64)) <= binding.kvcrush_scores_workspace(sh()) + (1 << 20)
+    assert binding.kvcrush_scores_workspace(sh(obs_window=-1)) == 0
+    # few heads: the normaliser pass wants scratch memory for key slices
+    assert binding.kvcrush_row_lse_workspace(sh(obs_window=64)) > 0
+    assert binding.kvcrush_row_lse_workspace(sh(B=8, Hq=32, Hkv=8, S=16384)) == 0      # enough workgroups already
+    assert binding.kvcrush_row_lse_workspace(sh(dtype=0, obs_window=64)) == 0          # fp32 path never slices
+    call = lambda shape, ws, n: lib.kvcrush_row_lse(ctypes.byref(shape), FAKE, FAKE, FAKE, ws, n, None)
+    assert call(sh(obs_window=64), FAKE, 16) == binding.ERR_WORKSPACE
+    assert call(sh(obs_window=64), ctypes.c_void_p(0x1004), 1 << 40) == binding.ERR_WORKSPACE
+    assert call(sh(D=96), None, 0) == binding.ERR_UNSUPPORTED
+    pool = lambda rows=2, S=64, kernel=3, a=FAKE, b=ctypes.c_void_p(0x100000): \
+        lib.kvcrush_pool_scores(rows, S, kernel, a, b, None)
+    assert pool(kernel=2) == binding.ERR_INVALID_ARG
+    assert pool(kernel=1025) == binding.ERR_INVALID_ARG
+    assert pool(S=0) == binding.ERR_INVALID_ARG
+    assert pool(b=FAKE) == binding.ERR_INVALID_ARG                       # in place
+    assert pool(b=ctypes.c_void_p(0x1000 + 256)) == binding.ERR_INVALID_ARG   # overlapping
+    assert pool(a=None) == binding.ERR_INVALID_ARG
+    assert pool(rows=0, a=None, b=None) == binding.OK
+
+
+def test_decode_entry_points_validation(lib):
+    sh = lambda **kw: make_shape(dict(B=2, Hq=8, Hkv=2, S=300, D=128, dtype=1, reduce_groups=1, obs_window=0), kw)
+    need = binding.kvcrush_scores_append_workspace(sh(), 320)
+    assert need >= 2 * 8 * 300 * 4
+    assert binding.kvcrush_scores_append_workspace(sh(), 299) == 0        # capacity below the valid length
+    assert binding.kvcrush_scores_append_workspace(sh(obs_window=8), 320) == 0
+    call = lambda shape, cap=320, q=FAKE, k=FAKE, sc=FAKE, ws=FAKE, n=1 << 40: \
+        lib.kvcrush_scores_append(ctypes.byref(shape), cap, q, k, sc, ws, n, None)
+    assert call(sh(), cap=100) == binding.ERR_INVALID_ARG
+    assert call(sh(Hq=7)) == binding.ERR_INVALID_ARG
+    assert call(sh(D=32)) == binding.ERR_UNSUPPORTED
+    assert call(sh(), q=None) == binding.ERR_INVALID_ARG
+    assert call(sh(), k=ctypes.c_void_p(0x1002)) == binding.ERR_INVALID_ARG
+    assert call(sh(), ws=None) == binding.ERR_WORKSPACE
+    assert call(sh(), n=need - 1) == binding.ERR_WORKSPACE
+    other = ctypes.c_void_p(0x200000)
+    cc = lambda B=1, Hkv=2, Hs=2, D=128, dtype=1, cs=100, cd=80, budget=40, k=FAKE, v=FAKE, sc=FAKE, idx=FAKE, \
+        ko=other, vo=other, so=other: lib.kvcrush_compact_cache(B, Hkv, Hs, D, dtype, cs, cd, budget, k, v, sc, idx,
+                                                                 ko, vo, so, None)
+    assert cc(budget=81) == binding.ERR_INVALID_ARG          # does not fit the destination
+    assert cc(budget=101, cd=200) == binding.ERR_INVALID_ARG  # more than the source holds
+    assert cc(dtype=5) == binding.ERR_INVALID_ARG
+    assert cc(D=4) == binding.ERR_UNSUPPORTED
+    assert cc(ko=FAKE) == binding.ERR_INVALID_ARG            # in place
+    assert cc(sc=None) == binding.ERR_INVALID_ARG
+    assert cc(budget=0, k=None, v=None, sc=None, idx=None, ko=None, vo=None, so=None) == binding.OK
+    # strided score rows in the selection
+    mk = binding.make_select_args
+    assert binding.kvcrush_select_workspace(mk(1, 8, 100, 50, 10, score_stride=99)) == 0
+    assert binding.kvcrush_select_workspace(mk(1, 8, 100, 50, 10, score_stride=128)) > 0
