@@ -54,6 +54,7 @@ def lib() -> ctypes.CDLL:
         L.kvcrush_oracle_group.argtypes = [i32, i32, vp, vp, i32, i32, u64, i32, vp, vp, vp]
         L.kvcrush_oracle_select.argtypes = [i32] * 7 + [u64, vp, vp, vp, vp, vp]
         L.kvcrush_oracle_select_protected.argtypes = [i32] * 9 + [u64, vp, vp, vp, vp, vp]
+        L.kvcrush_oracle_select_units.argtypes = [i32] * 10 + [u64, vp, vp, vp, vp, vp]
         L.kvcrush_oracle_compact.argtypes = [i32] * 6 + [vp, vp, vp, vp, i32, vp, vp]
         _lib = L
     return _lib
@@ -240,6 +241,25 @@ def select(scores_t, budget, n_important, bit_topk=0, anchor="alternating", anch
                                          _ptr(idx), _ptr(kind), _ptr(bw))
     _check(rc, "select")
     return idx, kind, bw
+
+
+def select_units(scores_t, unit, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
+                 anchor_bits=None, n_sink=0, n_recent=0):
+    """Chunk- / page-level stages 2-4: the unit of selection is `unit` consecutive tokens.
+    Returns (idx int32 [B,budget] tokens, kind uint8 [B,budget], unit bits int64 [B,Nu,Wu])."""
+    sc = _cpu(scores_t.to(torch.float32))
+    B, Hs, S = sc.shape
+    Nu = max((S - n_sink - n_recent) // unit, 0)
+    Wu = words_for(Hs * unit)
+    idx = torch.empty(B, budget, dtype=torch.int32)
+    kind = torch.empty(B, budget, dtype=torch.uint8)
+    ub = torch.zeros(B, Nu, Wu, dtype=torch.int64)
+    ab = None if anchor_bits is None else _cpu(anchor_bits.to(torch.int64))
+    rc = lib().kvcrush_oracle_select_units(B, Hs, S, unit, budget, n_important, bit_topk, n_sink, n_recent,
+                                           ANCHORS[anchor], ctypes.c_uint64(anchor_seed & (2**64 - 1)), _ptr(ab),
+                                           _ptr(sc), _ptr(idx), _ptr(kind), _ptr(ub))
+    _check(rc, "select_units")
+    return idx, kind, ub
 
 
 def compact(k, v, idx, block_table=None, block_size=16, dense_shape=None):

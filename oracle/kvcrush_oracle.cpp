@@ -427,6 +427,99 @@ int kvcrush_oracle_select_protected(int B, int Hs, int S, int budget, int n_impo
   return 0;
 }
 
+// Chunk- / page-level KVCrush (Sec. 4.3.4: baselines that work on chunks;
+// Sec. 4.3.5: paged caches).  The unit of selection is a run of `unit`
+// consecutive tokens.  As that section describes the paged variant:
+//   * a unit's importance is the baseline's token importance added up over the
+//     unit's tokens (here: fp32, tokens ascending, each token's importance being
+//     the fp32 sum of the score rows in row order);
+//   * a unit's binary vector is the concatenation of the head vectors of its
+//     tokens: bit j*Hs + r of the unit is bit r of its j-th token, the token
+//     bits being those of Alg. 1 (per-row top-bit_topk over TOKENS);
+//   * Alg. 2 then runs on units: anchor of unit*Hs bits, Hamming distance,
+//     buckets, one representative unit per bucket.
+// budget, n_important, n_sink, n_recent count tokens; budget - n_sink - n_recent,
+// n_important and the middle's length must be multiples of `unit`.
+// idx, kind: [B,budget] tokens (every token of a kept unit, ascending).
+// unit_bits_out (nullable): [B, Nu, Wu] with Nu = middle / unit units and
+// Wu = ceil(unit*Hs / 64) words each.
+int kvcrush_oracle_select_units(int B, int Hs, int S, int unit, int budget, int n_important,
+                                int bit_topk, int n_sink, int n_recent, int anchor_mode,
+                                uint64_t anchor_seed, const uint64_t* anchor_bits,
+                                const float* scores, int32_t* idx, uint8_t* kind,
+                                uint64_t* unit_bits_out) {
+  if (B < 1 || Hs < 1 || S < 1 || unit < 1 || budget < 0 || budget > S || n_sink < 0 ||
+      n_recent < 0 || n_sink + n_recent > budget)
+    return 1;
+  const int Sm = S - n_sink - n_recent, Bm = budget - n_sink - n_recent;
+  if (Sm % unit != 0 || Bm % unit != 0 || n_important < 0 || n_important > Bm ||
+      n_important % unit != 0)
+    return 1;
+  const int kbit = bit_topk == 0 ? Bm : bit_topk;
+  if (kbit < 0 || kbit > Sm) return 1;
+  const int Nu = Sm / unit, Bu = Bm / unit, Iu = n_important / unit, Ru = Bu - Iu;
+  const int W = words_for(Hs), Hu = Hs * unit, Wu = words_for(Hu);
+  const size_t one = 1;
+  std::vector<float> mid((size_t)Hs * std::max(Sm, 1)), tok_imp(std::max(Sm, 1)), unit_imp(std::max(Nu, 1));
+  std::vector<uint64_t> tok_bits(std::max((size_t)Sm * W, one)), unit_bits(std::max((size_t)Nu * Wu, one));
+  std::vector<uint8_t> is_imp(std::max(Nu, 1)), is_rep(std::max(Nu, 1));
+  std::vector<int32_t> reps(std::max(Ru, 1));
+  for (int b = 0; b < B; ++b) {
+    const float* sc = scores + (size_t)b * Hs * S;
+    std::fill(is_imp.begin(), is_imp.end(), 0);
+    std::fill(is_rep.begin(), is_rep.end(), 0);
+    if (Nu > 0) {
+      for (int r = 0; r < Hs; ++r)
+        for (int t = 0; t < Sm; ++t) mid[(size_t)r * Sm + t] = sc[(size_t)r * S + n_sink + t];
+      int rc = kvcrush_oracle_bits(Hs, Sm, kbit, mid.data(), tok_bits.data());
+      if (rc) return rc;
+      for (int t = 0; t < Sm; ++t) {
+        float acc = 0.0f;
+        for (int r = 0; r < Hs; ++r) acc = acc + mid[(size_t)r * Sm + t];
+        tok_imp[t] = acc;
+      }
+      std::fill(unit_bits.begin(), unit_bits.end(), 0ull);
+      for (int u = 0; u < Nu; ++u) {
+        float acc = 0.0f;
+        for (int j = 0; j < unit; ++j) {
+          const int t = u * unit + j;
+          acc = acc + tok_imp[t];
+          for (int r = 0; r < Hs; ++r)
+            if (get_bit(tok_bits.data() + (size_t)t * W, r)) {
+              const int pos = j * Hs + r;
+              unit_bits[(size_t)u * Wu + pos / 64] |= 1ull << (pos % 64);
+            }
+        }
+        unit_imp[u] = acc;
+      }
+      for (int u : topk_indices(unit_imp.data(), Nu, Iu)) is_imp[u] = 1;
+      rc = kvcrush_oracle_group(Hu, Nu, unit_bits.data(), is_imp.data(), Ru, anchor_mode, anchor_seed,
+                                b, anchor_bits ? anchor_bits + (size_t)b * Wu : nullptr, reps.data(),
+                                nullptr);
+      if (rc) return rc;
+      for (int j = 0; j < Ru; ++j) {
+        if (is_imp[reps[j]] || is_rep[reps[j]]) return 2;
+        is_rep[reps[j]] = 1;
+      }
+    }
+    int o = 0;
+    for (int t = 0; t < S; ++t) {
+      const bool prot = t < n_sink || t >= S - n_recent;
+      const int u = prot ? 0 : (t - n_sink) / unit;
+      if (prot || is_imp[u] || is_rep[u]) {
+        if (o >= budget) return 2;
+        idx[(size_t)b * budget + o] = t;
+        if (kind) kind[(size_t)b * budget + o] = prot ? 2 : (is_rep[u] ? 1 : 0);
+        ++o;
+      }
+    }
+    if (o != budget) return 2;
+    if (unit_bits_out && Nu > 0)
+      std::memcpy(unit_bits_out + (size_t)b * Nu * Wu, unit_bits.data(), sizeof(uint64_t) * Nu * Wu);
+  }
+  return 0;
+}
+
 // Stages 2-4 for a batch without protected tokens.
 int kvcrush_oracle_select(int B, int Hs, int S, int budget, int n_important, int bit_topk,
                           int anchor_mode, uint64_t anchor_seed, const uint64_t* anchor_bits,

@@ -358,3 +358,103 @@ def test_protected_ends_reject_inconsistent_arguments(oracle):
         n_imp = kw.pop("n_important", 5)
         with pytest.raises(RuntimeError):
             oracle.select(sc, 30, n_imp, 0, "alternating", **kw)
+
+
+# ---------------------------------------------------------------- chunk / page level
+def py_select_units(sc, unit, budget, n_imp, kbit, anchor_fn):
+    """Independent page-level selection: big-int page vectors, pairwise-Hamming medoids."""
+    Hs, S = len(sc), len(sc[0])
+    tok_bits = [0] * S
+    for r in range(Hs):
+        for t in py_topk(sc[r], kbit):
+            tok_bits[t] |= 1 << r
+    tok_imp = []
+    for t in range(S):
+        acc = np.float32(0.0)
+        for r in range(Hs):
+            acc = np.float32(acc + np.float32(sc[r][t]))
+        tok_imp.append(acc)
+    Nu = S // unit
+    page_bits, page_imp = [], []
+    for u in range(Nu):
+        v, acc = 0, np.float32(0.0)
+        for j in range(unit):
+            v |= tok_bits[u * unit + j] << (j * Hs)       # concatenation, token by token
+            acc = np.float32(acc + tok_imp[u * unit + j])
+        page_bits.append(v)
+        page_imp.append(float(acc))
+    important = set(py_topk(page_imp, n_imp // unit))
+    anchor = anchor_fn(page_bits, important)
+    reps, _ = py_group(page_bits, important, (budget - n_imp) // unit, anchor)
+    pages = sorted(important | set(reps))
+    idx = [u * unit + j for u in pages for j in range(unit)]
+    kind = [1 if u in reps else 0 for u in pages for _ in range(unit)]
+    return idx, kind, page_bits
+
+
+@pytest.mark.parametrize("B,Hs,S,unit,budget,n_imp,kbit,sink,recent,anchor", [
+    (2, 4, 96, 8, 32, 16, 0, 0, 0, "alternating"),       # chunks of 8 tokens
+    (1, 8, 256, 16, 96, 64, 0, 0, 0, "random"),          # 128-bit page vectors
+    (1, 8, 672 + 32, 32, 672, 384, 0, 32, 128, "random"),  # page size 32 with protected ends (Table 1's layout)
+    (2, 3, 90, 5, 40, 10, 50, 0, 0, "mean"),             # odd sizes; kbit > half: the mean anchor has one-bits
+    (1, 32, 128, 32, 64, 32, 0, 0, 0, "alternating"),    # 1024-bit page vectors
+    (1, 4, 64, 4, 64, 16, 0, 0, 0, "mean"),              # budget == S
+    (1, 4, 64, 4, 24, 0, 0, 4, 4, "alternating"),        # nothing important
+    (1, 4, 64, 4, 24, 24, 0, 0, 0, "alternating"),       # no representatives: paged top-k baseline
+])
+def test_unit_level_selection_matches_brute_force(oracle, B, Hs, S, unit, budget, n_imp, kbit, sink, recent, anchor):
+    sc = inputs.make_scores(B, Hs, S, seed=S + unit, ties=True)
+    idx, kind, ub = oracle.select_units(sc, unit, budget, n_imp, kbit, anchor, anchor_seed=4, n_sink=sink,
+                                        n_recent=recent)
+    Sm, Bm = S - sink - recent, budget - sink - recent
+    Hu = Hs * unit
+    Wu = (Hu + 63) // 64
+    for b in range(B):
+        def anchor_fn(bits, important):
+            if anchor == "alternating":
+                return alternating(Hu)
+            if anchor == "random":
+                z = oracle.splitmix64(4 + b, Wu)
+                return sum(z[w] << (64 * w) for w in range(Wu)) & ((1 << Hu) - 1)
+            disc = [u for u in range(len(bits)) if u not in important]
+            return sum(1 << r for r in range(Hu) if 2 * sum((bits[u] >> r) & 1 for u in disc) > len(disc))
+        mid = sc[b, :, sink:S - recent].tolist()
+        m_idx, m_kind, m_bits = py_select_units(mid, unit, Bm, n_imp, kbit or Bm, anchor_fn)
+        want_idx = list(range(sink)) + [t + sink for t in m_idx] + list(range(S - recent, S))
+        want_kind = [2] * sink + m_kind + [2] * recent
+        assert idx[b].tolist() == want_idx and kind[b].tolist() == want_kind
+        assert [words_to_int(ub[b, u]) for u in range(Sm // unit)] == m_bits
+        # whole units only
+        kept = idx[b, sink:budget - recent].view(-1, unit)
+        assert ((kept[:, 0] - sink) % unit == 0).all() and (kept[:, 1:] - kept[:, :-1] == 1).all()
+
+
+def test_unit_of_one_token_is_the_token_level_selection(oracle):
+    sc = inputs.make_scores(2, 8, 200, seed=8, ties=True)
+    for kw in (dict(), dict(n_sink=3, n_recent=10)):
+        a = oracle.select(sc, 60, 30, 0, "mean", 2, **kw)
+        b = oracle.select_units(sc, 1, 60, 30, 0, "mean", 2, **kw)
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+        mid = a[2][:, kw.get("n_sink", 0):200 - kw.get("n_recent", 0)]
+        assert torch.equal(mid, b[2])
+
+
+def test_unit_level_hand_worked_example(oracle):
+    """Two heads, pages of two tokens, eight tokens, per-head top-3.
+    head 0 = 9 8 .5 .25 1 0 5 .125 -> top-3 tokens {0, 1, 6};  head 1 = 8 .5 .5 .75 4 6 1 .375 -> {0, 5, 4}.
+    Token vectors (bit 0 = head 0): 3 1 0 0 2 2 1 0.  Page vectors (bit 2j + r): page 0 = 0111b,
+    page 1 = 0000b, page 2 = 1010b, page 3 = 0001b.  Page importance 17 + 8.5, 1 + 1, 5 + 6, 6 + .5:
+    page 0 is the one important page.  Alternating anchor 1010b: distances of pages 1, 2, 3 are 2, 0, 3,
+    so the order is 2, 1, 3; two buckets {2} and {1, 3}; in {1, 3} both members cost 1 and the lower
+    index wins: representatives 2 and 1.  Kept: pages 0, 1, 2 = tokens 0..5."""
+    sc = torch.tensor([[[9.0, 8.0, 0.5, 0.25, 1.0, 0.0, 5.0, 0.125],
+                        [8.0, 0.5, 0.5, 0.75, 4.0, 6.0, 1.0, 0.375]]])
+    _, _, tb = oracle.select(sc, 3, 3, 3, "alternating")
+    assert [int(x) for x in tb[0, :, 0].tolist()] == [3, 1, 0, 0, 2, 2, 1, 0]
+    idx, kind, ub = oracle.select_units(sc, 2, 6, 2, 3, "alternating")
+    assert [int(x) for x in ub[0, :, 0].tolist()] == [0b0111, 0b0000, 0b1010, 0b0001]
+    assert idx.tolist() == [[0, 1, 2, 3, 4, 5]] and kind.tolist() == [[0, 0, 1, 1, 1, 1]]
+    # with three buckets every grouped page is its own representative; with one, the medoid of
+    # {2, 1, 3} (pairwise distances 2-1: 2, 2-3: 3, 1-3: 1 -> costs 5, 3, 4) is page 1
+    idx1, kind1, _ = oracle.select_units(sc, 2, 4, 2, 3, "alternating")
+    assert idx1.tolist() == [[0, 1, 2, 3]] and kind1.tolist() == [[0, 0, 1, 1]]
