@@ -150,7 +150,7 @@ kvcrush_status kvcrush_pool_scores(int32_t rows, int32_t S, int32_t kernel, cons
  * result is unique for a given score tensor.
  */
 typedef struct {
-  int32_t B, Hs, S;        /* Hs score rows per sequence, 1 <= Hs <= 128               */
+  int32_t B, Hs, S;        /* Hs score rows per sequence, 1 <= Hs <= 1024              */
   int32_t budget;          /* tokens kept per sequence, 0 <= budget <= S               */
   int32_t n_important;     /* 0 <= n_important <= budget; the rest are representatives */
   int32_t bit_topk;        /* per-head top-k that sets a bit; 0 means `budget`         */
@@ -164,6 +164,15 @@ typedef struct {
                            /* budget - n_sink - n_recent tokens exactly as a sequence  */
                            /* of their own: n_important <= that number, bit_topk = 0   */
                            /* means that number, bit_topk <= middle length.  0, 0: off */
+  int32_t unit;            /* 0 or 1: tokens are selected.  P > 1: chunk- / page-level  */
+                           /* selection (Sec. 4.3.4, 4.3.5) on units of P consecutive   */
+                           /* middle tokens: a unit's importance is the sum of its      */
+                           /* tokens' importances (token order), its bit vector the     */
+                           /* concatenation of its tokens' head vectors (bit j * Hs + r */
+                           /* = head r of its j-th token; anchors have Hs * P bits),    */
+                           /* and Alg. 2 runs on units.  budget, n_important and the    */
+                           /* middle's length stay in tokens and must be multiples of   */
+                           /* P; Hs * P <= 1024.  idx lists every token of a kept unit. */
   uint64_t anchor_seed;    /* RANDOM only                                              */
   const uint64_t* anchor_bits; /* EXPLICIT only: device [B, W], W = ceil(Hs / 64)      */
 } kvcrush_select_args;
@@ -174,7 +183,9 @@ size_t kvcrush_select_workspace(const kvcrush_select_args* args);
  *   kind    nullable [B, budget] uint8: 0 kept as important, 1 as representative,
  *           2 protected (n_sink / n_recent)
  *   bits    nullable [B, S, W] uint64: head r is bit r % 64 of word r / 64; zero
- *           words for protected tokens
+ *           words for protected tokens.  With unit = P > 1: [B, Nu, Wu], one
+ *           vector of Wu = ceil(Hs * P / 64) words per unit of the middle
+ *           (Nu = (S - n_sink - n_recent) / P)
  */
 kvcrush_status kvcrush_select(const kvcrush_select_args* args, const float* scores, int32_t* idx,
                               uint8_t* kind, uint64_t* bits, void* workspace,

@@ -39,7 +39,7 @@ class Shape(ctypes.Structure):
 
 class SelectArgs(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hs", "S", "budget", "n_important", "bit_topk", "anchor",
-                                                 "score_stride", "n_sink", "n_recent")] + [
+                                                 "score_stride", "n_sink", "n_recent", "unit")] + [
         ("anchor_seed", ctypes.c_uint64), ("anchor_bits", ctypes.c_void_p)]
 
 
@@ -195,9 +195,9 @@ def lse_from_workspace(workspace: torch.Tensor, B: int, Hq: int, S: int) -> torc
 
 
 def make_select_args(B, Hs, S, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
-                     anchor_bits=None, n_sink=0, n_recent=0, score_stride=0) -> SelectArgs:
+                     anchor_bits=None, n_sink=0, n_recent=0, score_stride=0, unit=0) -> SelectArgs:
     return SelectArgs(B, Hs, S, budget, n_important, bit_topk, ANCHORS[anchor] if isinstance(anchor, str) else anchor,
-                      score_stride, n_sink, n_recent, anchor_seed & (2**64 - 1),
+                      score_stride, n_sink, n_recent, unit, anchor_seed & (2**64 - 1),
                       None if anchor_bits is None else anchor_bits.data_ptr())
 
 
@@ -207,7 +207,7 @@ def kvcrush_select_workspace(args: SelectArgs) -> int:
 
 def kvcrush_select(scores, budget, n_important, bit_topk=0, anchor="alternating", anchor_seed=0,
                    anchor_bits=None, want_kind=True, want_bits=False, idx=None, workspace=None, stream=None,
-                   n_sink=0, n_recent=0, valid_len=None):
+                   n_sink=0, n_recent=0, valid_len=None, unit=0):
     """scores [B,Hs,S] fp32 on the GPU -> (idx int32 [B,budget], kind uint8 | None, bits int64 [B,S,W] | None).
     n_sink / n_recent tokens at the two ends are always kept; the rest of the budget goes to the middle.
     valid_len: scores is a capacity-strided cache [B,Hs,capacity] of which the first valid_len tokens count."""
@@ -221,13 +221,16 @@ def kvcrush_select(scores, budget, n_important, bit_topk=0, anchor="alternating"
     if anchor_bits is not None:
         anchor_bits = _dev(anchor_bits, "anchor_bits")
     args = make_select_args(B, Hs, S, budget, n_important, bit_topk, anchor, anchor_seed, anchor_bits,
-                            n_sink, n_recent, stride)
+                            n_sink, n_recent, stride, unit)
     dev = scores.device
     if idx is None:
         idx = torch.empty(B, budget, dtype=torch.int32, device=dev)
     kind = torch.empty(B, budget, dtype=torch.uint8, device=dev) if want_kind else None
-    W = (Hs + 63) // 64
-    bits = torch.empty(B, S, W, dtype=torch.int64, device=dev) if want_bits else None
+    if unit > 1:   # one vector of Hs * unit bits per unit of the middle
+        bits_shape = (B, max(S - n_sink - n_recent, 0) // unit, (Hs * unit + 63) // 64)
+    else:
+        bits_shape = (B, S, (Hs + 63) // 64)
+    bits = torch.empty(bits_shape, dtype=torch.int64, device=dev) if want_bits else None
     if workspace is None:
         workspace = torch.empty(max(kvcrush_select_workspace(args), 16), dtype=torch.uint8, device=dev)
     st = load().kvcrush_select(ctypes.byref(args), _ptr(scores), _ptr(idx), _ptr(kind), _ptr(bits),

@@ -23,6 +23,8 @@
 //                         integer cost, wave arg-min with token tie-break.
 //   K4 emit_kernel        ordered compaction of (important | representative)
 //                         bitmaps into the ascending index list.
+#include <algorithm>
+
 #include "common.h"
 
 namespace {
@@ -32,7 +34,7 @@ using kvc::lanemask_lt;
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / KVC_WAVE;
-constexpr int kMaxHs = 128;
+constexpr int kMaxHs = 1024;  // bits per grouped item: score rows x tokens per unit
 constexpr int kMaxW = kMaxHs / 64;
 
 // Order-preserving map from fp32 to uint32 (larger float -> larger key);
@@ -86,6 +88,7 @@ struct TopkParams {
   uint32_t* keys_ws;    // [B,Hs+1,S] when the row does not fit LDS, else null
   int Hs, S, nw, kbit, n_important;  // S = selectable tokens per row (the middle, when ends are protected)
   int ld;               // row stride of `scores` in floats (the full sequence length)
+  int unit;             // tokens per selection unit; the importance row then ranks S / unit units
 };
 
 // Block-wide exclusive prefix sum of one int per thread, in thread order.
@@ -117,9 +120,14 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 
   const int row = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
-  const int S = p.S, Hs = p.Hs, nw = p.nw;
+  const int Hs = p.Hs;
+  // score rows rank tokens; the importance row ranks units of p.unit tokens (Sec. 4.3.5: a
+  // page's importance is that of its tokens added up)
+  const bool unit_row = row == Hs && p.unit > 1;
+  const int S = unit_row ? p.S / p.unit : p.S;
+  const int nw = unit_row ? (S + 63) / 64 : p.nw;
   const int k = row < Hs ? p.kbit : p.n_important;
-  uint64_t* __restrict__ mask_out = p.rowmask + ((size_t)b * (Hs + 1) + row) * nw;
+  uint64_t* __restrict__ mask_out = p.rowmask + ((size_t)b * (Hs + 1) + row) * p.nw;
 
   if (k == 0 || k == S) {  // nothing or everything: no search needed
     for (int c = tid; c < nw; c += kSelThreads) {
@@ -133,7 +141,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
     return;
   }
 
-  uint32_t* __restrict__ gkeys = KEYS_IN_LDS ? nullptr : p.keys_ws + ((size_t)b * (Hs + 1) + row) * S;
+  uint32_t* __restrict__ gkeys = KEYS_IN_LDS ? nullptr : p.keys_ws + ((size_t)b * (Hs + 1) + row) * p.S;
   auto key_at = [&](int t) -> uint32_t { return KEYS_IN_LDS ? lds_keys[t] : gkeys[t]; };
   auto key_put = [&](int t, uint32_t v) {
     if (KEYS_IN_LDS) lds_keys[t] = v; else gkeys[t] = v;
@@ -142,8 +150,21 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   const size_t ld = (size_t)p.ld;
 
   for (int i = tid; i < kRadixBins; i += kSelThreads) hist[i] = 0;
+  if (unit_row) {
+    // unit importance: token importances (fp32 sum of the rows, row order) added in token order
+    for (int u = tid; u < S; u += kSelThreads) {
+      float acc = 0.0f;
+      for (int j = 0; j < p.unit; ++j) {
+        const size_t t = (size_t)u * p.unit + j;
+        float tok = 0.0f;
+        for (int r = 0; r < Hs; ++r) tok = tok + sc[(size_t)r * ld + t];
+        acc = acc + tok;
+      }
+      key_put(u, float_key(acc));
+    }
+  }
   // keys: kBatch tokens per thread at a time so that their loads overlap
-  for (int t0 = tid; t0 < S; t0 += kBatch * kSelThreads) {
+  for (int t0 = tid; t0 < (unit_row ? 0 : S); t0 += kBatch * kSelThreads) {
     float v[kBatch];
     if (row < Hs) {
 #pragma unroll
@@ -269,6 +290,46 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   }
 }
 
+// ------------------------------------------------------------- K1b (units) --
+// Chunk- / page-level selection (Sec. 4.3.4, 4.3.5): the binary vector of a unit
+// of `unit` tokens is the concatenation of its tokens' head vectors, bit
+// j * Hs + r = head r of the unit's j-th token.  Rewritten as bitmaps over units,
+// that is Hs * unit "virtual rows": row j * Hs + r holds, for unit u, bit
+// u * unit + j of token row r.  After this de-interleave the grouping kernels
+// run on units exactly as they do on tokens.
+struct UnitRowsParams {
+  const uint64_t* rowmask_tok;  // [B,Hs+1,nw_tok]; row Hs: important UNITS in its first nw_unit words
+  uint64_t* rowmask_unit;       // [B,Hs*unit+1,nw_unit]
+  int Hs, unit, n_units, nw_tok, nw_unit;
+};
+
+__global__ __launch_bounds__(256) void unit_rows_kernel(UnitRowsParams p) {
+  const int b = blockIdx.y, lane = lane_id();
+  const int Hv = p.Hs * p.unit;
+  const uint64_t* __restrict__ src = p.rowmask_tok + (size_t)b * (p.Hs + 1) * p.nw_tok;
+  uint64_t* __restrict__ dst = p.rowmask_unit + (size_t)b * (Hv + 1) * p.nw_unit;
+  // one wave per output word
+  const long long n_words = (long long)(Hv + 1) * p.nw_unit;
+  const long long wave0 = (long long)blockIdx.x * 4 + threadIdx.x / KVC_WAVE;
+  for (long long i = wave0; i < n_words; i += (long long)gridDim.x * 4) {
+    const int row = (int)(i / p.nw_unit), c = (int)(i % p.nw_unit);
+    uint64_t word;
+    if (row == Hv) {
+      word = src[(size_t)p.Hs * p.nw_tok + c];
+    } else {
+      const int j = row / p.Hs, r = row % p.Hs;
+      const int u = c * 64 + lane;
+      bool bit = false;
+      if (u < p.n_units) {
+        const long long t = (long long)u * p.unit + j;
+        bit = (src[(size_t)r * p.nw_tok + (t >> 6)] >> (t & 63)) & 1ull;
+      }
+      word = __ballot(bit);
+    }
+    if (lane == 0) dst[i] = word;
+  }
+}
+
 // ------------------------------------------------------------------ K2 ----
 // The grouping of one sequence is spread over many small workgroups: the token
 // range is dealt out in contiguous runs of 64-token chunks to "global waves"
@@ -279,12 +340,13 @@ constexpr int kGsThreads = 256;
 constexpr int kGsWaves = kGsThreads / KVC_WAVE;
 constexpr int kGsChunksPerWg = 16;  // 1024 tokens a workgroup
 constexpr uint32_t kNotGrouped = 0xFFFFFFFFu;
+constexpr int kDistBits = 12;  // distances range over 0..kMaxHs
 
 struct GroupParams {
   const uint64_t* rowmask;      // [B,Hs+1,nw]
   uint64_t* bits;               // words of token 0 of sequence 0; sequences are bits_stride tokens apart
   size_t bits_stride;
-  uint32_t* dist_rank;          // [B,S]: distance | rank-in-wave << 8, or kNotGrouped
+  uint32_t* dist_rank;          // [B,S]: distance | rank-in-wave << kDistBits, or kNotGrouped
   int32_t* counts;              // [B,Hs+1,n_gw] tokens per (distance, global wave)
   int32_t* order;               // [B,S]: first N entries = grouped tokens by (d,t)
   uint64_t* repmask;            // [B,nw], zeroed by K2a
@@ -302,11 +364,14 @@ __device__ __forceinline__ uint64_t splitmix64_next(uint64_t& state) {
   return z ^ (z >> 31);
 }
 
+// WMAX: 64-bit words a bit vector may have (2 covers up to 128 score rows, kMaxW the page-level
+// vectors); loops over the words are unrolled so that the words stay in registers.
+template <int WMAX>
 __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
   extern __shared__ uint64_t lds_words[];       // this workgroup's slice [Hs+1][kGsChunksPerWg]
-  __shared__ int run[kGsWaves][kMaxHs + 1];     // per wave: tokens seen so far per distance
-  __shared__ int head_cnt[kMaxHs];
-  __shared__ uint64_t sh_anchor[kMaxW];
+  __shared__ int run[kGsWaves][WMAX * 64 + 1];  // per wave: tokens seen so far per distance
+  __shared__ int head_cnt[WMAX * 64];
+  __shared__ uint64_t sh_anchor[WMAX];
 
   const int b = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
   const int S = p.S, Hs = p.Hs, nw = p.nw, W = p.W;
@@ -320,8 +385,8 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
     lds_words[i] = c < wg_nc ? rm[(size_t)r * nw + wg_c0 + c] : 0ull;
   }
   for (int c = tid; c < wg_nc; c += kGsThreads) p.repmask[(size_t)b * nw + wg_c0 + c] = 0ull;
-  for (int i = tid; i < kGsWaves * (kMaxHs + 1); i += kGsThreads) (&run[0][0])[i] = 0;
-  if (tid < kMaxHs) head_cnt[tid] = 0;
+  for (int i = tid; i < kGsWaves * (WMAX * 64 + 1); i += kGsThreads) (&run[0][0])[i] = 0;
+  for (int i = tid; i < WMAX * 64; i += kGsThreads) head_cnt[i] = 0;
   __syncthreads();
 
   // ---- anchor (Alg. 2, first step); every workgroup derives the same one
@@ -354,9 +419,9 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
     sh_anchor[tid] = a;
   }
   __syncthreads();
-  uint64_t anchor[kMaxW];
+  uint64_t anchor[WMAX];
 #pragma unroll
-  for (int w = 0; w < kMaxW; ++w) anchor[w] = w < W ? sh_anchor[w] : 0ull;
+  for (int w = 0; w < WMAX; ++w) anchor[w] = w < W ? sh_anchor[w] : 0ull;
 
   // ---- this wave's chunks: bit words out, distance, stable rank inside the wave
   const int gw = blockIdx.x * kGsWaves + wave;
@@ -365,21 +430,30 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
   for (int c = c0; c < c1; ++c) {
     const int lc = c - wg_c0;
     const int t = c * 64 + lane;
-    uint64_t bw[kMaxW] = {0ull, 0ull};
-    for (int r = 0; r < Hs; ++r) {
-      const uint64_t word = lds_words[r * kGsChunksPerWg + lc];  // same address for the whole wave
-      bw[r >> 6] |= ((word >> lane) & 1ull) << (r & 63);
+    uint64_t bw[WMAX];
+    uint32_t d = 0;
+#pragma unroll
+    for (int w = 0; w < WMAX; ++w) {
+      uint64_t acc = 0ull;
+      const int nb = min(64, Hs - 64 * w);  // rows in this word (<= 0: none)
+      for (int rr = 0; rr < nb; ++rr) {
+        const uint64_t word = lds_words[(64 * w + rr) * kGsChunksPerWg + lc];  // same address for the whole wave
+        acc |= ((word >> lane) & 1ull) << rr;
+      }
+      bw[w] = acc;
+      d += (uint32_t)__popcll(acc ^ anchor[w]);
     }
     const bool grouped = t < S && !((lds_words[Hs * kGsChunksPerWg + lc] >> lane) & 1ull);
     if (t < S) {
-      for (int w = 0; w < W; ++w) p.bits[((size_t)b * p.bits_stride + t) * W + w] = bw[w];
+#pragma unroll
+      for (int w = 0; w < WMAX; ++w)
+        if (w < W) p.bits[((size_t)b * p.bits_stride + t) * W + w] = bw[w];
     }
-    const uint32_t d = (uint32_t)(__popcll(bw[0] ^ anchor[0]) + __popcll(bw[1] ^ anchor[1]));
     const uint64_t peers = match_peers(d, p.dbits, grouped);
     uint32_t packed = kNotGrouped;
     if (grouped) {
       const int base = run[wave][d];
-      packed = d | ((uint32_t)(base + __popcll(peers & lanemask_lt())) << 8);
+      packed = d | ((uint32_t)(base + __popcll(peers & lanemask_lt())) << kDistBits);
       if (lane == __ffsll((unsigned long long)peers) - 1) run[wave][d] = base + __popcll(peers);
     }
     if (t < S) p.dist_rank[(size_t)b * S + t] = packed;
@@ -425,7 +499,8 @@ __global__ __launch_bounds__(kGsThreads) void group_scatter_kernel(GroupParams p
     const int t = c * 64 + lane;
     if (t < S) {
       const uint32_t packed = p.dist_rank[(size_t)b * S + t];
-      if (packed != kNotGrouped) order[lds_base[(packed & 255u) * p.n_gw + gw] + (int)(packed >> 8)] = t;
+      if (packed != kNotGrouped)
+        order[lds_base[(packed & ((1u << kDistBits) - 1u)) * p.n_gw + gw] + (int)(packed >> kDistBits)] = t;
     }
   }
 }
@@ -442,6 +517,7 @@ struct MedoidParams {
 constexpr int kMedoidThreads = 256;
 constexpr int kMedoidWaves = kMedoidThreads / KVC_WAVE;
 
+template <int WMAX>
 __global__ __launch_bounds__(kMedoidThreads) void medoid_kernel(MedoidParams p) {
   const int b = blockIdx.y, lane = lane_id(), wave = threadIdx.x / KVC_WAVE;
   const int j = blockIdx.x * kMedoidWaves + wave;  // bucket of this wave
@@ -452,34 +528,37 @@ __global__ __launch_bounds__(kMedoidThreads) void medoid_kernel(MedoidParams p) 
   const int32_t* order = p.order + (size_t)b * p.S + lo;
   const uint64_t* bits = p.bits + (size_t)b * p.bits_stride * W;
 
-  // per-head member counts: lane l keeps heads l and l+64
-  int cnt[kMaxW] = {0, 0};
+  // per-bit member counts: lane l keeps bits l, l + 64, ...
+  int cnt[WMAX];
+#pragma unroll
+  for (int w = 0; w < WMAX; ++w) cnt[w] = 0;
   for (int m0 = 0; m0 < n; m0 += KVC_WAVE) {
     const int m = m0 + lane;
-    uint64_t bw[kMaxW] = {0ull, 0ull};
-    if (m < n) {
-      const int t = order[m];
-      for (int w = 0; w < W; ++w) bw[w] = bits[(size_t)t * W + w];
-    }
-    for (int r = 0; r < Hs; ++r) {
-      const int c = __popcll(__ballot((bw[r >> 6] >> (r & 63)) & 1ull));
-      if (lane == (r & 63)) cnt[r >> 6] += c;
+    const int t = m < n ? order[m] : 0;
+#pragma unroll
+    for (int w = 0; w < WMAX; ++w) {
+      const uint64_t bw = (m < n && w < W) ? bits[(size_t)t * W + w] : 0ull;
+      const int nb = min(64, Hs - 64 * w);
+      for (int rr = 0; rr < nb; ++rr) {
+        const int c = __popcll(__ballot((bw >> rr) & 1ull));
+        if (lane == rr) cnt[w] += c;
+      }
     }
   }
   // cost = summed Hamming distance to the members; keep (cost, token) minimum
   unsigned long long best = ~0ull;
   for (int m0 = 0; m0 < n; m0 += KVC_WAVE) {
     const int m = m0 + lane;
-    uint64_t bw[kMaxW] = {0ull, 0ull};
-    int t = 0;
-    if (m < n) {
-      t = order[m];
-      for (int w = 0; w < W; ++w) bw[w] = bits[(size_t)t * W + w];
-    }
+    const int t = m < n ? order[m] : 0;
     unsigned int cost = 0;
-    for (int r = 0; r < Hs; ++r) {
-      const int c = __shfl(cnt[r >> 6], r & 63);
-      cost += ((bw[r >> 6] >> (r & 63)) & 1ull) ? (unsigned)(n - c) : (unsigned)c;
+#pragma unroll
+    for (int w = 0; w < WMAX; ++w) {
+      const uint64_t bw = (m < n && w < W) ? bits[(size_t)t * W + w] : 0ull;
+      const int nb = min(64, Hs - 64 * w);
+      for (int rr = 0; rr < nb; ++rr) {
+        const int c = __shfl(cnt[w], rr);
+        cost += ((bw >> rr) & 1ull) ? (unsigned)(n - c) : (unsigned)c;
+      }
     }
     if (m < n) {
       const unsigned long long key = ((unsigned long long)cost << 32) | (unsigned)t;
@@ -510,6 +589,7 @@ struct EmitParams {
   int n_sink, n_recent, S_full, budget_full;
   uint64_t* bits_user;   // caller's bit words [B,S_full,W] or null: protected tokens get zero words
   int W;
+  int unit;              // tokens per selected item: every kept item expands to `unit` indices
 };
 
 __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
@@ -555,8 +635,11 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
       if ((kw >> lane) & 1ull) {
         const int o = sh_base[j] + __popcll(kw & lanemask_lt());
         if (o < p.budget) {  // always true for consistent masks; keeps stores in bounds regardless
-          idx_out[o] = (w0 + j) * 64 + lane + p.n_sink;
-          if (kind_out) kind_out[o] = (uint8_t)((rj >> lane) & 1ull);
+          const int item = (w0 + j) * 64 + lane;
+          for (int e = 0; e < p.unit; ++e) {
+            idx_out[(size_t)o * p.unit + e] = item * p.unit + e + p.n_sink;
+            if (kind_out) kind_out[(size_t)o * p.unit + e] = (uint8_t)((rj >> lane) & 1ull);
+          }
         }
       }
     }
@@ -566,42 +649,24 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
 }
 
 // ------------------------------------------------------------- host side ---
-struct SelectLayout {
-  size_t rowmask, repmask, bits, order, dist_rank, counts, keys, total;
-  int nw, W, n_wg, n_gw;  // grouping workgroups / global waves per sequence
+// What the kernels work on.  K1 ranks TOKENS (the middle ones, when ends are
+// protected) per score row; the grouping, the representatives and the emitted
+// list work on ITEMS: tokens, or units of `unit` tokens whose bit vectors have
+// Hs * unit bits.
+struct SelectPlan {
+  int unit, S_tok, nw_tok;     // tokens between the protected ends, their 64-token words
+  int n_items, nw, Hv, W;      // items, their 64-item words, bits per item, 64-bit words per item
+  int budget_items, imp_items; // kept / important items
+  int n_wg, n_gw;              // grouping workgroups / global waves per sequence
   bool keys_in_lds;
+  // workspace offsets
+  size_t rowmask_tok, rowmask, repmask, bits, order, dist_rank, counts, keys, total;
 };
 
 // The radix select keeps a row's keys in LDS when they fit beside the static
 // arrays (160 KiB of LDS per workgroup on gfx950); longer rows go through the
 // workspace instead.
 constexpr int kLdsKeyCapacity = 36864;  // 144 KiB of keys
-
-SelectLayout select_layout(const kvcrush_select_args* a, bool need_bits_ws) {
-  SelectLayout L;
-  L.nw = (a->S + 63) / 64;
-  L.W = (a->Hs + 63) / 64;
-  L.keys_in_lds = a->S <= kLdsKeyCapacity;
-  size_t off = 0;
-  L.rowmask = off;
-  off += kvc::align_up((size_t)a->B * (a->Hs + 1) * L.nw * 8, 256);
-  L.repmask = off;
-  off += kvc::align_up((size_t)a->B * L.nw * 8, 256);
-  L.order = off;
-  off += kvc::align_up((size_t)a->B * a->S * 4, 256);
-  L.n_wg = (L.nw + kGsChunksPerWg - 1) / kGsChunksPerWg;
-  L.n_gw = L.n_wg * kGsWaves;
-  L.dist_rank = off;
-  off += kvc::align_up((size_t)a->B * a->S * 4, 256);
-  L.counts = off;
-  off += kvc::align_up((size_t)a->B * (a->Hs + 1) * L.n_gw * 4, 256);
-  L.bits = off;
-  if (need_bits_ws) off += kvc::align_up((size_t)a->B * a->S * L.W * 8, 256);
-  L.keys = off;
-  if (!L.keys_in_lds) off += kvc::align_up((size_t)a->B * (a->Hs + 1) * a->S * 4, 256);
-  L.total = off;
-  return L;
-}
 
 bool select_args_ok(const kvcrush_select_args* a) {
   if (!a) return false;
@@ -614,26 +679,91 @@ bool select_args_ok(const kvcrush_select_args* a) {
   if (a->bit_topk < 0 || a->bit_topk > a->S - prot) return false;
   if (a->anchor < KVCRUSH_ANCHOR_RANDOM || a->anchor > KVCRUSH_ANCHOR_EXPLICIT) return false;
   if (a->anchor == KVCRUSH_ANCHOR_EXPLICIT && !a->anchor_bits) return false;
+  if (a->unit < 0) return false;
+  const int unit = a->unit > 1 ? a->unit : 1;
+  if ((a->S - prot) % unit != 0 || (a->budget - prot) % unit != 0 || a->n_important % unit != 0)
+    return false;
   return true;
 }
 
-// The selection proper runs on the tokens between the protected ends, as on a
-// sequence of its own.
-kvcrush_select_args middle_args(const kvcrush_select_args* a) {
-  kvcrush_select_args m = *a;
-  m.S = a->S - a->n_sink - a->n_recent;
-  m.budget = a->budget - a->n_sink - a->n_recent;
-  m.n_sink = m.n_recent = 0;
-  return m;
+// Sizes supported by the kernels (beyond what the arguments' own consistency demands).
+bool select_args_supported(const kvcrush_select_args* a) {
+  const long long unit = a->unit > 1 ? a->unit : 1;
+  return a->Hs * unit <= kMaxHs;
+}
+
+SelectPlan select_plan(const kvcrush_select_args* a, bool need_bits_ws) {
+  SelectPlan P;
+  P.unit = a->unit > 1 ? a->unit : 1;
+  P.S_tok = a->S - a->n_sink - a->n_recent;
+  P.nw_tok = (P.S_tok + 63) / 64;
+  P.n_items = P.S_tok / P.unit;
+  P.nw = (P.n_items + 63) / 64;
+  P.Hv = a->Hs * P.unit;
+  P.W = (P.Hv + 63) / 64;
+  P.budget_items = (a->budget - a->n_sink - a->n_recent) / P.unit;
+  P.imp_items = a->n_important / P.unit;
+  P.keys_in_lds = P.S_tok <= kLdsKeyCapacity;
+  P.n_wg = (P.nw + kGsChunksPerWg - 1) / kGsChunksPerWg;
+  P.n_gw = P.n_wg * kGsWaves;
+  const size_t B = (size_t)a->B;
+  size_t off = 0;
+  P.rowmask_tok = off;
+  off += kvc::align_up(B * (a->Hs + 1) * P.nw_tok * 8, 256);
+  P.rowmask = P.rowmask_tok;  // token level: the same bitmaps
+  if (P.unit > 1) {
+    P.rowmask = off;
+    off += kvc::align_up(B * (P.Hv + 1) * P.nw * 8, 256);
+  }
+  P.repmask = off;
+  off += kvc::align_up(B * P.nw * 8, 256);
+  P.order = off;
+  off += kvc::align_up(B * P.n_items * 4, 256);
+  P.dist_rank = off;
+  off += kvc::align_up(B * P.n_items * 4, 256);
+  P.counts = off;
+  off += kvc::align_up(B * (P.Hv + 1) * P.n_gw * 4, 256);
+  P.bits = off;
+  if (need_bits_ws) off += kvc::align_up(B * P.n_items * P.W * 8, 256);
+  P.keys = off;
+  if (!P.keys_in_lds) off += kvc::align_up(B * (a->Hs + 1) * P.S_tok * 4, 256);
+  P.total = off;
+  return P;
+}
+
+template <int WMAX>
+kvcrush_status launch_grouping(const GroupParams& g, const MedoidParams& m, const SelectPlan& P, int B,
+                               int Br, hipStream_t stream) {
+  const size_t dyn_a = (size_t)(P.Hv + 1) * kGsChunksPerWg * 8;
+  if (dyn_a > 32 * 1024) {
+    if (hipFuncSetAttribute((const void*)group_rank_kernel<WMAX>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)dyn_a) != hipSuccess)
+      return KVCRUSH_ERR_HIP;
+  }
+  hipLaunchKernelGGL(group_rank_kernel<WMAX>, dim3(P.n_wg, B), dim3(kGsThreads), dyn_a, stream, g);
+  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  const size_t dyn_b = (size_t)(P.Hv + 1) * P.n_gw * 4;
+  if (dyn_b > 32 * 1024) {
+    if (hipFuncSetAttribute((const void*)group_scatter_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)dyn_b) != hipSuccess)
+      return KVCRUSH_ERR_HIP;
+  }
+  hipLaunchKernelGGL(group_scatter_kernel, dim3(P.n_wg, B), dim3(kGsThreads), dyn_b, stream, g);
+  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  if (Br > 0) {
+    hipLaunchKernelGGL(medoid_kernel<WMAX>, dim3((Br + kMedoidWaves - 1) / kMedoidWaves, B),
+                       dim3(kMedoidThreads), 0, stream, m);
+    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  }
+  return KVCRUSH_OK;
 }
 
 }  // namespace
 
 extern "C" size_t kvcrush_select_workspace(const kvcrush_select_args* args) {
-  if (!select_args_ok(args) || args->Hs > kMaxHs) return 0;
+  if (!select_args_ok(args) || !select_args_supported(args)) return 0;
   // sized for the case where the caller does not ask for the bit words
-  const kvcrush_select_args m = middle_args(args);
-  return select_layout(&m, true).total;
+  return select_plan(args, true).total;
 }
 
 extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const float* scores,
@@ -641,115 +771,121 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
                                          void* workspace, size_t workspace_bytes,
                                          void* hip_stream) {
   if (!select_args_ok(args)) return KVCRUSH_ERR_INVALID_ARG;
-  if (args->Hs > kMaxHs) return KVCRUSH_ERR_UNSUPPORTED;
+  if (!select_args_supported(args)) return KVCRUSH_ERR_UNSUPPORTED;
   if (!scores || (!idx && args->budget > 0)) return KVCRUSH_ERR_INVALID_ARG;
   if (!kvc::aligned16(scores) || !kvc::aligned16(workspace) || (bits && !kvc::aligned16(bits)))
     return KVCRUSH_ERR_INVALID_ARG;
-  const kvcrush_select_args mid = middle_args(args);
-  const SelectLayout L = select_layout(&mid, bits == nullptr);
-  if (L.total > 0 && (!workspace || workspace_bytes < L.total)) return KVCRUSH_ERR_WORKSPACE;
+  const SelectPlan P = select_plan(args, bits == nullptr);
+  if (P.total > 0 && (!workspace || workspace_bytes < P.total)) return KVCRUSH_ERR_WORKSPACE;
+  // LDS tables of the grouping: (bits + 1) x 16 chunk words, (bits + 1) x global waves counters
+  if ((size_t)(P.Hv + 1) * kGsChunksPerWg * 8 > 136 * 1024 || (size_t)(P.Hv + 1) * P.n_gw * 4 > 120 * 1024)
+    return KVCRUSH_ERR_UNSUPPORTED;
 
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  // from here on S, budget are those of the middle; S_full is the row length
-  const int B = args->B, Hs = args->Hs, S = mid.S, S_full = args->S, budget = mid.budget;
-  const int Br = budget - args->n_important, N = S - args->n_important;
-  const int kbit = args->bit_topk == 0 ? budget : args->bit_topk;
-  uint64_t* rowmask = (uint64_t*)(ws + L.rowmask);
-  uint64_t* repmask = (uint64_t*)(ws + L.repmask);
-  int32_t* order = (int32_t*)(ws + L.order);
-  uint64_t* bits_buf = bits ? bits + (size_t)args->n_sink * L.W : (uint64_t*)(ws + L.bits);
-  const size_t bits_stride = bits ? (size_t)S_full : (size_t)S;
+  const int B = args->B, Hs = args->Hs, S_full = args->S;
+  const int Br = P.budget_items - P.imp_items, N = P.n_items - P.imp_items;
+  const int kbit = args->bit_topk == 0 ? args->budget - args->n_sink - args->n_recent : args->bit_topk;
+  uint64_t* rowmask_tok = (uint64_t*)(ws + P.rowmask_tok);
+  uint64_t* rowmask = (uint64_t*)(ws + P.rowmask);
+  uint64_t* repmask = (uint64_t*)(ws + P.repmask);
+  int32_t* order = (int32_t*)(ws + P.order);
+  // caller's bit words: [B,S,W] per token (protected tokens included), or [B,n_items,W] per unit
+  const bool token_level = P.unit == 1;
+  uint64_t* bits_buf = !bits ? (uint64_t*)(ws + P.bits) : (token_level ? bits + (size_t)args->n_sink * P.W : bits);
+  const size_t bits_stride = (bits && token_level) ? (size_t)S_full : (size_t)P.n_items;
 
-  if (S > 0) {
+  if (P.n_items > 0) {
     TopkParams p;
     p.scores = scores + args->n_sink;
     p.ld = args->score_stride ? args->score_stride : S_full;
-    p.rowmask = rowmask;
-    p.keys_ws = L.keys_in_lds ? nullptr : (uint32_t*)(ws + L.keys);
+    p.unit = P.unit;
+    p.rowmask = rowmask_tok;
+    p.keys_ws = P.keys_in_lds ? nullptr : (uint32_t*)(ws + P.keys);
     p.Hs = Hs;
-    p.S = S;
-    p.nw = L.nw;
+    p.S = P.S_tok;
+    p.nw = P.nw_tok;
     p.kbit = kbit;
-    p.n_important = args->n_important;
-    const size_t dyn = L.keys_in_lds ? (size_t)S * 4 : 0;
+    p.n_important = P.imp_items;
+    const size_t dyn = P.keys_in_lds ? (size_t)P.S_tok * 4 : 0;
     if (dyn > 48 * 1024) {
       if (hipFuncSetAttribute((const void*)topk_mask_kernel<true>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn) != hipSuccess)
         return KVCRUSH_ERR_HIP;
     }
-    if (L.keys_in_lds)
+    if (P.keys_in_lds)
       hipLaunchKernelGGL(topk_mask_kernel<true>, dim3(Hs + 1, B), dim3(kSelThreads), dyn, stream, p);
     else
       hipLaunchKernelGGL(topk_mask_kernel<false>, dim3(Hs + 1, B), dim3(kSelThreads), 0, stream, p);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
-  if (S > 0) {
-    GroupParams p;
-    p.rowmask = rowmask;
-    p.bits = bits_buf;
-    p.bits_stride = bits_stride;
-    p.dist_rank = (uint32_t*)(ws + L.dist_rank);
-    p.counts = (int32_t*)(ws + L.counts);
-    p.order = order;
-    p.repmask = repmask;
-    p.anchor_bits = args->anchor_bits;
-    p.anchor_seed = args->anchor_seed;
+  if (P.n_items > 0 && !token_level) {
+    UnitRowsParams p;
+    p.rowmask_tok = rowmask_tok;
+    p.rowmask_unit = rowmask;
     p.Hs = Hs;
-    p.S = S;
-    p.nw = L.nw;
-    p.W = L.W;
-    p.N = N;
-    p.anchor_mode = args->anchor;
-    int dbits = 0;
-    while ((1 << dbits) <= Hs) ++dbits;  // distances range over 0..Hs
-    p.dbits = dbits;
-    p.n_gw = L.n_gw;
-    const size_t dyn_a = (size_t)(Hs + 1) * kGsChunksPerWg * 8;  // <= 16.5 KiB
-    hipLaunchKernelGGL(group_rank_kernel, dim3(L.n_wg, B), dim3(kGsThreads), dyn_a, stream, p);
-    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-    const size_t dyn_b = (size_t)(Hs + 1) * L.n_gw * 4;
-    if (dyn_b > 120 * 1024) return KVCRUSH_ERR_UNSUPPORTED;  // Hs * S beyond ~60M: table too large for LDS
-    if (dyn_b > 32 * 1024) {
-      if (hipFuncSetAttribute((const void*)group_scatter_kernel,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_b) != hipSuccess)
-        return KVCRUSH_ERR_HIP;
-    }
-    hipLaunchKernelGGL(group_scatter_kernel, dim3(L.n_wg, B), dim3(kGsThreads), dyn_b, stream, p);
+    p.unit = P.unit;
+    p.n_units = P.n_items;
+    p.nw_tok = P.nw_tok;
+    p.nw_unit = P.nw;
+    const long long words = (long long)(P.Hv + 1) * P.nw;
+    const int gx = (int)std::min<long long>((words + 3) / 4, 2048);
+    hipLaunchKernelGGL(unit_rows_kernel, dim3(gx, B), dim3(256), 0, stream, p);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
-  if (Br > 0) {
-    MedoidParams p;
-    p.bits = bits_buf;
-    p.bits_stride = bits_stride;
-    p.order = order;
-    p.repmask = repmask;
-    p.Hs = Hs;
-    p.S = S;
-    p.nw = L.nw;
-    p.W = L.W;
-    p.N = N;
-    p.Br = Br;
-    hipLaunchKernelGGL(medoid_kernel, dim3((Br + kMedoidWaves - 1) / kMedoidWaves, B),
-                       dim3(kMedoidThreads), 0, stream, p);
-    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  if (P.n_items > 0) {
+    GroupParams g;
+    g.rowmask = rowmask;
+    g.bits = bits_buf;
+    g.bits_stride = bits_stride;
+    g.dist_rank = (uint32_t*)(ws + P.dist_rank);
+    g.counts = (int32_t*)(ws + P.counts);
+    g.order = order;
+    g.repmask = repmask;
+    g.anchor_bits = args->anchor_bits;
+    g.anchor_seed = args->anchor_seed;
+    g.Hs = P.Hv;
+    g.S = P.n_items;
+    g.nw = P.nw;
+    g.W = P.W;
+    g.N = N;
+    g.anchor_mode = args->anchor;
+    int dbits = 0;
+    while ((1 << dbits) <= P.Hv) ++dbits;  // distances range over 0..Hv
+    g.dbits = dbits;
+    g.n_gw = P.n_gw;
+    MedoidParams m;
+    m.bits = bits_buf;
+    m.bits_stride = bits_stride;
+    m.order = order;
+    m.repmask = repmask;
+    m.Hs = P.Hv;
+    m.S = P.n_items;
+    m.nw = P.nw;
+    m.W = P.W;
+    m.N = N;
+    m.Br = Br;
+    const kvcrush_status st = P.W <= 2 ? launch_grouping<2>(g, m, P, B, Br, stream)
+                                       : launch_grouping<kMaxW>(g, m, P, B, Br, stream);
+    if (st != KVCRUSH_OK) return st;
   }
   if (args->budget > 0) {
     EmitParams p;
-    p.impmask_base = rowmask + (size_t)Hs * L.nw;
+    p.impmask_base = rowmask + (size_t)P.Hv * P.nw;
     p.repmask = repmask;
     p.idx = idx;
     p.kind = kind;
-    p.imp_stride = (size_t)(Hs + 1) * L.nw;
-    p.S = S;
-    p.nw = L.nw;
-    p.budget = budget;
+    p.imp_stride = (size_t)(P.Hv + 1) * P.nw;
+    p.S = P.n_items;
+    p.nw = P.nw;
+    p.budget = P.budget_items;
     p.n_sink = args->n_sink;
     p.n_recent = args->n_recent;
     p.S_full = S_full;
     p.budget_full = args->budget;
-    p.bits_user = bits;
-    p.W = L.W;
+    p.bits_user = token_level ? bits : nullptr;
+    p.W = P.W;
+    p.unit = P.unit;
     hipLaunchKernelGGL(emit_kernel, dim3(B), dim3(kSelThreads), 0, stream, p);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }

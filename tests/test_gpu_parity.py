@@ -108,6 +108,64 @@ def test_select_protected_ends(kv, oracle, B, Hs, S, budget, n_imp, kbit, sink, 
     check_select(kv, oracle, sc, budget, n_imp, kbit, anchor, seed=11, n_sink=sink, n_recent=recent)
 
 
+@pytest.mark.parametrize("B,Hs,S,unit,budget,n_imp,kbit,sink,recent,anchor", [
+    (2, 8, 1024, 8, 256, 192, 0, 0, 0, "alternating"),        # chunks of 8 tokens: 64-bit vectors
+    (1, 8, 4096, 16, 1024, 768, 0, 0, 0, "mean"),             # pages of 16: 128-bit vectors
+    (1, 8, 32768, 32, 1024, 768, 0, 0, 0, "random"),          # config-5 sizes, pages of 32: 256-bit vectors
+    (1, 8, 2080, 32, 672, 384, 0, 32, 128, "random"),         # Table 1: 32 initial + middle + 128 recent, page 32
+    (2, 32, 2048, 32, 512, 256, 0, 0, 0, "alternating"),      # one bit per query head: 1024-bit vectors
+    (2, 3, 900, 5, 400, 100, 500, 0, 0, "mean"),              # odd sizes; kbit > half: one-bits in the mean anchor
+    (1, 4, 640, 4, 640, 160, 0, 0, 0, "mean"),                # budget == S
+    (1, 4, 640, 4, 240, 0, 0, 40, 40, "alternating"),         # nothing important
+    (1, 4, 640, 4, 240, 240, 0, 0, 0, "alternating"),         # no representatives: the paged top-k baseline
+    (1, 12, 6000, 6, 1200, 600, 0, 0, 0, "random"),           # 72-bit vectors: a partly used second word
+])
+def test_select_units_matches_oracle(kv, oracle, B, Hs, S, unit, budget, n_imp, kbit, sink, recent, anchor):
+    say(f"unit-level select B={B} Hs={Hs} S={S} unit={unit} budget={budget} n_imp={n_imp} sink={sink} recent={recent}")
+    sc = inputs.make_scores(B, Hs, S, seed=S + unit, ties=True)
+    ends = dict(n_sink=sink, n_recent=recent)
+    idx, kind, bits = kv.kvcrush_select(sc.cuda(), budget, n_imp, kbit, anchor, 21, want_bits=True, unit=unit, **ends)
+    torch.cuda.synchronize()
+    ridx, rkind, rbits = oracle.select_units(sc, unit, budget, n_imp, kbit, anchor, 21, **ends)
+    assert torch.equal(bits.cpu(), rbits), "unit bit vectors differ"
+    assert torch.equal(idx.cpu(), ridx), "retained indices differ"
+    assert torch.equal(kind.cpu(), rkind)
+    idx2, _, _ = kv.kvcrush_select(sc.cuda(), budget, n_imp, kbit, anchor, 21, want_kind=False, unit=unit, **ends)
+    torch.cuda.synchronize()
+    assert torch.equal(idx2.cpu(), ridx)
+
+
+@pytest.mark.parametrize("Hs,S,budget,n_imp,anchor", [(129, 700, 200, 120, "random"), (300, 1000, 300, 100, "mean"),
+                                                       (1024, 512, 128, 64, "alternating")])
+def test_select_many_score_rows(kv, oracle, Hs, S, budget, n_imp, anchor):
+    """Token-level selection with more than 128 score rows (bit vectors of 3 to 16 words)."""
+    say(f"select with Hs={Hs} score rows")
+    sc = inputs.make_scores(1, Hs, S, seed=Hs, ties=True)
+    check_select(kv, oracle, sc, budget, n_imp, S * 3 // 5 if anchor == "mean" else 0, anchor, seed=2)
+
+
+def test_page_level_pipeline_on_a_paged_cache(kv, oracle):
+    """Scores -> page-level selection (page = the cache's 16-token block) -> gather from the paged pool."""
+    say("page-level selection on a paged cache")
+    w = inputs.Workload("t", 1, 8, 2, 2048, 128, "bf16", 512, 0.25, "alternating", True, paged=True, block_size=16)
+    seed = 31
+    q, k, v = inputs.make_qkv(w, seed)
+    sc, _ = kv.kvcrush_scores(q.cuda(), k.cuda(), True)
+    idx, kind, _ = kv.kvcrush_select(sc, 512, 384, 0, "alternating", 0, unit=16)
+    bt = inputs.make_block_table(w, seed)
+    kp, vp = inputs.to_paged(k.cuda(), bt, 16), inputs.to_paged(v.cuda(), bt, 16)
+    ko, vo = kv.kvcrush_compact(kp, vp, idx, block_table=bt.cuda(), block_size=16, dense_shape=(1, 2, 2048, 128))
+    torch.cuda.synchronize()
+    ridx, rkind, _ = oracle.select_units(sc.cpu(), 16, 512, 384, 0, "alternating", 0)
+    assert torch.equal(idx.cpu(), ridx) and torch.equal(kind.cpu(), rkind)
+    rk, rv = oracle.compact(k, v, ridx)
+    assert torch.equal(ko.cpu().view(torch.uint8), rk.view(torch.uint8))
+    assert torch.equal(vo.cpu().view(torch.uint8), rv.view(torch.uint8))
+    # whole blocks are kept: the reduced cache's block table is a gather of the old one
+    pages = idx.cpu()[0, ::16] // 16
+    assert torch.equal(idx.cpu()[0].view(-1, 16), (pages[:, None] * 16 + torch.arange(16)[None, :]).to(torch.int32))
+
+
 def test_per_layer_budgets_share_one_workspace(kv, oracle):
     """A pyramid of budgets over the layers (the PyramidKV pairing): budget and split
     are per-call arguments and the workspace sized for one call serves them all."""

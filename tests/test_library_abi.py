@@ -86,7 +86,12 @@ def test_select_rejects_bad_arguments(lib):
     assert call(mk(1, 8, 100, 50, 51)) == binding.ERR_INVALID_ARG            # n_important > budget
     assert call(mk(1, 8, 100, 50, 10, bit_topk=101)) == binding.ERR_INVALID_ARG
     assert call(mk(1, 0, 100, 50, 10)) == binding.ERR_INVALID_ARG
-    assert call(mk(1, 129, 100, 50, 10)) == binding.ERR_UNSUPPORTED          # more than 128 heads
+    assert call(mk(1, 1025, 100, 50, 10)) == binding.ERR_UNSUPPORTED         # more than 1024 bits per vector
+    assert call(mk(1, 64, 128, 64, 32, unit=32)) == binding.ERR_UNSUPPORTED  # 64 rows x 32 tokens = 2048 bits
+    assert call(mk(1, 8, 100, 48, 16, unit=8)) == binding.ERR_INVALID_ARG    # 100 tokens are not whole units
+    assert call(mk(1, 8, 96, 50, 16, unit=8)) == binding.ERR_INVALID_ARG     # nor is a budget of 50
+    assert call(mk(1, 8, 96, 48, 12, unit=8)) == binding.ERR_INVALID_ARG     # nor 12 important tokens
+    assert call(mk(1, 8, 96, 48, 16, unit=-2)) == binding.ERR_INVALID_ARG
     assert call(mk(1, 8, 100, 50, 10, anchor=9)) == binding.ERR_INVALID_ARG
     assert call(mk(1, 8, 100, 50, 10, anchor="explicit")) == binding.ERR_INVALID_ARG  # no anchor_bits
     assert call(mk(1, 8, 100, 50, 10), scores=None) == binding.ERR_INVALID_ARG
