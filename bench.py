@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--window", type=int, default=0,
                     help="observation window W: only the last W queries score the tokens (SnapKV-style scoring)")
     ap.add_argument("--pool", type=int, default=0, help="max-pool the scores with this odd kernel before selection")
+    ap.add_argument("--unit", type=int, default=0,
+                    help="chunk- / page-level selection on units of this many tokens (0: token level)")
     ap.add_argument("--decode", action="store_true",
                     help="time the decoding-time score append on caches of --cache-len tokens instead of the "
                          "per-layer compression step")
@@ -54,7 +56,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer, row_begin=0, pool=0):
+def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer, row_begin=0, pool=0, unit=0):
     """The oracle as it stands, single-threaded, on a bounded sample: every query
     row of ONE query head of layer 0 (1/Hq of the layer's score work), plus the
     full selection and gather of that layer.  Extrapolated to a whole layer."""
@@ -71,7 +73,10 @@ def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer, row_begin=0, pool=0):
     t0 = time.perf_counter()
     if pool:
         sc = oracle.maxpool(sc, pool)
-    idx, _, _ = oracle.select(sc, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(layer))
+    if unit > 1:
+        idx, _, _ = oracle.select_units(sc, unit, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(layer))
+    else:
+        idx, _, _ = oracle.select(sc, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(layer))
     t_sel = time.perf_counter() - t0
     kc, vc = k0.cpu(), v0.cpu()
     t0 = time.perf_counter()
@@ -187,7 +192,7 @@ def main():
     scores = torch.empty(w.B, Hs, w.S, dtype=torch.float32, device=dev)
     idx = torch.empty(w.B, w.budget, dtype=torch.int32, device=dev)
     sel_ws = torch.empty(kv.kvcrush_select_workspace(
-        kv.make_select_args(w.B, Hs, w.S, w.budget, w.n_important)), dtype=torch.uint8, device=dev)
+        kv.make_select_args(w.B, Hs, w.S, w.budget, w.n_important, unit=args.unit)), dtype=torch.uint8, device=dev)
     k_out = torch.empty(w.B, w.Hkv, w.budget, w.D, dtype=w.torch_dtype, device=dev)
     v_out = torch.empty_like(k_out)
 
@@ -205,7 +210,7 @@ def main():
         if pooled is not None:
             kv.kvcrush_pool_scores(scores, args.pool, out=pooled)
         kv.kvcrush_select(scores if pooled is None else pooled, w.budget, w.n_important, 0, w.anchor,
-                          inputs.anchor_seed(L), want_kind=False, idx=idx, workspace=sel_ws)
+                          inputs.anchor_seed(L), want_kind=False, idx=idx, workspace=sel_ws, unit=args.unit)
         if ev:
             ev[3].record()
         if w.paged:
@@ -276,7 +281,7 @@ def main():
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "S": w.S, "D": w.D,
                    "budget": w.budget, "n_important": w.n_important, "n_representative": w.n_rep,
                    "anchor": w.anchor, "reduce_groups": w.reduce_groups, "paged": w.paged,
-                   "resident_layers": n_layers, "obs_window": W, "pool_kernel": args.pool},
+                   "resident_layers": n_layers, "obs_window": W, "pool_kernel": args.pool, "unit": args.unit},
         "roofline": roofline, "stages": stages, "row_sum_check": ok,
     }
     if not args.no_cpu_baseline:
@@ -284,7 +289,7 @@ def main():
         step(0)
         torch.cuda.synchronize()
         out["cpu_baseline"] = cpu_baseline(w, layers[0]["q"], layers[0]["k"], layers[0]["v"], scores, 0,
-                                           q_first, args.pool)
+                                           q_first, args.pool, args.unit)
     print(json.dumps(out), flush=True)
 
 

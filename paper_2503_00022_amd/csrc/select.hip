@@ -227,8 +227,23 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int t = t0 + u * kSelThreads;
-        if (t < S && (kk[u] & known) == prefix)
-          atomicAdd(&hist[(kk[u] >> shift) & (uint32_t)(bins - 1)], 1u);
+        bool todo = t < S && (kk[u] & known) == prefix;
+        const uint32_t bin = (kk[u] >> shift) & (uint32_t)(bins - 1);
+        // Scores of similar size share their leading bits, so most lanes of a wave want the
+        // same bin and their atomics would be served one by one: the bins of a few lanes are
+        // counted by ballot first, whoever is left (many distinct bins, no such pile-up) adds singly.
+#pragma unroll
+        for (int round = 0; round < 3; ++round) {
+          const uint64_t left = __ballot(todo);
+          if (left == 0) break;
+          const uint32_t lead = (uint32_t)__shfl((int)bin, __ffsll((unsigned long long)left) - 1);
+          const uint64_t same = __ballot(todo && bin == lead);
+          if (todo && bin == lead) {
+            if ((same & lanemask_lt()) == 0) atomicAdd(&hist[lead], (uint32_t)__popcll(same));
+            todo = false;
+          }
+        }
+        if (todo) atomicAdd(&hist[bin], 1u);
       }
     }
     __syncthreads();
@@ -636,9 +651,15 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
         const int o = sh_base[j] + __popcll(kw & lanemask_lt());
         if (o < p.budget) {  // always true for consistent masks; keeps stores in bounds regardless
           const int item = (w0 + j) * 64 + lane;
-          for (int e = 0; e < p.unit; ++e) {
-            idx_out[(size_t)o * p.unit + e] = item * p.unit + e + p.n_sink;
-            if (kind_out) kind_out[(size_t)o * p.unit + e] = (uint8_t)((rj >> lane) & 1ull);
+          const uint8_t kd = (uint8_t)((rj >> lane) & 1ull);
+          if (p.unit == 1) {
+            idx_out[o] = item + p.n_sink;
+            if (kind_out) kind_out[o] = kd;
+          } else {
+            for (int e = 0; e < p.unit; ++e) {
+              idx_out[(size_t)o * p.unit + e] = item * p.unit + e + p.n_sink;
+              if (kind_out) kind_out[(size_t)o * p.unit + e] = kd;
+            }
           }
         }
       }
@@ -865,8 +886,9 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
     m.W = P.W;
     m.N = N;
     m.Br = Br;
-    const kvcrush_status st = P.W <= 2 ? launch_grouping<2>(g, m, P, B, Br, stream)
-                                       : launch_grouping<kMaxW>(g, m, P, B, Br, stream);
+    const kvcrush_status st = P.W <= 2   ? launch_grouping<2>(g, m, P, B, Br, stream)
+                              : P.W <= 4 ? launch_grouping<4>(g, m, P, B, Br, stream)
+                                         : launch_grouping<kMaxW>(g, m, P, B, Br, stream);
     if (st != KVCRUSH_OK) return st;
   }
   if (args->budget > 0) {
