@@ -124,7 +124,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   // score rows rank tokens; the importance row ranks units of p.unit tokens (Sec. 4.3.5: a
   // page's importance is that of its tokens added up)
   const bool unit_row = row == Hs && p.unit > 1;
-  const int S = unit_row ? p.S / p.unit : p.S;
+  const int S_tok = p.S;
+  const int S = unit_row ? S_tok / p.unit : S_tok;
   const int nw = unit_row ? (S + 63) / 64 : p.nw;
   const int k = row < Hs ? p.kbit : p.n_important;
   uint64_t* __restrict__ mask_out = p.rowmask + ((size_t)b * (Hs + 1) + row) * p.nw;
@@ -150,27 +151,14 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   const size_t ld = (size_t)p.ld;
 
   for (int i = tid; i < kRadixBins; i += kSelThreads) hist[i] = 0;
-  if (unit_row) {
-    // unit importance: token importances (fp32 sum of the rows, row order) added in token order
-    for (int u = tid; u < S; u += kSelThreads) {
-      float acc = 0.0f;
-      for (int j = 0; j < p.unit; ++j) {
-        const size_t t = (size_t)u * p.unit + j;
-        float tok = 0.0f;
-        for (int r = 0; r < Hs; ++r) tok = tok + sc[(size_t)r * ld + t];
-        acc = acc + tok;
-      }
-      key_put(u, float_key(acc));
-    }
-  }
   // keys: kBatch tokens per thread at a time so that their loads overlap
-  for (int t0 = tid; t0 < (unit_row ? 0 : S); t0 += kBatch * kSelThreads) {
+  for (int t0 = tid; t0 < S_tok; t0 += kBatch * kSelThreads) {
     float v[kBatch];
     if (row < Hs) {
 #pragma unroll
       for (int u = 0; u < kBatch; ++u) {
         const int t = t0 + u * kSelThreads;
-        v[u] = t < S ? sc[(size_t)row * ld + t] : 0.0f;
+        v[u] = t < S_tok ? sc[(size_t)row * ld + t] : 0.0f;
       }
     } else {
       // token importance: fp32 sum of the score rows, taken in row order
@@ -185,7 +173,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
           for (int u = 0; u < kBatch; ++u) {
             const int t = t0 + u * kSelThreads;
-            x[rr][u] = t < S ? sc[(size_t)(r + rr) * ld + t] : 0.0f;
+            x[rr][u] = t < S_tok ? sc[(size_t)(r + rr) * ld + t] : 0.0f;
           }
 #pragma unroll
         for (int rr = 0; rr < 8; ++rr)
@@ -196,7 +184,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
           const int t = t0 + u * kSelThreads;
-          const float x = t < S ? sc[(size_t)r * ld + t] : 0.0f;
+          const float x = t < S_tok ? sc[(size_t)r * ld + t] : 0.0f;
           v[u] = v[u] + x;
         }
       }
@@ -204,10 +192,26 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
     for (int u = 0; u < kBatch; ++u) {
       const int t = t0 + u * kSelThreads;
-      if (t < S) key_put(t, float_key(v[u]));
+      // (unit row: the token's importance itself is parked here, keys follow below)
+      if (t < S_tok) key_put(t, unit_row ? __float_as_uint(v[u]) : float_key(v[u]));
     }
   }
   __syncthreads();
+  if (unit_row) {
+    // Unit importance = its tokens' importances added in token order.  Unit u reads slots
+    // [u * unit, (u + 1) * unit) and its key goes to slot u; units are taken 1024 at a time,
+    // reads and writes of a round apart, so a slot is never overwritten before its reader
+    // (unit u / unit, which comes no later than unit u) has passed.
+    for (int u0 = 0; u0 < S; u0 += kSelThreads) {
+      const int u = u0 + tid;
+      float acc = 0.0f;
+      if (u < S)
+        for (int j = 0; j < p.unit; ++j) acc = acc + __uint_as_float(key_at(u * p.unit + j));
+      __syncthreads();
+      if (u < S) key_put(u, float_key(acc));
+      __syncthreads();
+    }
+  }
 
   // MSB-first radix select of the k-th largest key: 11, 11 and 10 bits a pass.
   // One LDS histogram shared by the workgroup; only keys that still match the
