@@ -286,8 +286,9 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
 
   if constexpr (C::kPipelined) {
     if (n_full > 0) {
-      tile_load_async<C>(kh, f_begin * C::kTile, S, lds[0], rel, wave);
-      tile_load_async<C>(kh, (f_begin + min(1, n_full - 1)) * C::kTile, S, lds[1], rel, wave);
+      // (these tiles end before the workgroup's first query: always whole)
+      tile_load_async_full<C>(kh, f_begin * C::kTile, lds[0], rel, wave);
+      tile_load_async_full<C>(kh, (f_begin + min(1, n_full - 1)) * C::kTile, lds[1], rel, wave);
       wait_async_loads();
       __syncthreads();
       // tile t lives in lds[t % 3]: while iteration `it` multiplies tiles it and
@@ -316,7 +317,7 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
       auto body = [&](auto P, int it) {
         constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
         constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
-        tile_load_async<C>(kh, (f_begin + min(it + 2, n_full - 1)) * C::kTile, S, lds[ld], rel, wave);
+        tile_load_async_full<C>(kh, (f_begin + min(it + 2, n_full - 1)) * C::kTile, lds[ld], rel, wave);
         const bool live = it < n_full;
         float sum[2], mref[2];
         // block (it, sub 1) goes through the MFMAs while block (it, sub 0) is summed

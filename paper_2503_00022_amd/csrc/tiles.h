@@ -113,6 +113,19 @@ __device__ __forceinline__ void tile_load_async(const char* head_base, int row0,
   }
 }
 
+// The same for a tile that lies wholly inside the sequence: no clamping, the
+// address is the uniform tile base plus the lane's fixed offset.
+template <class C>
+__device__ __forceinline__ void tile_load_async_full(const char* head_base, int row0, char* buf,
+                                                     const uint32_t (&rel)[C::kLoadsPerWave], int wave) {
+  const char* tile = head_base + (size_t)row0 * C::kRowBytes;
+#pragma unroll
+  for (int j = 0; j < C::kLoadsPerWave; ++j)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile + rel[j]),
+                                     (__attribute__((address_space(3))) void*)(buf + (wave + kWaves * j) * 1024),
+                                     16, 0, 0);
+}
+
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 
