@@ -603,3 +603,89 @@ def test_decode_loop_with_evictions(kv, oracle):
     assert torch.equal(kc.cpu()[:, :, :n].view(torch.uint8), o_k[:, :, :n].view(torch.uint8))
     assert torch.equal(vc.cpu()[:, :, :n].view(torch.uint8), o_v[:, :, :n].view(torch.uint8))
     assert rel_err(sc[:, :, :n], o_sc[:, :, :n]) <= SCORE_RTOL
+
+
+# ------------------------------------------------------------------ HIP graphs
+def test_whole_path_replays_from_a_hip_graph(kv, oracle):
+    """The entry points only enqueue kernels on the caller's stream and allocate nothing, so a
+    layer's compression can be captured once and replayed.  Three replays on fresh inputs, eager
+    work and synchronisations in between, each compared with the eager result and the oracle."""
+    say("graph capture of scores -> select -> compact, three replays")
+    w = inputs.Workload("t", 2, 8, 2, 1500, 128, "bf16", 400, 0.25, "mean", True, sink_bias=True)
+    dev = torch.device("cuda")
+    q = torch.empty(w.B, w.Hq, w.S, w.D, dtype=torch.bfloat16, device=dev)
+    k = torch.empty(w.B, w.Hkv, w.S, w.D, dtype=torch.bfloat16, device=dev)
+    v = torch.empty_like(k)
+    shape = kv.make_shape(q, k, True)
+    ws = torch.empty(kv.kvcrush_scores_workspace(shape), dtype=torch.uint8, device=dev)
+    sel_ws = torch.empty(kv.kvcrush_select_workspace(kv.make_select_args(w.B, w.Hkv, w.S, 400, 300, n_sink=4,
+                                                                        n_recent=16)), dtype=torch.uint8, device=dev)
+    sc = torch.empty(w.B, w.Hkv, w.S, device=dev)
+    idx = torch.empty(w.B, 400, dtype=torch.int32, device=dev)
+    ko = torch.empty(w.B, w.Hkv, 400, w.D, dtype=torch.bfloat16, device=dev)
+    vo = torch.empty_like(ko)
+
+    def layer():
+        kv.kvcrush_scores(q, k, True, scores=sc, workspace=ws)
+        kv.kvcrush_select(sc, 400, 300, 0, "mean", 5, want_kind=False, idx=idx, workspace=sel_ws, n_sink=4,
+                          n_recent=16)
+        kv.kvcrush_compact(k, v, idx, k_out=ko, v_out=vo, validate=False)
+
+    def load(seed):
+        a, b, c = inputs.make_qkv(w, seed)
+        q.copy_(a); k.copy_(b); v.copy_(c)
+        return a, b, c
+
+    load(100)
+    layer()                                   # eager warm-up (also sets kernel attributes)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            layer()
+    torch.cuda.synchronize()
+    for seed in (101, 102, 103):
+        hq, hk, hv = load(seed)
+        ko.zero_(); vo.zero_(); idx.zero_(); sc.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (sc, idx, ko, vo)]
+        layer()                               # the same work eagerly, on the same inputs
+        torch.cuda.synchronize()
+        for a, b in zip(got, (sc, idx, ko, vo)):
+            assert torch.equal(a, b), "graph replay differs from the eager run"
+        ridx, _, _ = oracle.select(got[0].cpu(), 400, 300, 0, "mean", 5, n_sink=4, n_recent=16)
+        assert torch.equal(got[1].cpu(), ridx)
+        rk, rv = oracle.compact(hk, hv, ridx)
+        assert torch.equal(got[2].cpu().view(torch.uint8), rk.view(torch.uint8))
+    ref = oracle.scores(hq, hk, True, threads=THREADS)
+    assert rel_err(got[0], ref) <= SCORE_RTOL
+
+
+def test_decode_steps_replay_from_a_hip_graph(kv, oracle):
+    say("graph capture of a decoding step, replays at growing cache lengths need one graph per length")
+    B, Hq, Hkv, D, cap = 2, 8, 2, 128, 512
+    dev = torch.device("cuda")
+    g0 = torch.Generator().manual_seed(9)
+    kc_h = torch.randn(B, Hkv, cap, D, generator=g0).to(torch.bfloat16)
+    kc, sc = kc_h.cuda(), torch.zeros(B, Hkv, cap, device=dev)
+    qn = torch.empty(B, Hq, D, dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(kv.kvcrush_scores_append_workspace(kv.Shape(B, Hq, Hkv, cap, D, kv.BF16, 1, 0), cap),
+                     dtype=torch.uint8, device=dev)
+    o_sc = torch.zeros(B, Hkv, cap)
+    side = torch.cuda.Stream()
+    for n in (300, 301, 302):
+        q_h = torch.randn(B, Hq, D, generator=g0).to(torch.bfloat16)
+        qn.copy_(q_h)
+        kv.kvcrush_scores_append(qn, kc, sc.clone(), n, True, workspace=ws)     # eager warm-up on a copy
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()                  # the cache length is a launch argument: one graph per step
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                kv.kvcrush_scores_append(qn, kc, sc, n, True, workspace=ws)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        oracle.scores_append(q_h, kc_h, o_sc, n, True)
+        assert rel_err(sc[:, :, :n], o_sc[:, :, :n]) <= SCORE_RTOL
