@@ -225,14 +225,21 @@ kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int32_t D, int
  * entries at or beyond S are not touched.  Appending tokens S0+1 .. S one by one
  * to the scores of a prefix of length S0 gives kvcrush_scores of the whole
  * sequence (to rounding).  shape->obs_window must be 0; D in {64, 128}.
+ *   lengths    NULL, or device int32 [B]: the number of valid tokens of each
+ *              sequence, read by the kernels when they run; shape->S is then
+ *              only their upper bound (it sizes the launch and the workspace;
+ *              values are clamped to [1, shape->S]).  A serving loop can so
+ *              replay one captured launch sequence for every step and for
+ *              sequences of different lengths, updating `lengths` on the device.
  *   workspace  kvcrush_scores_append_workspace(shape, capacity) bytes, 16-byte
  *              aligned (base-2 logits and per-block partial normalisers).
  * Errors as kvcrush_scores.
  */
 size_t kvcrush_scores_append_workspace(const kvcrush_shape* shape, int32_t capacity);
 kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int32_t capacity,
-                                     const void* q_new, const void* k, float* scores,
-                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+                                     const int32_t* lengths, const void* q_new, const void* k,
+                                     float* scores, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream);
 
 /* Eviction while decoding: once kvcrush_select (run on the valid part of the
  * score rows, see kvcrush_select_args.score_stride) has chosen `budget` tokens,

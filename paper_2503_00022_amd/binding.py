@@ -74,7 +74,7 @@ def load() -> ctypes.CDLL:
         L.kvcrush_compact.restype = ctypes.c_int
         L.kvcrush_scores_append_workspace.argtypes = [ctypes.POINTER(Shape), i32]
         L.kvcrush_scores_append_workspace.restype = sz
-        L.kvcrush_scores_append.argtypes = [ctypes.POINTER(Shape), i32, vp, vp, vp, vp, sz, vp]
+        L.kvcrush_scores_append.argtypes = [ctypes.POINTER(Shape), i32, vp, vp, vp, vp, vp, sz, vp]
         L.kvcrush_scores_append.restype = ctypes.c_int
         L.kvcrush_compact_cache.argtypes = [i32] * 8 + [vp] * 8
         L.kvcrush_compact_cache.restype = ctypes.c_int
@@ -278,9 +278,11 @@ def kvcrush_scores_append_workspace(shape: Shape, capacity: int) -> int:
     return int(load().kvcrush_scores_append_workspace(ctypes.byref(shape), capacity))
 
 
-def kvcrush_scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool, workspace=None, stream=None):
+def kvcrush_scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool, workspace=None, stream=None,
+                          lengths=None):
     """One decoding step, in place on scores_cache [B,Hs,capacity] fp32: the new token's queries
-    q_new [B,Hq,D] attend to the first S tokens of k_cache [B,Hkv,capacity,D] (the new key included)."""
+    q_new [B,Hq,D] attend to the first S tokens of k_cache [B,Hkv,capacity,D] (the new key included).
+    lengths: optional int32 [B] on the GPU with each sequence's own valid length (S is then their bound)."""
     q_new, k_cache, scores_cache = _dev(q_new, "q_new"), _dev(k_cache, "k_cache"), _dev(scores_cache, "scores_cache")
     if q_new.dim() != 3 or k_cache.dim() != 4 or q_new.dtype != k_cache.dtype or scores_cache.dtype != torch.float32:
         raise ValueError("q_new [B,Hq,D] and k_cache [B,Hkv,capacity,D] of one dtype, scores_cache fp32")
@@ -294,8 +296,12 @@ def kvcrush_scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: b
     if workspace is None:
         workspace = torch.empty(max(kvcrush_scores_append_workspace(shape, cap), 16), dtype=torch.uint8,
                                 device=q_new.device)
-    st = load().kvcrush_scores_append(ctypes.byref(shape), cap, _ptr(q_new), _ptr(k_cache), _ptr(scores_cache),
-                                      _ptr(workspace), workspace.numel(), _stream(stream))
+    if lengths is not None:
+        lengths = _dev(lengths, "lengths")
+        if lengths.dtype != torch.int32 or tuple(lengths.shape) != (B,):
+            raise ValueError("lengths must be int32 [B]")
+    st = load().kvcrush_scores_append(ctypes.byref(shape), cap, _ptr(lengths), _ptr(q_new), _ptr(k_cache),
+                                      _ptr(scores_cache), _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "kvcrush_scores_append")
     return scores_cache
 

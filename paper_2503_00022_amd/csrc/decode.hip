@@ -42,7 +42,8 @@ struct AppendParams {
   float* scores;       // [B,Hs,capacity]
   float* logits;       // workspace [B,Hq,S]
   float2* part;        // workspace [B,Hq,n_kb]
-  int B, Hq, Hkv, S, capacity, G, reduce_groups, n_kb;
+  const int* lengths;  // null, or [B]: valid tokens of each sequence (<= S), read on the device
+  int B, Hq, Hkv, S, capacity, G, reduce_groups, n_kb;  // S: valid tokens, or their upper bound with lengths
   float scale_log2;    // log2(e) / sqrt(D)
 };
 
@@ -100,8 +101,9 @@ __global__ __launch_bounds__(kThreads) void append_logits_kernel(AppendParams p)
   const int tid = threadIdx.x, lane = kvc::lane_id(), wave = tid / KVC_WAVE;
   const int kb = blockIdx.x, bg = blockIdx.y;  // bg = b * Hkv + kv head
   const int b = bg / p.Hkv, g = bg % p.Hkv;
-  const int S = p.S;
+  const int S = p.lengths ? min(max(p.lengths[b], 1), p.S) : p.S;
   const int k0 = kb * kKeysPerWg;
+  if (k0 >= S) return;  // this sequence is shorter than the launch's upper bound (uniform exit)
   const int col = lane % kLanesPerRow, sub = lane / kLanesPerRow;
   const char* kh = p.k + (size_t)bg * p.capacity * kRowBytes;
 
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(kThreads) void append_logits_kernel(AppendParams p)
     for (int i = 0; i < nh; ++i) {
       const int h = g * p.G + h0 + i;
       const float x = key < S ? lds_logit[i][tid] : kNegBig;
-      if (key < S) p.logits[((size_t)b * p.Hq + h) * S + key] = x;
+      if (key < S) p.logits[((size_t)b * p.Hq + h) * p.S + key] = x;
       const float m = block_max(x, red);
       const float l = block_sum(key < S ? __builtin_amdgcn_exp2f(x - m) : 0.0f, red);
       if (tid == 0) p.part[((size_t)b * p.Hq + h) * p.n_kb + kb] = make_float2(m, l);
@@ -166,8 +168,9 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
   const int tid = threadIdx.x, lane = kvc::lane_id(), wave = tid / KVC_WAVE;
   const int kb = blockIdx.x, bg = blockIdx.y;  // bg = b * Hkv + kv head
   const int b = bg / p.Hkv, g = bg % p.Hkv;
-  const int S = p.S;
+  const int S = p.lengths ? min(max(p.lengths[b], 1), p.S) : p.S;
   const int k0 = kb * kKeysPerWg;
+  if (k0 >= S) return;  // this sequence is shorter than the launch's upper bound (uniform exit)
   const char* kh = p.k + (size_t)bg * p.capacity * C::kRowBytes;
 
   uint32_t rel[C::kLoadsPerWave];
@@ -229,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
       p.part[((size_t)b * p.Hq + g * p.G + h0 + tid) * p.n_kb + kb] = make_float2(m, lt);
     }
     if (n < nh) {
-      float* dst = p.logits + bh * S;
+      float* dst = p.logits + bh * p.S;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -249,26 +252,29 @@ __global__ __launch_bounds__(kThreads) void append_update_kernel(AppendParams p)
   const int Hs = p.reduce_groups ? p.Hkv : p.Hq;
   const int b = row / Hs, r = row % Hs;
   const int h_first = p.reduce_groups ? r * p.G : r, n_heads = p.reduce_groups ? p.G : 1;
+  const int S = p.lengths ? min(max(p.lengths[b], 1), p.S) : p.S;
+  if (kb * kKeysPerWg >= S) return;
+  const int n_kb = (S + kKeysPerWg - 1) / kKeysPerWg;  // blocks that wrote a pair for this sequence
   const int key = kb * kKeysPerWg + tid;
   float acc = 0.0f;
   for (int i = 0; i < n_heads; ++i) {
     const size_t bh = (size_t)b * p.Hq + h_first + i;
     // row normaliser from the per-workgroup pairs
     float m = kNegBig;
-    for (int j = tid; j < p.n_kb; j += kThreads) m = fmaxf(m, p.part[bh * p.n_kb + j].x);
+    for (int j = tid; j < n_kb; j += kThreads) m = fmaxf(m, p.part[bh * p.n_kb + j].x);
     m = block_max(m, red);
     float l = 0.0f;
-    for (int j = tid; j < p.n_kb; j += kThreads) {
+    for (int j = tid; j < n_kb; j += kThreads) {
       const float2 ml = p.part[bh * p.n_kb + j];
       l += ml.y * __builtin_amdgcn_exp2f(ml.x - m);
     }
     l = block_sum(l, red);
     const float lse2 = m + __builtin_amdgcn_logf(l);
-    if (key < p.S) acc += __builtin_amdgcn_exp2f(p.logits[bh * p.S + key] - lse2);
+    if (key < S) acc += __builtin_amdgcn_exp2f(p.logits[bh * p.S + key] - lse2);
   }
-  if (key < p.S) {
+  if (key < S) {
     float* dst = p.scores + (size_t)row * p.capacity + key;
-    *dst = (key == p.S - 1 ? 0.0f : *dst) + acc;  // the new token's slot starts from nothing
+    *dst = (key == S - 1 ? 0.0f : *dst) + acc;  // the new token's slot starts from nothing
   }
 }
 
@@ -313,9 +319,9 @@ extern "C" size_t kvcrush_scores_append_workspace(const kvcrush_shape* shape, in
 }
 
 extern "C" kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int32_t capacity,
-                                                const void* q_new, const void* k, float* scores,
-                                                void* workspace, size_t workspace_bytes,
-                                                void* hip_stream) {
+                                                const int32_t* lengths, const void* q_new,
+                                                const void* k, float* scores, void* workspace,
+                                                size_t workspace_bytes, void* hip_stream) {
   if (!append_shape_ok(shape, capacity)) return KVCRUSH_ERR_INVALID_ARG;
   if (shape->D != 64 && shape->D != 128) return KVCRUSH_ERR_UNSUPPORTED;
   if ((long long)shape->B * shape->Hq > 65535) return KVCRUSH_ERR_UNSUPPORTED;
@@ -331,6 +337,7 @@ extern "C" kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int3
   p.scores = scores;
   p.logits = (float*)workspace;
   p.part = (float2*)((char*)workspace + logits_bytes(shape));
+  p.lengths = lengths;
   p.B = shape->B;
   p.Hq = shape->Hq;
   p.Hkv = shape->Hkv;

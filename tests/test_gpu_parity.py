@@ -689,3 +689,43 @@ def test_decode_steps_replay_from_a_hip_graph(kv, oracle):
         torch.cuda.synchronize()
         oracle.scores_append(q_h, kc_h, o_sc, n, True)
         assert rel_err(sc[:, :, :n], o_sc[:, :, :n]) <= SCORE_RTOL
+
+
+def test_decode_with_device_lengths_one_graph_for_all_steps(kv, oracle):
+    """Sequences of different lengths, the lengths living on the device: one captured launch
+    sequence serves every decoding step (the host only bumps the length tensor)."""
+    say("decode append with per-sequence device lengths, one graph replayed over 5 steps")
+    B, Hq, Hkv, D, cap = 3, 8, 2, 128, 640
+    dev = torch.device("cuda")
+    g0 = torch.Generator().manual_seed(12)
+    kc_h = torch.randn(B, Hkv, cap, D, generator=g0).to(torch.bfloat16)
+    start = [37, 300, 513]                                   # one, two and three key blocks
+    lens = torch.tensor(start, dtype=torch.int32, device=dev)
+    sc_h = torch.rand(B, Hkv, cap, generator=g0)
+    kc, sc = kc_h.cuda(), sc_h.clone().cuda()
+    qn = torch.zeros(B, Hq, D, dtype=torch.bfloat16, device=dev)
+    bound = 600                                              # upper bound that sizes launch and workspace
+    ws = torch.empty(kv.kvcrush_scores_append_workspace(kv.Shape(B, Hq, Hkv, bound, D, kv.BF16, 1, 0), cap),
+                     dtype=torch.uint8, device=dev)
+    scratch = sc.clone()
+    kv.kvcrush_scores_append(qn, kc, scratch, bound, True, workspace=ws, lengths=lens)   # eager warm-up
+    torch.cuda.synchronize()
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            kv.kvcrush_scores_append(qn, kc, sc, bound, True, workspace=ws, lengths=lens)
+    torch.cuda.synchronize()
+    o_sc = sc_h.clone()
+    for step in range(5):
+        q_h = torch.randn(B, Hq, D, generator=g0).to(torch.bfloat16)
+        qn.copy_(q_h)
+        lens.add_(1)                                         # every sequence got one more token
+        graph.replay()
+        torch.cuda.synchronize()
+        for b in range(B):                                   # the oracle takes one length per call
+            n = start[b] + step + 1
+            part = o_sc[b:b + 1].clone()
+            oracle.scores_append(q_h[b:b + 1], kc_h[b:b + 1], part, n, True)
+            o_sc[b] = part[0]
+            assert rel_err(sc[b, :, :n], o_sc[b, :, :n]) <= SCORE_RTOL, (step, b)
+            assert torch.equal(sc[b, :, n:].cpu(), sc_h[b, :, n:]), "entries beyond a sequence's length were touched"

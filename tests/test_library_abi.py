@@ -208,7 +208,7 @@ def test_decode_entry_points_validation(lib):
     assert binding.kvcrush_scores_append_workspace(sh(), 299) == 0        # capacity below the valid length
     assert binding.kvcrush_scores_append_workspace(sh(obs_window=8), 320) == 0
     call = lambda shape, cap=320, q=FAKE, k=FAKE, sc=FAKE, ws=FAKE, n=1 << 40: \
-        lib.kvcrush_scores_append(ctypes.byref(shape), cap, q, k, sc, ws, n, None)
+        lib.kvcrush_scores_append(ctypes.byref(shape), cap, None, q, k, sc, ws, n, None)
     assert call(sh(), cap=100) == binding.ERR_INVALID_ARG
     assert call(sh(Hq=7)) == binding.ERR_INVALID_ARG
     assert call(sh(D=32)) == binding.ERR_UNSUPPORTED
