@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--decode", action="store_true",
                     help="time the decoding-time score append on caches of --cache-len tokens instead of the "
                          "per-layer compression step")
+    ap.add_argument("--graph", action="store_true",
+                    help="--decode: capture one step per resident cache in a HIP graph and time replays")
     ap.add_argument("--cache-len", type=int, default=0, help="--decode: valid tokens per cache (0: the workload's budget)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -119,15 +121,30 @@ def run_decode(args, torch, kv, inputs, dev):
         qn, kc, sc = caches[i % n_caches]
         kv.kvcrush_scores_append(qn, kc, sc, S, w.reduce_groups, workspace=ws)
 
-    for i in range(args.warmup):
+    for i in range(max(args.warmup, n_caches if args.graph else 0)):
         step(i)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    e1.record()
+    if args.graph:
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(n_caches):
+                    step(i)
+        torch.cuda.synchronize()
+        replays = max(1, args.steps // n_caches)
+        args.steps = replays * n_caches
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(replays):
+            graph.replay()
+        e1.record()
+    else:
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     gpu_ms = e0.elapsed_time(e1) / args.steps
@@ -137,7 +154,8 @@ def run_decode(args, torch, kv, inputs, dev):
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}_decode_cache{S}", "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "cache_len": S,
-                   "capacity": cap, "D": w.D, "reduce_groups": w.reduce_groups, "resident_caches": n_caches},
+                   "capacity": cap, "D": w.D, "reduce_groups": w.reduce_groups, "resident_caches": n_caches,
+                   "hip_graph": args.graph},
         "roofline": {"bound": "hbm", "kernel": "append_logits_kernel + append_update_kernel",
                      "achieved": k_bytes / (gpu_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": k_bytes / (gpu_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
