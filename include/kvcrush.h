@@ -175,6 +175,7 @@ typedef struct {
                            /* P; Hs * P <= 1024.  idx lists every token of a kept unit. */
   uint64_t anchor_seed;    /* RANDOM only                                              */
   const uint64_t* anchor_bits; /* EXPLICIT only: device [B, W], W = ceil(Hs / 64)      */
+                           /* (ceil(Hs * P / 64) with unit = P > 1)                    */
 } kvcrush_select_args;
 
 size_t kvcrush_select_workspace(const kvcrush_select_args* args);
@@ -259,7 +260,7 @@ kvcrush_status kvcrush_compact_cache(int32_t B, int32_t Hkv, int32_t Hs, int32_t
 
 const char* kvcrush_status_string(kvcrush_status status);
 
-/* Library version, e.g. 100 for 0.1.0. */
+/* Library version, e.g. 110 for 0.1.1. */
 int32_t kvcrush_version(void);
 
 #ifdef __cplusplus

@@ -135,6 +135,19 @@ def test_select_units_matches_oracle(kv, oracle, B, Hs, S, unit, budget, n_imp, 
     assert torch.equal(idx2.cpu(), ridx)
 
 
+def test_select_units_explicit_anchor(kv, oracle):
+    say("unit-level select with a caller-supplied 192-bit anchor")
+    B, Hs, S, unit = 2, 12, 1920, 16
+    sc = inputs.make_scores(B, Hs, S, seed=77, ties=True)
+    g = torch.Generator().manual_seed(3)
+    anchor = torch.randint(-2**62, 2**62, (B, 3), generator=g, dtype=torch.int64)   # bits beyond 192 are ignored
+    idx, kind, bits = kv.kvcrush_select(sc.cuda(), 480, 320, 0, "explicit", 0, anchor.cuda(), want_bits=True,
+                                        unit=unit)
+    torch.cuda.synchronize()
+    ridx, rkind, rbits = oracle.select_units(sc, unit, 480, 320, 0, "explicit", 0, anchor)
+    assert torch.equal(bits.cpu(), rbits) and torch.equal(idx.cpu(), ridx) and torch.equal(kind.cpu(), rkind)
+
+
 @pytest.mark.parametrize("Hs,S,budget,n_imp,anchor", [(129, 700, 200, 120, "random"), (300, 1000, 300, 100, "mean"),
                                                        (1024, 512, 128, 64, "alternating")])
 def test_select_many_score_rows(kv, oracle, Hs, S, budget, n_imp, anchor):
@@ -729,3 +742,24 @@ def test_decode_with_device_lengths_one_graph_for_all_steps(kv, oracle):
             o_sc[b] = part[0]
             assert rel_err(sc[b, :, :n], o_sc[b, :, :n]) <= SCORE_RTOL, (step, b)
             assert torch.equal(sc[b, :, n:].cpu(), sc_h[b, :, n:]), "entries beyond a sequence's length were touched"
+
+
+def test_scores_long_sequence_index_arithmetic(kv, oracle):
+    """S = 100000 (ragged, 391 key blocks, 87 query chunks): the oracle can afford the last 64
+    query rows, which fix the window scores everywhere and the full scores of the last 64 tokens
+    (only those rows reach them); the full scores also get the row-total invariant."""
+    say("scores at S=100000: window W=64 against the oracle, full scores' tail and totals")
+    w = inputs.Workload("t", 1, 4, 1, 100000, 128, "bf16", 1000, 0.25, "alternating", True, sink_bias=True)
+    q, k, _ = inputs.make_qkv(w, 4, want_v=False)
+    qd, kd = q.cuda(), k.cuda()
+    win, _ = kv.kvcrush_scores(qd, kd, True, window=64)
+    full, _ = kv.kvcrush_scores(qd, kd, True)
+    torch.cuda.synchronize()
+    ref = oracle.scores(q, k, True, threads=THREADS, window=64)
+    got, want = win.cpu().double(), ref.double()
+    big = want > 1e-30
+    assert ((got[big] - want[big]).abs() / want[big]).max().item() <= SCORE_RTOL
+    assert rel_err(full[..., -64:], ref[..., -64:]) <= SCORE_RTOL
+    tot = full.double().sum(-1).cpu()
+    assert torch.allclose(tot, torch.full_like(tot, 4.0 * w.S), rtol=1e-4)
+    assert (full > 0).all()
