@@ -17,6 +17,9 @@ import torch
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "kvcrush_oracle.cpp")
 _LIB = os.path.join(_DIR, "libkvcrush_oracle.so")
+# The mutation tests (tests/test_oracle_mutations.py) point this at a copy of the oracle with a
+# planted mistake to show that the pins notice it; nothing else sets it.
+_LIB_OVERRIDE = os.environ.get("KVCRUSH_ORACLE_LIB_FOR_MUTATION_TEST")
 CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC"]
 
 F32, BF16 = 0, 1
@@ -40,7 +43,7 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        L = ctypes.CDLL(_LIB_OVERRIDE or build())
         vp, i32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
         L.kvcrush_oracle_head_colsums.argtypes = [i32, i32, i32, vp, vp, i32, i32, vp, vp]
         L.kvcrush_oracle_scores.argtypes = [i32] * 8 + [vp] * 4

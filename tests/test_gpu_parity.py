@@ -236,6 +236,22 @@ def test_select_explicit_anchor_negative_and_zero_scores(kv, oracle):
     check_select(kv, oracle, torch.ones(1, 8, 500), 100, 60, 0, "alternating")
 
 
+def test_select_importance_sum_is_sequential_fp32(kv, oracle):
+    """Token importance is the fp32 sum of the score rows in row order; any other order or width
+    ranks these three tokens differently ((2 + 1e8) - 1e8 = 0 in fp32)."""
+    sc = torch.zeros(1, 3, 4)
+    sc[0, :, 0] = torch.tensor([1e8, -1e8, 1.0])
+    sc[0, :, 1] = torch.tensor([0.25, 0.25, 0.25])
+    sc[0, :, 2] = torch.tensor([2.0, 1e8, -1e8])
+    idx, _, _ = kv.kvcrush_select(sc.cuda(), 1, 1, 1, "alternating")
+    torch.cuda.synchronize()
+    assert idx.cpu().tolist() == [[0]] == oracle.select(sc, 1, 1, 1, "alternating")[0].tolist()
+    # the same through the page-level path (units of two tokens: sums 1 + 0.75 and 0 + 0)
+    idx2, _, _ = kv.kvcrush_select(sc.cuda(), 2, 2, 1, "alternating", unit=2)
+    torch.cuda.synchronize()
+    assert idx2.cpu().tolist() == [[0, 1]] == oracle.select_units(sc, 2, 2, 2, 1, "alternating")[0].tolist()
+
+
 def test_select_is_deterministic(kv):
     sc = inputs.make_scores(2, 8, 5000, seed=3, ties=True).cuda()
     a = kv.kvcrush_select(sc, 1000, 750, want_bits=True)
