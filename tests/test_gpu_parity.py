@@ -779,3 +779,69 @@ def test_scores_long_sequence_index_arithmetic(kv, oracle):
     tot = full.double().sum(-1).cpu()
     assert torch.allclose(tot, torch.full_like(tot, 4.0 * w.S), rtol=1e-4)
     assert (full > 0).all()
+
+
+def test_select_random_sweep(kv, oracle):
+    """Seeded sweep over shapes, budgets, anchors, protected ends and unit sizes (60 cases)."""
+    import random
+    rng = random.Random(20250300)
+    for case in range(60):
+        unit = rng.choice([1, 1, 1, 2, 4, 8, 16, 32])
+        Hs = rng.choice([1, 2, 3, 8, 8, 17, 32, 64, 100])
+        while Hs * unit > 1024:
+            Hs //= 2
+        B = rng.choice([1, 1, 2, 3])
+        n_units = rng.randint(1, 6000 // unit) if rng.random() < 0.8 else rng.randint(1, 20)
+        sink = rng.choice([0, 0, 0, 1, 4, 32, 70])
+        recent = rng.choice([0, 0, 0, 1, 16, 128])
+        Sm = n_units * unit
+        S = Sm + sink + recent
+        bu = rng.randint(0, n_units)                      # kept units
+        iu = rng.randint(0, bu)                           # of which important
+        if rng.random() < 0.15:
+            iu = bu
+        if rng.random() < 0.1:
+            iu = 0
+        budget, n_imp = bu * unit + sink + recent, iu * unit
+        kbit = rng.choice([0, 0, rng.randint(0, Sm)])
+        anchor = rng.choice(["alternating", "mean", "random"])
+        ties = rng.random() < 0.6
+        say(f"  sweep {case}: B={B} Hs={Hs} S={S} unit={unit} budget={budget} n_imp={n_imp} kbit={kbit} "
+            f"sink={sink} recent={recent} {anchor} ties={ties}")
+        sc = inputs.make_scores(B, Hs, S, seed=1000 + case, ties=ties)
+        kw = dict(n_sink=sink, n_recent=recent)
+        idx, kind, _ = kv.kvcrush_select(sc.cuda(), budget, n_imp, kbit, anchor, case, unit=unit, **kw)
+        torch.cuda.synchronize()
+        if unit > 1:
+            ridx, rkind, _ = oracle.select_units(sc, unit, budget, n_imp, kbit, anchor, case, **kw)
+        else:
+            ridx, rkind, _ = oracle.select(sc, budget, n_imp, kbit, anchor, case, **kw)
+        assert torch.equal(idx.cpu(), ridx) and torch.equal(kind.cpu(), rkind), f"case {case}"
+
+
+def test_scores_random_sweep(kv, oracle):
+    """Seeded sweep over small score shapes: dtype, head dim, grouping, window, ragged lengths."""
+    import random
+    rng = random.Random(77)
+    for case in range(24):
+        dtype = rng.choice(["bf16", "bf16", "f32"])
+        D = rng.choice([64, 128])
+        Hkv = rng.choice([1, 2, 3])
+        G = rng.choice([1, 2, 3, 4, 8])
+        B = rng.choice([1, 2])
+        S = rng.choice([rng.randint(1, 300), rng.randint(300, 1500), rng.randint(1500, 2600)])
+        if dtype == "f32":
+            S = min(S, 900)
+        rg = rng.random() < 0.6
+        W = rng.choice([0, 0, 1, rng.randint(1, S), S + 5])
+        say(f"  sweep {case}: B={B} Hq={Hkv * G} Hkv={Hkv} S={S} D={D} {dtype} reduce_groups={rg} window={W}")
+        w = inputs.Workload("t", B, Hkv * G, Hkv, S, D, dtype, max(1, S // 4), 0.5, "alternating", rg, sink_bias=True)
+        q, k, _ = inputs.make_qkv(w, 500 + case, want_v=False)
+        sc, _ = kv.kvcrush_scores(q.cuda(), k.cuda(), rg, window=W)
+        torch.cuda.synchronize()
+        ref = oracle.scores(q, k, rg, threads=THREADS, window=W)
+        got, want = sc.cpu().double(), ref.double()
+        big = want > 1e-30
+        assert ((got[big] - want[big]).abs() / want[big]).max().item() <= SCORE_RTOL, f"case {case}"
+        if (~big).any():
+            assert got[~big].abs().max().item() <= 1e-30
