@@ -232,6 +232,12 @@ kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int32_t D, int
  *              values are clamped to [1, shape->S]).  A serving loop can so
  *              replay one captured launch sequence for every step and for
  *              sequences of different lengths, updating `lengths` on the device.
+ *   block_table  NULL: k is dense [B, Hkv, capacity, D].  Otherwise k is a paged
+ *              pool [n_blocks, block_size, Hkv, D] (the layout kvcrush_compact
+ *              reads) and block_table [B, capacity / block_size] int32 names the
+ *              pool block of each logical block; capacity % block_size == 0;
+ *              entries must be valid pool blocks (not checked on the device).
+ *              scores stay dense [B, Hs, capacity].
  *   workspace  kvcrush_scores_append_workspace(shape, capacity) bytes, 16-byte
  *              aligned (base-2 logits and per-block partial normalisers).
  * Errors as kvcrush_scores.
@@ -239,6 +245,7 @@ kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int32_t D, int
 size_t kvcrush_scores_append_workspace(const kvcrush_shape* shape, int32_t capacity);
 kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int32_t capacity,
                                      const int32_t* lengths, const void* q_new, const void* k,
+                                     const int32_t* block_table, int32_t block_size,
                                      float* scores, void* workspace, size_t workspace_bytes,
                                      void* hip_stream);
 

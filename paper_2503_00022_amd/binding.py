@@ -74,7 +74,7 @@ def load() -> ctypes.CDLL:
         L.kvcrush_compact.restype = ctypes.c_int
         L.kvcrush_scores_append_workspace.argtypes = [ctypes.POINTER(Shape), i32]
         L.kvcrush_scores_append_workspace.restype = sz
-        L.kvcrush_scores_append.argtypes = [ctypes.POINTER(Shape), i32, vp, vp, vp, vp, vp, sz, vp]
+        L.kvcrush_scores_append.argtypes = [ctypes.POINTER(Shape), i32, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.kvcrush_scores_append.restype = ctypes.c_int
         L.kvcrush_compact_cache.argtypes = [i32] * 8 + [vp] * 8
         L.kvcrush_compact_cache.restype = ctypes.c_int
@@ -279,17 +279,26 @@ def kvcrush_scores_append_workspace(shape: Shape, capacity: int) -> int:
 
 
 def kvcrush_scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool, workspace=None, stream=None,
-                          lengths=None):
+                          lengths=None, block_table=None, block_size=16):
     """One decoding step, in place on scores_cache [B,Hs,capacity] fp32: the new token's queries
     q_new [B,Hq,D] attend to the first S tokens of k_cache [B,Hkv,capacity,D] (the new key included).
-    lengths: optional int32 [B] on the GPU with each sequence's own valid length (S is then their bound)."""
+    lengths: optional int32 [B] on the GPU with each sequence's own valid length (S is then their bound).
+    block_table: k_cache is then a paged pool [n_blocks,block_size,Hkv,D], block_table int32
+    [B,capacity/block_size]."""
     q_new, k_cache, scores_cache = _dev(q_new, "q_new"), _dev(k_cache, "k_cache"), _dev(scores_cache, "scores_cache")
     if q_new.dim() != 3 or k_cache.dim() != 4 or q_new.dtype != k_cache.dtype or scores_cache.dtype != torch.float32:
         raise ValueError("q_new [B,Hq,D] and k_cache [B,Hkv,capacity,D] of one dtype, scores_cache fp32")
     B, Hq, D = q_new.shape
-    Hkv, cap = k_cache.shape[1], k_cache.shape[2]
-    if k_cache.shape[0] != B or k_cache.shape[3] != D:
-        raise ValueError("q_new and k_cache disagree on B or D")
+    if block_table is None:
+        Hkv, cap = k_cache.shape[1], k_cache.shape[2]
+        if k_cache.shape[0] != B or k_cache.shape[3] != D:
+            raise ValueError("q_new and k_cache disagree on B or D")
+    else:
+        block_table = _dev(block_table, "block_table")
+        Hkv, cap = k_cache.shape[2], block_table.shape[1] * block_size
+        if block_table.dtype != torch.int32 or block_table.shape[0] != B or k_cache.shape[1] != block_size \
+                or k_cache.shape[3] != D:
+            raise ValueError("paged k_cache must be [n_blocks,block_size,Hkv,D] with block_table int32 [B,n]")
     if tuple(scores_cache.shape) != (B, Hkv if reduce_groups else Hq, cap):
         raise ValueError("scores_cache must be [B,Hs,capacity]")
     shape = Shape(B, Hq, Hkv, int(S), D, _dtype_code(q_new), int(bool(reduce_groups)), 0)
@@ -301,7 +310,8 @@ def kvcrush_scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: b
         if lengths.dtype != torch.int32 or tuple(lengths.shape) != (B,):
             raise ValueError("lengths must be int32 [B]")
     st = load().kvcrush_scores_append(ctypes.byref(shape), cap, _ptr(lengths), _ptr(q_new), _ptr(k_cache),
-                                      _ptr(scores_cache), _ptr(workspace), workspace.numel(), _stream(stream))
+                                      _ptr(block_table), block_size, _ptr(scores_cache), _ptr(workspace),
+                                      workspace.numel(), _stream(stream))
     _check(st, "kvcrush_scores_append")
     return scores_cache
 

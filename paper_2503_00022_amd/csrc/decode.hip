@@ -43,9 +43,20 @@ struct AppendParams {
   float* logits;       // workspace [B,Hq,S]
   float2* part;        // workspace [B,Hq,n_kb]
   const int* lengths;  // null, or [B]: valid tokens of each sequence (<= S), read on the device
+  const int* block_table;  // null: k is dense [B,Hkv,capacity,D]; else k is a pool
+                           // [n_blocks,block_size,Hkv,D] and block_table [B,capacity/block_size]
+  int block_size;
   int B, Hq, Hkv, S, capacity, G, reduce_groups, n_kb;  // S: valid tokens, or their upper bound with lengths
   float scale_log2;    // log2(e) / sqrt(D)
 };
+
+// First byte of key row `key` of sequence b, KV head g (bg = b * Hkv + g).
+__device__ __forceinline__ const char* key_row(const AppendParams& p, int b, int g, int bg, int key,
+                                               int row_bytes) {
+  if (!p.block_table) return p.k + ((size_t)bg * p.capacity + key) * row_bytes;
+  const int blk = p.block_table[(size_t)b * (p.capacity / p.block_size) + key / p.block_size];
+  return p.k + (((size_t)blk * p.block_size + key % p.block_size) * p.Hkv + g) * row_bytes;
+}
 
 template <bool BF16>
 __device__ __forceinline__ void unpack(const vec16& x, float (&f)[BF16 ? 8 : 4]) {
@@ -105,7 +116,6 @@ __global__ __launch_bounds__(kThreads) void append_logits_kernel(AppendParams p)
   const int k0 = kb * kKeysPerWg;
   if (k0 >= S) return;  // this sequence is shorter than the launch's upper bound (uniform exit)
   const int col = lane % kLanesPerRow, sub = lane / kLanesPerRow;
-  const char* kh = p.k + (size_t)bg * p.capacity * kRowBytes;
 
   for (int h0 = 0; h0 < p.G; h0 += kHeadChunk) {
     const int nh = min(kHeadChunk, p.G - h0);
@@ -122,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void append_logits_kernel(AppendParams p)
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
         const int key = k0 + wave * (kKeysPerWg / kWaves) + (it0 + u) * kRowsPerWave + sub;
-        kx[u] = *(const vec16*)(kh + (size_t)min(key, S - 1) * kRowBytes + col * 16);
+        kx[u] = *(const vec16*)(key_row(p, b, g, bg, min(key, S - 1), kRowBytes) + col * 16);
       }
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
@@ -178,7 +188,20 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
     const int row0 = k0 + C::kTile * w;
-    if (row0 < S) tile_load_async<C>(kh, row0, S, lds[w], rel, wave);  // tiles past the end stay unread
+    if (row0 >= S) continue;  // tiles past the end stay unread
+    if (!p.block_table) {
+      tile_load_async<C>(kh, row0, S, lds[w], rel, wave);
+    } else {
+      // paged pool: the same LDS image, every 16-byte chunk fetched from its row's block
+#pragma unroll
+      for (int j = 0; j < C::kLoadsPerWave; ++j) {
+        const int row = (int)(rel[j] / C::kRowBytes), in_row = (int)(rel[j] % C::kRowBytes);
+        const char* src = key_row(p, b, g, bg, min(row0 + row, S - 1), C::kRowBytes) + in_row;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(lds[w] + (wave + kWaves * j) * 1024),
+                                         16, 0, 0);
+      }
+    }
   }
   wait_async_loads();
   __syncthreads();
@@ -320,9 +343,11 @@ extern "C" size_t kvcrush_scores_append_workspace(const kvcrush_shape* shape, in
 
 extern "C" kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int32_t capacity,
                                                 const int32_t* lengths, const void* q_new,
-                                                const void* k, float* scores, void* workspace,
+                                                const void* k, const int32_t* block_table,
+                                                int32_t block_size, float* scores, void* workspace,
                                                 size_t workspace_bytes, void* hip_stream) {
   if (!append_shape_ok(shape, capacity)) return KVCRUSH_ERR_INVALID_ARG;
+  if (block_table && (block_size < 1 || capacity % block_size != 0)) return KVCRUSH_ERR_INVALID_ARG;
   if (shape->D != 64 && shape->D != 128) return KVCRUSH_ERR_UNSUPPORTED;
   if ((long long)shape->B * shape->Hq > 65535) return KVCRUSH_ERR_UNSUPPORTED;
   if (!q_new || !k || !scores) return KVCRUSH_ERR_INVALID_ARG;
@@ -338,6 +363,8 @@ extern "C" kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int3
   p.logits = (float*)workspace;
   p.part = (float2*)((char*)workspace + logits_bytes(shape));
   p.lengths = lengths;
+  p.block_table = block_table;
+  p.block_size = block_table ? block_size : 1;
   p.B = shape->B;
   p.Hq = shape->Hq;
   p.Hkv = shape->Hkv;

@@ -845,3 +845,32 @@ def test_scores_random_sweep(kv, oracle):
         assert ((got[big] - want[big]).abs() / want[big]).max().item() <= SCORE_RTOL, f"case {case}"
         if (~big).any():
             assert got[~big].abs().max().item() <= 1e-30
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,cap,D,dtype,rg,bs", [
+    (2, 8, 2, 300, 320, 128, "bf16", True, 16),
+    (1, 4, 4, 257, 288, 64, "bf16", False, 32),
+    (2, 2, 2, 513, 640, 128, "f32", False, 16),
+    (8, 32, 8, 2049, 2304, 128, "bf16", True, 16),
+])
+def test_scores_append_on_a_paged_pool(kv, oracle, B, Hq, Hkv, S, cap, D, dtype, rg, bs):
+    """The K cache lives in a pool of blocks scattered by a random block table; the oracle reads
+    the same keys from the dense tensor they were scattered from."""
+    say(f"paged append B={B} Hq={Hq} Hkv={Hkv} S={S} capacity={cap} D={D} {dtype} block={bs}")
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(S + bs)
+    qn = torch.randn(B, Hq, D, generator=g).to(td)
+    kc = torch.randn(B, Hkv, cap, D, generator=g).to(td)
+    nb = cap // bs
+    bt = torch.randperm(B * nb, generator=g).to(torch.int32).view(B, nb)
+    pool = inputs.to_paged(kc, bt, bs)
+    Hs = Hkv if rg else Hq
+    old = torch.rand(B, Hs, cap, generator=g)
+    got = kv.kvcrush_scores_append(qn.cuda(), pool.cuda(), old.clone().cuda(), S, rg, block_table=bt.cuda(),
+                                   block_size=bs)
+    dense = kv.kvcrush_scores_append(qn.cuda(), kc.cuda(), old.clone().cuda(), S, rg)
+    torch.cuda.synchronize()
+    want = oracle.scores_append(qn, kc, old.clone(), S, rg)
+    assert rel_err(got[:, :, :S], want[:, :, :S]) <= SCORE_RTOL
+    assert torch.equal(got.cpu()[:, :, S:], old[:, :, S:])
+    assert torch.equal(got, dense), "paged and dense caches must give identical bits"

@@ -207,8 +207,8 @@ def test_decode_entry_points_validation(lib):
     assert need >= 2 * 8 * 300 * 4
     assert binding.kvcrush_scores_append_workspace(sh(), 299) == 0        # capacity below the valid length
     assert binding.kvcrush_scores_append_workspace(sh(obs_window=8), 320) == 0
-    call = lambda shape, cap=320, q=FAKE, k=FAKE, sc=FAKE, ws=FAKE, n=1 << 40: \
-        lib.kvcrush_scores_append(ctypes.byref(shape), cap, None, q, k, sc, ws, n, None)
+    call = lambda shape, cap=320, q=FAKE, k=FAKE, sc=FAKE, ws=FAKE, n=1 << 40, bt=None, bs=16: \
+        lib.kvcrush_scores_append(ctypes.byref(shape), cap, None, q, k, bt, bs, sc, ws, n, None)
     assert call(sh(), cap=100) == binding.ERR_INVALID_ARG
     assert call(sh(Hq=7)) == binding.ERR_INVALID_ARG
     assert call(sh(D=32)) == binding.ERR_UNSUPPORTED
@@ -216,6 +216,8 @@ def test_decode_entry_points_validation(lib):
     assert call(sh(), k=ctypes.c_void_p(0x1002)) == binding.ERR_INVALID_ARG
     assert call(sh(), ws=None) == binding.ERR_WORKSPACE
     assert call(sh(), n=need - 1) == binding.ERR_WORKSPACE
+    assert call(sh(), cap=330, bt=FAKE, bs=16) == binding.ERR_INVALID_ARG     # capacity is not whole blocks
+    assert call(sh(), bt=FAKE, bs=0) == binding.ERR_INVALID_ARG
     other = ctypes.c_void_p(0x200000)
     cc = lambda B=1, Hkv=2, Hs=2, D=128, dtype=1, cs=100, cd=80, budget=40, k=FAKE, v=FAKE, sc=FAKE, idx=FAKE, \
         ko=other, vo=other, so=other: lib.kvcrush_compact_cache(B, Hkv, Hs, D, dtype, cs, cd, budget, k, v, sc, idx,
