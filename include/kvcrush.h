@@ -211,6 +211,19 @@ kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int32_t D, int
                                const int32_t* block_table, int32_t block_size, void* k_out,
                                void* v_out, void* hip_stream);
 
+/* Page-level eviction on a paged pool (Sec. 4.3.5): when kvcrush_select ran with
+ * unit == block_size on a sequence without protected ends, every kept unit is one
+ * pool block and the reduced cache needs no copy at all, only its block table:
+ *   block_table_out[b, j] = block_table[b, idx[b, j * block_size] / block_size],
+ *   j < budget / block_size.
+ *   idx          [B, budget] int32 as written by kvcrush_select (whole units)
+ *   block_table  [B, S / block_size] int32;  block_table_out [B, budget / block_size]
+ * S and budget must be multiples of block_size. */
+kvcrush_status kvcrush_compact_block_table(int32_t B, int32_t S, int32_t budget,
+                                           int32_t block_size, const int32_t* idx,
+                                           const int32_t* block_table, int32_t* block_table_out,
+                                           void* hip_stream);
+
 /* ------------------------------------------------------------- decoding --
  * The cache of a sequence that is being generated grows by one token per step
  * (Sec. 1) and the accumulated-attention importance keeps accumulating over

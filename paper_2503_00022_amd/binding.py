@@ -22,7 +22,8 @@ EXPORTS = (
     "kvcrush_scores_workspace", "kvcrush_scores", "kvcrush_row_lse_workspace", "kvcrush_row_lse",
     "kvcrush_pool_scores",
     "kvcrush_select_workspace", "kvcrush_select", "kvcrush_compact", "kvcrush_scores_append_workspace",
-    "kvcrush_scores_append", "kvcrush_compact_cache", "kvcrush_status_string", "kvcrush_version",
+    "kvcrush_scores_append", "kvcrush_compact_cache", "kvcrush_compact_block_table", "kvcrush_status_string",
+    "kvcrush_version",
 )
 
 
@@ -78,6 +79,8 @@ def load() -> ctypes.CDLL:
         L.kvcrush_scores_append.restype = ctypes.c_int
         L.kvcrush_compact_cache.argtypes = [i32] * 8 + [vp] * 8
         L.kvcrush_compact_cache.restype = ctypes.c_int
+        L.kvcrush_compact_block_table.argtypes = [i32] * 4 + [vp] * 4
+        L.kvcrush_compact_block_table.restype = ctypes.c_int
         L.kvcrush_status_string.argtypes = [ctypes.c_int]
         L.kvcrush_status_string.restype = ctypes.c_char_p
         L.kvcrush_version.restype = i32
@@ -335,6 +338,21 @@ def kvcrush_compact_cache(k, v, scores, idx, k_out, v_out, scores_out, stream=No
                                       _ptr(scores_out), _stream(stream))
     _check(st, "kvcrush_compact_cache")
     return k_out, v_out, scores_out
+
+
+def kvcrush_compact_block_table(idx, block_table, block_size: int, out=None, stream=None):
+    """Page-level eviction on a paged pool: idx [B,budget] (whole blocks, from kvcrush_select with
+    unit == block_size) and block_table [B,S/block_size] -> the kept blocks [B,budget/block_size]."""
+    idx, block_table = _dev(idx, "idx"), _dev(block_table, "block_table")
+    if idx.dtype != torch.int32 or block_table.dtype != torch.int32 or idx.shape[0] != block_table.shape[0]:
+        raise ValueError("idx and block_table must be int32 with the same batch size")
+    B, budget = idx.shape
+    if out is None:
+        out = torch.empty(B, budget // block_size, dtype=torch.int32, device=idx.device)
+    st = load().kvcrush_compact_block_table(B, block_table.shape[1] * block_size, budget, block_size, _ptr(idx),
+                                            _ptr(block_table), _ptr(_dev(out, "out")), _stream(stream))
+    _check(st, "kvcrush_compact_block_table")
+    return out
 
 
 def kvcrush_version() -> int:

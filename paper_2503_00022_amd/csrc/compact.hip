@@ -135,6 +135,35 @@ extern "C" kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int
   return launch_compact(p, (hipStream_t)hip_stream);
 }
 
+// Page-level eviction on a paged pool whose block size is the selection unit: nothing moves, the
+// reduced cache is the list of kept blocks.
+__global__ __launch_bounds__(kCompactThreads) void block_table_gather_kernel(const int32_t* idx,
+                                                                           const int32_t* block_table,
+                                                                           int32_t* out, int budget,
+                                                                           int unit, int blocks_src) {
+  const int b = blockIdx.y, kept = budget / unit;
+  for (int j = blockIdx.x * kCompactThreads + threadIdx.x; j < kept; j += gridDim.x * kCompactThreads)
+    out[(size_t)b * kept + j] = block_table[(size_t)b * blocks_src + idx[(size_t)b * budget + (size_t)j * unit] / unit];
+}
+
+extern "C" kvcrush_status kvcrush_compact_block_table(int32_t B, int32_t S, int32_t budget,
+                                                      int32_t block_size, const int32_t* idx,
+                                                      const int32_t* block_table,
+                                                      int32_t* block_table_out, void* hip_stream) {
+  if (B < 1 || S < 1 || block_size < 1 || budget < 0 || budget > S || S % block_size != 0 ||
+      budget % block_size != 0)
+    return KVCRUSH_ERR_INVALID_ARG;
+  if (budget == 0) return KVCRUSH_OK;
+  if (!idx || !block_table || !block_table_out) return KVCRUSH_ERR_INVALID_ARG;
+  if (B > 65535) return KVCRUSH_ERR_UNSUPPORTED;
+  const int kept = budget / block_size;
+  const int gx = std::min(64, (kept + kCompactThreads - 1) / kCompactThreads);
+  hipLaunchKernelGGL(block_table_gather_kernel, dim3(gx, B), dim3(kCompactThreads), 0,
+                     (hipStream_t)hip_stream, idx, block_table, block_table_out, budget, block_size,
+                     S / block_size);
+  return kvc::launch_status();
+}
+
 extern "C" kvcrush_status kvcrush_compact_cache(int32_t B, int32_t Hkv, int32_t Hs, int32_t D,
                                                 int32_t dtype, int32_t cap_src, int32_t cap_dst,
                                                 int32_t budget, const void* k, const void* v,

@@ -174,9 +174,15 @@ def test_page_level_pipeline_on_a_paged_cache(kv, oracle):
     rk, rv = oracle.compact(k, v, ridx)
     assert torch.equal(ko.cpu().view(torch.uint8), rk.view(torch.uint8))
     assert torch.equal(vo.cpu().view(torch.uint8), rv.view(torch.uint8))
-    # whole blocks are kept: the reduced cache's block table is a gather of the old one
+    # whole blocks are kept: the reduced cache's block table is a gather of the old one, and the
+    # pool read through it is the compacted cache (no data was moved)
     pages = idx.cpu()[0, ::16] // 16
     assert torch.equal(idx.cpu()[0].view(-1, 16), (pages[:, None] * 16 + torch.arange(16)[None, :]).to(torch.int32))
+    bt_small = kv.kvcrush_compact_block_table(idx, bt.cuda(), 16)
+    torch.cuda.synchronize()
+    assert torch.equal(bt_small.cpu()[0], bt[0, pages.long()])
+    via_table = kp[bt_small[0].long()].permute(2, 0, 1, 3).reshape(2, 512, 128)     # [Hkv, kept tokens, D]
+    assert torch.equal(via_table.cpu().view(torch.uint8), rk[0].view(torch.uint8))
 
 
 def test_per_layer_budgets_share_one_workspace(kv, oracle):

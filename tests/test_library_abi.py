@@ -229,6 +229,12 @@ def test_decode_entry_points_validation(lib):
     assert cc(ko=FAKE) == binding.ERR_INVALID_ARG            # in place
     assert cc(sc=None) == binding.ERR_INVALID_ARG
     assert cc(budget=0, k=None, v=None, sc=None, idx=None, ko=None, vo=None, so=None) == binding.OK
+    cb = lambda B=1, S=64, budget=32, bs=16, idx=FAKE, bt=FAKE, out=other: \
+        lib.kvcrush_compact_block_table(B, S, budget, bs, idx, bt, out, None)
+    assert cb(budget=40) == binding.ERR_INVALID_ARG          # not whole blocks
+    assert cb(S=70) == binding.ERR_INVALID_ARG
+    assert cb(out=None) == binding.ERR_INVALID_ARG
+    assert cb(budget=0, idx=None, bt=None, out=None) == binding.OK
     # strided score rows in the selection
     mk = binding.make_select_args
     assert binding.kvcrush_select_workspace(mk(1, 8, 100, 50, 10, score_stride=99)) == 0
