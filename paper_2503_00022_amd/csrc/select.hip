@@ -357,7 +357,8 @@ __global__ __launch_bounds__(256) void unit_rows_kernel(UnitRowsParams p) {
 // count table; K2b turns the table into start ranks and scatters.
 constexpr int kGsThreads = 256;
 constexpr int kGsWaves = kGsThreads / KVC_WAVE;
-constexpr int kGsChunksPerWg = 16;  // 1024 tokens a workgroup
+constexpr int kGsChunksPerWg = 16;  // 64-item chunks a workgroup takes (4 for long bit vectors, whose
+                                    // per-item work is large and whose item counts are small)
 constexpr uint32_t kNotGrouped = 0xFFFFFFFFu;
 constexpr int kDistBits = 12;  // distances range over 0..kMaxHs
 
@@ -385,9 +386,9 @@ __device__ __forceinline__ uint64_t splitmix64_next(uint64_t& state) {
 
 // WMAX: 64-bit words a bit vector may have (2 covers up to 128 score rows, kMaxW the page-level
 // vectors); loops over the words are unrolled so that the words stay in registers.
-template <int WMAX>
+template <int WMAX, int CPW>
 __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
-  extern __shared__ uint64_t lds_words[];       // this workgroup's slice [Hs+1][kGsChunksPerWg]
+  extern __shared__ uint64_t lds_words[];       // this workgroup's slice [Hs+1][CPW]
   __shared__ int run[kGsWaves][WMAX * 64 + 1];  // per wave: tokens seen so far per distance
   __shared__ int head_cnt[WMAX * 64];
   __shared__ uint64_t sh_anchor[WMAX];
@@ -395,12 +396,12 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
   const int b = blockIdx.y, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
   const int S = p.S, Hs = p.Hs, nw = p.nw, W = p.W;
   const uint64_t* __restrict__ rm = p.rowmask + (size_t)b * (Hs + 1) * nw;
-  const int wg_c0 = blockIdx.x * kGsChunksPerWg;
-  const int wg_nc = min(kGsChunksPerWg, nw - wg_c0);
+  const int wg_c0 = blockIdx.x * CPW;
+  const int wg_nc = min(CPW, nw - wg_c0);
 
   // this workgroup's words of every row -> LDS (read many times below)
-  for (int i = tid; i < (Hs + 1) * kGsChunksPerWg; i += kGsThreads) {
-    const int r = i / kGsChunksPerWg, c = i % kGsChunksPerWg;
+  for (int i = tid; i < (Hs + 1) * CPW; i += kGsThreads) {
+    const int r = i / CPW, c = i % CPW;
     lds_words[i] = c < wg_nc ? rm[(size_t)r * nw + wg_c0 + c] : 0ull;
   }
   for (int c = tid; c < wg_nc; c += kGsThreads) p.repmask[(size_t)b * nw + wg_c0 + c] = 0ull;
@@ -444,7 +445,7 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
 
   // ---- this wave's chunks: bit words out, distance, stable rank inside the wave
   const int gw = blockIdx.x * kGsWaves + wave;
-  constexpr int kPerWave = kGsChunksPerWg / kGsWaves;
+  constexpr int kPerWave = CPW / kGsWaves;
   const int c0 = min(nw, wg_c0 + wave * kPerWave), c1 = min(nw, c0 + kPerWave);
   for (int c = c0; c < c1; ++c) {
     const int lc = c - wg_c0;
@@ -456,13 +457,13 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
       uint64_t acc = 0ull;
       const int nb = min(64, Hs - 64 * w);  // rows in this word (<= 0: none)
       for (int rr = 0; rr < nb; ++rr) {
-        const uint64_t word = lds_words[(64 * w + rr) * kGsChunksPerWg + lc];  // same address for the whole wave
+        const uint64_t word = lds_words[(64 * w + rr) * CPW + lc];  // same address for the whole wave
         acc |= ((word >> lane) & 1ull) << rr;
       }
       bw[w] = acc;
       d += (uint32_t)__popcll(acc ^ anchor[w]);
     }
-    const bool grouped = t < S && !((lds_words[Hs * kGsChunksPerWg + lc] >> lane) & 1ull);
+    const bool grouped = t < S && !((lds_words[Hs * CPW + lc] >> lane) & 1ull);
     if (t < S) {
 #pragma unroll
       for (int w = 0; w < WMAX; ++w)
@@ -482,6 +483,7 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
     p.counts[((size_t)b * (Hs + 1) + d) * p.n_gw + gw] = run[wave][d];
 }
 
+template <int CPW>
 __global__ __launch_bounds__(kGsThreads) void group_scatter_kernel(GroupParams p) {
   extern __shared__ int lds_base[];  // [(Hs+1) * n_gw] start rank of every (distance, global wave)
   __shared__ int wave_tot[kGsWaves];
@@ -511,8 +513,8 @@ __global__ __launch_bounds__(kGsThreads) void group_scatter_kernel(GroupParams p
   __syncthreads();
 
   const int gw = blockIdx.x * kGsWaves + wave;
-  constexpr int kPerWave = kGsChunksPerWg / kGsWaves;
-  const int c0 = min(nw, (int)blockIdx.x * kGsChunksPerWg + wave * kPerWave), c1 = min(nw, c0 + kPerWave);
+  constexpr int kPerWave = CPW / kGsWaves;
+  const int c0 = min(nw, (int)blockIdx.x * CPW + wave * kPerWave), c1 = min(nw, c0 + kPerWave);
   int32_t* __restrict__ order = p.order + (size_t)b * S;
   for (int c = c0; c < c1; ++c) {
     const int t = c * 64 + lane;
@@ -592,6 +594,75 @@ __global__ __launch_bounds__(kMedoidThreads) void medoid_kernel(MedoidParams p) 
   if (lane == 0) {
     const int t = (int)(best & 0xFFFFFFFFull);
     atomicOr((unsigned long long*)&p.repmask[(size_t)b * p.nw + (t >> 6)], 1ull << (t & 63));
+  }
+}
+
+// Long bit vectors (page level: few buckets, hundreds of bits): a workgroup per bucket, the
+// four waves share the vector's words (wave w takes words w, w + 4, ...); counts stay inside a
+// wave, the members' costs are added across the waves through LDS.
+template <int WMAX>
+__global__ __launch_bounds__(kMedoidThreads) void medoid_wide_kernel(MedoidParams p) {
+  __shared__ unsigned int part[kMedoidWaves][KVC_WAVE];
+  const int b = blockIdx.y, lane = lane_id(), wave = threadIdx.x / KVC_WAVE;
+  const int j = blockIdx.x;  // bucket of this workgroup
+  const int W = p.W, Hs = p.Hs;
+  const long long lo = (long long)j * p.N / p.Br, hi = (long long)(j + 1) * p.N / p.Br;
+  const int n = (int)(hi - lo);
+  const int32_t* order = p.order + (size_t)b * p.S + lo;
+  const uint64_t* bits = p.bits + (size_t)b * p.bits_stride * W;
+  constexpr int kOwn = (WMAX + kMedoidWaves - 1) / kMedoidWaves;  // words a wave may own
+
+  int cnt[kOwn];
+#pragma unroll
+  for (int o = 0; o < kOwn; ++o) cnt[o] = 0;
+  for (int m0 = 0; m0 < n; m0 += KVC_WAVE) {
+    const int m = m0 + lane;
+    const int t = m < n ? order[m] : 0;
+#pragma unroll
+    for (int o = 0; o < kOwn; ++o) {
+      const int w = wave + o * kMedoidWaves;
+      const uint64_t bw = (m < n && w < W) ? bits[(size_t)t * W + w] : 0ull;
+      const int nb = min(64, Hs - 64 * w);
+      for (int rr = 0; rr < nb; ++rr) {
+        const int c = __popcll(__ballot((bw >> rr) & 1ull));
+        if (lane == rr) cnt[o] += c;
+      }
+    }
+  }
+  unsigned long long best = ~0ull;
+  for (int m0 = 0; m0 < n; m0 += KVC_WAVE) {
+    const int m = m0 + lane;
+    const int t = m < n ? order[m] : 0;
+    unsigned int cost = 0;
+#pragma unroll
+    for (int o = 0; o < kOwn; ++o) {
+      const int w = wave + o * kMedoidWaves;
+      const uint64_t bw = (m < n && w < W) ? bits[(size_t)t * W + w] : 0ull;
+      const int nb = min(64, Hs - 64 * w);
+      for (int rr = 0; rr < nb; ++rr) {
+        const int c = __shfl(cnt[o], rr);
+        cost += ((bw >> rr) & 1ull) ? (unsigned)(n - c) : (unsigned)c;
+      }
+    }
+    part[wave][lane] = cost;
+    __syncthreads();
+    if (wave == 0 && m < n) {
+      const unsigned int total = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+      const unsigned long long key = ((unsigned long long)total << 32) | (unsigned)t;
+      best = key < best ? key : best;
+    }
+    __syncthreads();
+  }
+  if (wave == 0) {
+#pragma unroll
+    for (int off = KVC_WAVE / 2; off > 0; off >>= 1) {
+      const unsigned long long o = __shfl_xor(best, off);
+      best = o < best ? o : best;
+    }
+    if (lane == 0) {
+      const int t = (int)(best & 0xFFFFFFFFull);
+      atomicOr((unsigned long long*)&p.repmask[(size_t)b * p.nw + (t >> 6)], 1ull << (t & 63));
+    }
   }
 }
 
@@ -682,7 +753,7 @@ struct SelectPlan {
   int unit, S_tok, nw_tok;     // tokens between the protected ends, their 64-token words
   int n_items, nw, Hv, W;      // items, their 64-item words, bits per item, 64-bit words per item
   int budget_items, imp_items; // kept / important items
-  int n_wg, n_gw;              // grouping workgroups / global waves per sequence
+  int cpw, n_wg, n_gw;         // chunks per grouping workgroup, workgroups / global waves per sequence
   bool keys_in_lds;
   // workspace offsets
   size_t rowmask_tok, rowmask, repmask, bits, order, dist_rank, counts, keys, total;
@@ -729,7 +800,11 @@ SelectPlan select_plan(const kvcrush_select_args* a, bool need_bits_ws) {
   P.budget_items = (a->budget - a->n_sink - a->n_recent) / P.unit;
   P.imp_items = a->n_important / P.unit;
   P.keys_in_lds = P.S_tok <= kLdsKeyCapacity;
-  P.n_wg = (P.nw + kGsChunksPerWg - 1) / kGsChunksPerWg;
+  // long vectors: a quarter of the chunks per workgroup, as long as the scatter's count table
+  // ((bits + 1) x global waves) still fits LDS
+  P.cpw = kGsChunksPerWg;
+  if (P.W > 2 && (size_t)(P.Hv + 1) * ((P.nw + 3) / 4) * kGsWaves * 4 <= 96 * 1024) P.cpw = 4;
+  P.n_wg = (P.nw + P.cpw - 1) / P.cpw;
   P.n_gw = P.n_wg * kGsWaves;
   const size_t B = (size_t)a->B;
   size_t off = 0;
@@ -756,28 +831,31 @@ SelectPlan select_plan(const kvcrush_select_args* a, bool need_bits_ws) {
   return P;
 }
 
-template <int WMAX>
+template <int WMAX, int CPW>
 kvcrush_status launch_grouping(const GroupParams& g, const MedoidParams& m, const SelectPlan& P, int B,
                                int Br, hipStream_t stream) {
-  const size_t dyn_a = (size_t)(P.Hv + 1) * kGsChunksPerWg * 8;
+  const size_t dyn_a = (size_t)(P.Hv + 1) * CPW * 8;
   if (dyn_a > 32 * 1024) {
-    if (hipFuncSetAttribute((const void*)group_rank_kernel<WMAX>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)dyn_a) != hipSuccess)
+    if (hipFuncSetAttribute((const void*)group_rank_kernel<WMAX, CPW>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_a) != hipSuccess)
       return KVCRUSH_ERR_HIP;
   }
-  hipLaunchKernelGGL(group_rank_kernel<WMAX>, dim3(P.n_wg, B), dim3(kGsThreads), dyn_a, stream, g);
+  hipLaunchKernelGGL((group_rank_kernel<WMAX, CPW>), dim3(P.n_wg, B), dim3(kGsThreads), dyn_a, stream, g);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   const size_t dyn_b = (size_t)(P.Hv + 1) * P.n_gw * 4;
   if (dyn_b > 32 * 1024) {
-    if (hipFuncSetAttribute((const void*)group_scatter_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)group_scatter_kernel<CPW>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)dyn_b) != hipSuccess)
       return KVCRUSH_ERR_HIP;
   }
-  hipLaunchKernelGGL(group_scatter_kernel, dim3(P.n_wg, B), dim3(kGsThreads), dyn_b, stream, g);
+  hipLaunchKernelGGL(group_scatter_kernel<CPW>, dim3(P.n_wg, B), dim3(kGsThreads), dyn_b, stream, g);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   if (Br > 0) {
-    hipLaunchKernelGGL(medoid_kernel<WMAX>, dim3((Br + kMedoidWaves - 1) / kMedoidWaves, B),
-                       dim3(kMedoidThreads), 0, stream, m);
+    if (WMAX > 2 && Br <= 65535)
+      hipLaunchKernelGGL(medoid_wide_kernel<WMAX>, dim3(Br, B), dim3(kMedoidThreads), 0, stream, m);
+    else
+      hipLaunchKernelGGL(medoid_kernel<WMAX>, dim3((Br + kMedoidWaves - 1) / kMedoidWaves, B),
+                         dim3(kMedoidThreads), 0, stream, m);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
   return KVCRUSH_OK;
@@ -803,7 +881,7 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
   const SelectPlan P = select_plan(args, bits == nullptr);
   if (P.total > 0 && (!workspace || workspace_bytes < P.total)) return KVCRUSH_ERR_WORKSPACE;
   // LDS tables of the grouping: (bits + 1) x 16 chunk words, (bits + 1) x global waves counters
-  if ((size_t)(P.Hv + 1) * kGsChunksPerWg * 8 > 136 * 1024 || (size_t)(P.Hv + 1) * P.n_gw * 4 > 120 * 1024)
+  if ((size_t)(P.Hv + 1) * P.cpw * 8 > 136 * 1024 || (size_t)(P.Hv + 1) * P.n_gw * 4 > 120 * 1024)
     return KVCRUSH_ERR_UNSUPPORTED;
 
   hipStream_t stream = (hipStream_t)hip_stream;
@@ -890,9 +968,15 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
     m.W = P.W;
     m.N = N;
     m.Br = Br;
-    const kvcrush_status st = P.W <= 2   ? launch_grouping<2>(g, m, P, B, Br, stream)
-                              : P.W <= 4 ? launch_grouping<4>(g, m, P, B, Br, stream)
-                                         : launch_grouping<kMaxW>(g, m, P, B, Br, stream);
+    kvcrush_status st;
+    if (P.W <= 2)
+      st = launch_grouping<2, kGsChunksPerWg>(g, m, P, B, Br, stream);
+    else if (P.W <= 4)
+      st = P.cpw == 4 ? launch_grouping<4, 4>(g, m, P, B, Br, stream)
+                      : launch_grouping<4, kGsChunksPerWg>(g, m, P, B, Br, stream);
+    else
+      st = P.cpw == 4 ? launch_grouping<kMaxW, 4>(g, m, P, B, Br, stream)
+                      : launch_grouping<kMaxW, kGsChunksPerWg>(g, m, P, B, Br, stream);
     if (st != KVCRUSH_OK) return st;
   }
   if (args->budget > 0) {
