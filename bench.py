@@ -250,11 +250,19 @@ def main():
         if ev:
             ev[4].record()
 
+    copy_gbs = None
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
         dst.copy_(src)       # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        c1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 10 * 2.0 * (256 << 20) / (c0.elapsed_time(c1) * 1e-3) / 1e9   # read + write
         del src, dst
 
     for i in range(args.warmup):
@@ -334,6 +342,8 @@ def main():
     }
     if args.graph:
         out["eager_ms_per_step"] = eager_ms_per_step
+    if copy_gbs is not None:
+        out["plain_copy_gbs"] = copy_gbs   # the runtime's device-to-device copy of 256 MiB, read + write
     if not args.no_cpu_baseline:
         # layer 0 again, so that its scores are the ones handed to the oracle's selection
         step(0)
