@@ -46,7 +46,8 @@ struct AppendParams {
   const int* block_table;  // null: k is dense [B,Hkv,capacity,D]; else k is a pool
                            // [n_blocks,block_size,Hkv,D] and block_table [B,capacity/block_size]
   int block_size;
-  int B, Hq, Hkv, S, capacity, G, reduce_groups, n_kb;  // S: valid tokens, or their upper bound with lengths
+  int B, Hq, Hkv, S, capacity, G, reduce_groups;  // S: valid tokens, or their upper bound with lengths
+  int logit_keys, n_kb;  // keys per workgroup of the logits kernel, and how many such blocks S has
   float scale_log2;    // log2(e) / sqrt(D)
 };
 
@@ -168,25 +169,27 @@ __global__ __launch_bounds__(kThreads) void append_logits_kernel(AppendParams p)
 }
 
 // bf16: logits of 256 keys x up to 32 heads per pass on the matrix cores.
-template <int D>
+// TPW: 64-row tiles per workgroup (4: one tile per wave; 2: two waves share a tile, one 32-row half
+// each, which halves the LDS per workgroup so that more of them overlap their loads on a CU).
+template <int D, int TPW>
 __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendParams p) {
   using C = Cfg<true, D>;
-  static_assert(C::kTile * kWaves == kKeysPerWg, "one 64-row tile per wave");
-  __shared__ __attribute__((aligned(1024))) char lds[kWaves][C::kTileBytes];
+  constexpr int kSubs = 2 * TPW / kWaves;  // 32-row halves a wave multiplies: 2 or 1
+  __shared__ __attribute__((aligned(1024))) char lds[TPW][C::kTileBytes];
   __shared__ float red[2][kWaves][32];
 
   const int tid = threadIdx.x, lane = kvc::lane_id(), wave = tid / KVC_WAVE;
   const int kb = blockIdx.x, bg = blockIdx.y;  // bg = b * Hkv + kv head
   const int b = bg / p.Hkv, g = bg % p.Hkv;
   const int S = p.lengths ? min(max(p.lengths[b], 1), p.S) : p.S;
-  const int k0 = kb * kKeysPerWg;
+  const int k0 = kb * (C::kTile * TPW);
   if (k0 >= S) return;  // this sequence is shorter than the launch's upper bound (uniform exit)
   const char* kh = p.k + (size_t)bg * p.capacity * C::kRowBytes;
 
   uint32_t rel[C::kLoadsPerWave];
   tile_lane_offsets<C>(rel, wave, lane);
 #pragma unroll
-  for (int w = 0; w < kWaves; ++w) {
+  for (int w = 0; w < TPW; ++w) {
     const int row0 = k0 + C::kTile * w;
     if (row0 >= S) continue;  // tiles past the end stay unread
     if (!p.block_table) {
@@ -208,7 +211,8 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
 
   const int n = lane & 31;  // result column of this lane = head inside the chunk
   const int off0 = lds_frag_offset0<C>(lane);
-  const int key_base = k0 + C::kTile * wave + 4 * (lane >> 5);  // + 32 * sub + 8 * (r / 4) + r % 4
+  const int my_tile = wave % TPW, sub0 = (wave / TPW) * kSubs;  // this wave's rows: tile, first half
+  const int key_base = k0 + C::kTile * my_tile + 32 * sub0 + 4 * (lane >> 5);  // + 32 * sub + 8 * (r / 4) + r % 4
   for (int h0 = 0; h0 < p.G; h0 += 32) {
     const int nh = min(32, p.G - h0);
     const size_t bh = (size_t)b * p.Hq + g * p.G + h0 + min(n, nh - 1);
@@ -219,18 +223,19 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
       if (n >= nh) v = u32x4{0u, 0u, 0u, 0u};
       qf[s] = v;
     }
-    f32x16 acc[2];
+    f32x16 acc[kSubs];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int sub = 0; sub < kSubs; ++sub) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[sub][r] = 0.0f;
 #pragma unroll
-      for (int s = 0; s < C::kSteps; ++s) mma_step<true>(acc[sub], lds_frag<C>(lds[wave], off0, sub, s), qf[s]);
+      for (int s = 0; s < C::kSteps; ++s)
+        mma_step<true>(acc[sub], lds_frag<C>(lds[my_tile], off0, sub0 + sub, s), qf[s]);
     }
-    // this lane: 32 keys of head n.  Keys past the end (and whole unread tiles) are masked here.
+    // this lane: 16 * kSubs keys of head n.  Keys past the end (and whole unread tiles) are masked here.
     float m = kNegBig;
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+    for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = key_base + 32 * sub + 8 * (r >> 2) + (r & 3);
@@ -244,7 +249,7 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
     m = fmaxf(fmaxf(red[0][0][n], red[0][1][n]), fmaxf(red[0][2][n], red[0][3][n]));
     float l = 0.0f;
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+    for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) l += __builtin_amdgcn_exp2f(acc[sub][r] - m);  // masked keys: 2^-huge = 0
     l += __shfl_xor(l, 32);
@@ -257,7 +262,7 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
     if (n < nh) {
       float* dst = p.logits + bh * p.S;
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
+      for (int sub = 0; sub < kSubs; ++sub)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = key_base + 32 * sub + 8 * (r >> 2) + (r & 3);
@@ -277,7 +282,7 @@ __global__ __launch_bounds__(kThreads) void append_update_kernel(AppendParams p)
   const int h_first = p.reduce_groups ? r * p.G : r, n_heads = p.reduce_groups ? p.G : 1;
   const int S = p.lengths ? min(max(p.lengths[b], 1), p.S) : p.S;
   if (kb * kKeysPerWg >= S) return;
-  const int n_kb = (S + kKeysPerWg - 1) / kKeysPerWg;  // blocks that wrote a pair for this sequence
+  const int n_kb = (S + p.logit_keys - 1) / p.logit_keys;  // blocks that wrote a pair for this sequence
   const int key = kb * kKeysPerWg + tid;
   float acc = 0.0f;
   for (int i = 0; i < n_heads; ++i) {
@@ -305,7 +310,12 @@ size_t logits_bytes(const kvcrush_shape* s) {
   return kvc::align_up((size_t)s->B * s->Hq * s->S * sizeof(float), 256);
 }
 
-int key_blocks(const kvcrush_shape* s) { return (s->S + kKeysPerWg - 1) / kKeysPerWg; }
+// Keys per workgroup of the logits kernel.  (Two tiles per workgroup on the matrix-core path, 128 keys,
+// measured no faster than four: the kernel is not short of loads in flight.)
+constexpr int kMfmaTilesPerWg = 4;
+int logit_keys(const kvcrush_shape* s) { return s->dtype == KVCRUSH_BF16 ? 64 * kMfmaTilesPerWg : kKeysPerWg; }
+
+int key_blocks(const kvcrush_shape* s) { return (s->S + logit_keys(s) - 1) / logit_keys(s); }
 
 size_t part_bytes(const kvcrush_shape* s) {
   return kvc::align_up((size_t)s->B * s->Hq * key_blocks(s) * sizeof(float2), 256);
@@ -324,13 +334,14 @@ bool append_shape_ok(const kvcrush_shape* s, int capacity) {
 template <bool BF16, int D>
 kvcrush_status launch_append(const AppendParams& p, hipStream_t stream) {
   if constexpr (BF16) {
-    hipLaunchKernelGGL((append_logits_mfma_kernel<D>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((append_logits_mfma_kernel<D, kMfmaTilesPerWg>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
   } else {
     hipLaunchKernelGGL((append_logits_kernel<BF16, D>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
   }
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   const int Hs = p.reduce_groups ? p.Hkv : p.Hq;
-  hipLaunchKernelGGL(append_update_kernel, dim3(p.n_kb, p.B * Hs), dim3(kThreads), 0, stream, p);
+  hipLaunchKernelGGL(append_update_kernel, dim3((p.S + kKeysPerWg - 1) / kKeysPerWg, p.B * Hs), dim3(kThreads), 0,
+                     stream, p);
   return kvc::launch_status();
 }
 
@@ -372,6 +383,7 @@ extern "C" kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int3
   p.capacity = capacity;
   p.G = shape->Hq / shape->Hkv;
   p.reduce_groups = shape->reduce_groups;
+  p.logit_keys = logit_keys(shape);
   p.n_kb = key_blocks(shape);
   p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)shape->D));
   hipStream_t stream = (hipStream_t)hip_stream;
