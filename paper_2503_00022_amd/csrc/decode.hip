@@ -206,23 +206,31 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
       }
     }
   }
-  wait_async_loads();
-  __syncthreads();
-
   const int n = lane & 31;  // result column of this lane = head inside the chunk
-  const int off0 = lds_frag_offset0<C>(lane);
-  const int my_tile = wave % TPW, sub0 = (wave / TPW) * kSubs;  // this wave's rows: tile, first half
-  const int key_base = k0 + C::kTile * my_tile + 32 * sub0 + 4 * (lane >> 5);  // + 32 * sub + 8 * (r / 4) + r % 4
-  for (int h0 = 0; h0 < p.G; h0 += 32) {
+  // query vectors of a chunk of up to 32 heads, as the MFMA's column operand (issued before the
+  // wait for the tiles, so that the two latencies overlap)
+  u32x4 qf[C::kSteps];
+  auto load_q = [&](int h0) {
     const int nh = min(32, p.G - h0);
     const size_t bh = (size_t)b * p.Hq + g * p.G + h0 + min(n, nh - 1);
-    u32x4 qf[C::kSteps];
 #pragma unroll
     for (int s = 0; s < C::kSteps; ++s) {
       u32x4 v = *(const u32x4*)(p.q_new + bh * C::kRowBytes + (s + (lane >> 5) * C::kSteps) * 16);
       if (n >= nh) v = u32x4{0u, 0u, 0u, 0u};
       qf[s] = v;
     }
+  };
+  load_q(0);
+  wait_async_loads();
+  __syncthreads();
+
+  const int off0 = lds_frag_offset0<C>(lane);
+  const int my_tile = wave % TPW, sub0 = (wave / TPW) * kSubs;  // this wave's rows: tile, first half
+  const int key_base = k0 + C::kTile * my_tile + 32 * sub0 + 4 * (lane >> 5);  // + 32 * sub + 8 * (r / 4) + r % 4
+  for (int h0 = 0; h0 < p.G; h0 += 32) {
+    const int nh = min(32, p.G - h0);
+    const size_t bh = (size_t)b * p.Hq + g * p.G + h0 + min(n, nh - 1);
+    if (h0 > 0) load_q(h0);
     f32x16 acc[kSubs];
 #pragma unroll
     for (int sub = 0; sub < kSubs; ++sub) {
