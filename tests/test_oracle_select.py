@@ -458,3 +458,17 @@ def test_unit_level_hand_worked_example(oracle):
     # {2, 1, 3} (pairwise distances 2-1: 2, 2-3: 3, 1-3: 1 -> costs 5, 3, 4) is page 1
     idx1, kind1, _ = oracle.select_units(sc, 2, 4, 2, 3, "alternating")
     assert idx1.tolist() == [[0, 1, 2, 3]] and kind1.tolist() == [[0, 0, 1, 1]]
+
+
+def test_equal_bit_vectors_give_the_first_token_of_each_rank_range(oracle):
+    """All grouped tokens alike: every distance and every cost ties, so each bucket's
+    representative is its lowest token, i.e. the first of its rank range."""
+    S, Hs, Br = 23, 6, 5
+    bw = torch.full((S, 1), 0b101101, dtype=torch.int64)
+    imp = torch.zeros(S, dtype=torch.uint8)
+    imp[[0, 7, 8]] = 1
+    disc = [t for t in range(S) if t not in (0, 7, 8)]
+    N = len(disc)
+    for anchor in ("alternating", "mean", "random"):
+        reps, _ = oracle.group(Hs, bw, imp, Br, anchor=anchor, anchor_seed=3)
+        assert reps.tolist() == [disc[j * N // Br] for j in range(Br)]
