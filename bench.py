@@ -296,6 +296,7 @@ def main():
         ms_per_step = (time.perf_counter() - t0) * 1e3 / (replays * n_layers)
     stage = [sum(e[j].elapsed_time(e[j + 1]) for e in evs) / args.steps for j in range(4)]  # ms
     t_lse, t_col, t_sel, t_cmp = stage
+    med = [sorted(e[j].elapsed_time(e[j + 1]) for e in evs)[len(evs) // 2] for j in range(4)]
     tokens = w.B * w.S
 
     # algorithmic work (what the method must compute / move, not what a kernel happens to do)
@@ -321,6 +322,7 @@ def main():
         "select_compact_gbs": (bytes_sel + bytes_cmp) / ((t_sel + t_cmp) * 1e-3) / 1e9,
         "select_compact_frac_of_hbm_peak": (bytes_sel + bytes_cmp) / ((t_sel + t_cmp) * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "compact_gbs": bytes_cmp / (t_cmp * 1e-3) / 1e9,
+        "median_ms": {"lse": med[0], "colsum": med[1], "select": med[2], "compact": med[3]},
     }
 
     # cheap sanity check of the last step's scores: every row totals (group size) x S
