@@ -31,12 +31,24 @@
 //     sum_r (bit_r ? n - cnt_r : cnt_r).
 //   * Every tie goes to the lower token index.  Output ascending by position.
 //
+// Beyond the five stages the same file states the variants the paper pairs the
+// method with: scoring from an observation window of the last queries and max
+// pooling of the scores (the SnapKV baseline as Sec. 2.3 / 4.1.1 summarise it),
+// protected initial and recent tokens (Table 1's cache layout), chunk- / page-
+// level selection (Sec. 4.3.4, 4.3.5), and the decoding-time steps (one more
+// query row per generated token, eviction on capacity-strided caches).
+//
 // Parity pins (tests/test_oracle_*.py): brute force with the full SxS matrix,
 // the harmonic closed form for uniform attention, column sums totalling the
 // number of query rows, float64 library softmax, hand-worked Hamming/bucket
-// examples, splitmix64's published first outputs.  Whether the retained
-// tokens preserve model accuracy is "parity unpinned" (needs the paper's
-// datasets and weights).
+// examples (token and page level), splitmix64's published first outputs, an
+// independent big-integer implementation of the whole selection (also on the
+// middle between protected ends and on pages), library max pooling, the
+// identity "prefix scored at once + one append per later token = the whole
+// sequence scored at once", strided gathers against a library gather; and a
+// mutation test that plants single mistakes in a copy of this file and checks
+// that a named pin notices each.  Whether the retained tokens preserve model
+// accuracy is "parity unpinned" (needs the paper's datasets and weights).
 //
 // Build: g++ -O2 -std=c++17 -ffp-contract=off -fno-fast-math -shared -fPIC
 
