@@ -389,19 +389,21 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
 }
 
 // lse of the rows whose keys were cut into slices: the slices' (reference, sum)
-// pairs stand for sum * 2^reference; added up in slice order.
+// pairs stand for sum * 2^reference.  One wave per query row, lane s holds slice
+// s (there are at most 64); the sum over the slices is a fixed shuffle tree.
 __global__ __launch_bounds__(256) void lse_combine_kernel(ScoreParams p) {
-  const int r = blockIdx.x * 256 + threadIdx.x, bh = blockIdx.y;  // bh = b * Hq + head
+  const int lane = kvc::lane_id();
+  const int r = blockIdx.x * (256 / KVC_WAVE) + threadIdx.x / KVC_WAVE, bh = blockIdx.y;  // bh = b * Hq + head
   if (r >= p.split_rows) return;
-  const float2* src = p.split_ml + (size_t)bh * p.n_split * p.split_rows + r;
-  float mt = kNegBig;
-  for (int s = 0; s < p.n_split; ++s) mt = fmaxf(mt, src[(size_t)s * p.split_rows].x);
-  float lt = 0.0f;
-  for (int s = 0; s < p.n_split; ++s) {
-    const float2 ml = src[(size_t)s * p.split_rows];
-    lt += ml.y * __builtin_amdgcn_exp2f(ml.x - mt);
-  }
-  p.lse[(size_t)bh * p.S + p.split_q0 + r] = (mt + __builtin_amdgcn_logf(lt)) * kLn2;
+  float2 ml = make_float2(kNegBig, 0.0f);
+  if (lane < p.n_split) ml = p.split_ml[((size_t)bh * p.n_split + lane) * p.split_rows + r];
+  float mt = ml.x;
+#pragma unroll
+  for (int off = KVC_WAVE / 2; off > 0; off >>= 1) mt = fmaxf(mt, __shfl_xor(mt, off));
+  float lt = ml.y * __builtin_amdgcn_exp2f(ml.x - mt);
+#pragma unroll
+  for (int off = KVC_WAVE / 2; off > 0; off >>= 1) lt += __shfl_xor(lt, off);
+  if (lane == 0) p.lse[(size_t)bh * p.S + p.split_q0 + r] = (mt + __builtin_amdgcn_logf(lt)) * kLn2;
 }
 
 // ------------------------------------------------------------- pass B ------
@@ -656,6 +658,7 @@ struct LsePlan {
 constexpr int kWantedWorkgroups = 1024;  // four per compute unit
 constexpr int kMinTilesPerSlice = 4;
 constexpr int kMaxSplit = 64;
+static_assert(kMaxSplit <= KVC_WAVE, "lse_combine_kernel gives one lane to each slice");
 
 LsePlan lse_plan(int B, int Hq, int Hkv, int S, bool bf16, int q_first, bool may_split) {
   LsePlan pl;
@@ -699,8 +702,7 @@ kvcrush_status launch_lse(const ScoreParams& base, float2* split_ml, hipStream_t
                      dim3(kThreads), 0, stream, a);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   if (pl.n_split > 1) {
-    hipLaunchKernelGGL(lse_combine_kernel, dim3((pl.split_rows + 255) / 256, a.B * a.Hq), dim3(256), 0,
-                       stream, a);
+    hipLaunchKernelGGL(lse_combine_kernel, dim3((pl.split_rows + 3) / 4, a.B * a.Hq), dim3(256), 0, stream, a);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
   return KVCRUSH_OK;
