@@ -76,6 +76,11 @@ typedef struct {
                             observation window of the SnapKV baseline, Sec. 2.3);
                             every score row then totals W instead of S, and lse rows
                             before the window are unspecified / not needed.           */
+  float softmax_scale;   /* factor on Q . K before the softmax; 0 means 1 / sqrt(D).
+                            Heads of another size are scored by zero-padding them to
+                            64 or 128 values and passing 1 / sqrt(true size) here
+                            (e.g. 96-value heads: D = 128, softmax_scale = 1/sqrt(96));
+                            models with their own attention scale pass that.          */
 } kvcrush_shape;
 
 /* ---------------------------------------------------------------- stage 1 --

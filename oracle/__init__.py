@@ -45,10 +45,11 @@ def lib() -> ctypes.CDLL:
     if _lib is None:
         L = ctypes.CDLL(_LIB_OVERRIDE or build())
         vp, i32, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64
-        L.kvcrush_oracle_head_colsums.argtypes = [i32, i32, i32, vp, vp, i32, i32, vp, vp]
-        L.kvcrush_oracle_scores.argtypes = [i32] * 8 + [vp] * 4
+        f64 = ctypes.c_double
+        L.kvcrush_oracle_head_colsums.argtypes = [i32, i32, i32, vp, vp, i32, i32, f64, vp, vp]
+        L.kvcrush_oracle_scores.argtypes = [i32] * 8 + [f64] + [vp] * 4
         L.kvcrush_oracle_maxpool.argtypes = [i32, i32, i32, vp, vp]
-        L.kvcrush_oracle_scores_append.argtypes = [i32] * 8 + [vp, vp, vp]
+        L.kvcrush_oracle_scores_append.argtypes = [i32] * 8 + [f64, vp, vp, vp]
         L.kvcrush_oracle_compact_cache.argtypes = [i32] * 8 + [vp] * 7
         L.kvcrush_oracle_topk.argtypes = [vp, i32, i32, vp]
         L.kvcrush_oracle_splitmix64.argtypes = [u64, i32, vp]
@@ -89,7 +90,7 @@ def words_for(Hs: int) -> int:
     return (Hs + 63) // 64
 
 
-def head_colsums(q_head, k_head, row_begin=0, row_end=None, want_lse=False):
+def head_colsums(q_head, k_head, row_begin=0, row_end=None, want_lse=False, scale=0.0):
     """Received attention for one head over query rows [row_begin, row_end).
 
     q_head, k_head: [S, D].  Returns float64 [S] (and float64 lse [S], zero
@@ -100,16 +101,16 @@ def head_colsums(q_head, k_head, row_begin=0, row_end=None, want_lse=False):
     c = torch.zeros(S, dtype=torch.float64)
     lse = torch.zeros(S, dtype=torch.float64) if want_lse else None
     rc = lib().kvcrush_oracle_head_colsums(S, D, _dtype_code(q_head), _ptr(q_head), _ptr(k_head),
-                                           row_begin, row_end, _ptr(c), _ptr(lse))
+                                           row_begin, row_end, scale, _ptr(c), _ptr(lse))
     _check(rc, "head_colsums")
     return (c, lse) if want_lse else c
 
 
-def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1, window: int = 0):
+def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1, window: int = 0, scale: float = 0.0):
     """scores [B,Hs,S] fp32 from q [B,Hq,S,D], k [B,Hkv,S,D].
 
     window = W > 0: only the last min(W, S) query rows contribute (lse rows
-    before the window are zero).
+    before the window are zero).  scale: factor on the dot products (0: 1/sqrt(D)).
 
     threads > 1 spreads independent (batch, head) units of the unchanged
     single-threaded routine over host threads (the foreign call releases the
@@ -124,7 +125,7 @@ def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1, window: 
     if threads <= 1:
         out = torch.empty(B, Hs, S, dtype=torch.float32)
         lse = torch.empty(B, Hq, S, dtype=torch.float32) if want_lse else None
-        rc = lib().kvcrush_oracle_scores(B, Hq, Hkv, S, D, _dtype_code(q), int(reduce_groups), window,
+        rc = lib().kvcrush_oracle_scores(B, Hq, Hkv, S, D, _dtype_code(q), int(reduce_groups), window, scale,
                                          _ptr(q), _ptr(k), _ptr(out), _ptr(lse))
         _check(rc, "scores")
         return (out, lse) if want_lse else out
@@ -133,7 +134,7 @@ def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1, window: 
     units = [(b, h) for b in range(B) for h in range(Hq)]
     with ThreadPoolExecutor(max_workers=threads) as ex:
         res = list(ex.map(lambda u: head_colsums(q[u[0], u[1]], k[u[0], u[1] // G], row_begin, S,
-                                                 want_lse=True), units))
+                                                 want_lse=True, scale=scale), units))
     c = torch.stack([r[0] for r in res]).view(B, Hq, S)
     lse = torch.stack([r[1] for r in res]).view(B, Hq, S).to(torch.float32)
     if reduce_groups:
@@ -146,7 +147,7 @@ def scores(q, k, reduce_groups: bool, want_lse=False, threads: int = 1, window: 
     return (out, lse) if want_lse else out
 
 
-def scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool):
+def scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool, scale: float = 0.0):
     """One decoding step, in place on scores_cache [B,Hs,capacity] (fp32): the new token's
     queries q_new [B,Hq,D] attend to the first S tokens of k_cache [B,Hkv,capacity,D]."""
     q_new, k_cache = _cpu(q_new), _cpu(k_cache)
@@ -154,7 +155,7 @@ def scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool):
     B, Hq, D = q_new.shape
     Hkv, cap = k_cache.shape[1], k_cache.shape[2]
     assert scores_cache.shape == (B, Hkv if reduce_groups else Hq, cap)
-    rc = lib().kvcrush_oracle_scores_append(B, Hq, Hkv, S, cap, D, _dtype_code(q_new), int(reduce_groups),
+    rc = lib().kvcrush_oracle_scores_append(B, Hq, Hkv, S, cap, D, _dtype_code(q_new), int(reduce_groups), scale,
                                             _ptr(q_new), _ptr(k_cache), _ptr(scores_cache))
     _check(rc, "scores_append")
     return scores_cache

@@ -107,12 +107,14 @@ extern "C" {
 // [row_begin, row_end) puts on key t <= i.  q_head, k_head: [S, D] row-major.
 // lse (nullable, [S]) receives log(sum_j exp(s_ij)) for the rows visited.
 // c is accumulated into (caller zeroes it), so disjoint row ranges add up.
+// scale: factor on the dot products; 0 means the usual 1 / sqrt(D) (heads stored with padding, or
+// models with their own attention scale, pass theirs).
 int kvcrush_oracle_head_colsums(int S, int D, int dtype, const void* q_head, const void* k_head,
-                                int row_begin, int row_end, double* c, double* lse) {
+                                int row_begin, int row_end, double scale, double* c, double* lse) {
   if (S < 1 || D < 1 || row_begin < 0 || row_end > S || row_begin > row_end) return 1;
   std::vector<double> kd((size_t)S * D), qrow(D), s(S), p(S);
   for (size_t i = 0; i < (size_t)S * D; ++i) kd[i] = widen(k_head, i, dtype);
-  const double inv_sqrt_d = 1.0 / std::sqrt((double)D);
+  const double inv_sqrt_d = scale != 0.0 ? scale : 1.0 / std::sqrt((double)D);
   for (int i = row_begin; i < row_end; ++i) {
     for (int d = 0; d < D; ++d) qrow[d] = widen(q_head, (size_t)i * D + d, dtype);
     double m = -INFINITY;
@@ -143,7 +145,7 @@ int kvcrush_oracle_head_colsums(int S, int D, int dtype, const void* q_head, con
 // prompt, as Sec. 2.3 summarises that baseline); lse_out rows before the
 // window are left at zero.
 int kvcrush_oracle_scores(int B, int Hq, int Hkv, int S, int D, int dtype, int reduce_groups,
-                          int obs_window, const void* q, const void* k, float* scores,
+                          int obs_window, double scale, const void* q, const void* k, float* scores,
                           float* lse_out) {
   if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || D < 1 || obs_window < 0) return 1;
   const int row_begin = (obs_window == 0 || obs_window >= S) ? 0 : S - obs_window;
@@ -159,7 +161,7 @@ int kvcrush_oracle_scores(int B, int Hq, int Hkv, int S, int D, int dtype, int r
         const char* qh = (const char*)q + ((size_t)b * Hq + h) * head_elems * es;
         const char* kh = (const char*)k + ((size_t)b * Hkv + g) * head_elems * es;
         std::fill(lse.begin(), lse.end(), 0.0);
-        int rc = kvcrush_oracle_head_colsums(S, D, dtype, qh, kh, row_begin, S, c.data(), lse.data());
+        int rc = kvcrush_oracle_head_colsums(S, D, dtype, qh, kh, row_begin, S, scale, c.data(), lse.data());
         if (rc) return rc;
         if (lse_out)
           for (int t = 0; t < S; ++t) lse_out[((size_t)b * Hq + h) * S + t] = (float)lse[t];
@@ -187,11 +189,11 @@ int kvcrush_oracle_scores(int B, int Hq, int Hkv, int S, int D, int dtype, int r
 // group's heads are summed in double, heads ascending, before the single
 // rounding to float of old + sum.
 int kvcrush_oracle_scores_append(int B, int Hq, int Hkv, int S, int capacity, int D, int dtype,
-                                 int reduce_groups, const void* q_new, const void* k,
+                                 int reduce_groups, double scale, const void* q_new, const void* k,
                                  float* scores) {
   if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || S < 1 || capacity < S || D < 1) return 1;
   const int G = Hq / Hkv, Hs = reduce_groups ? Hkv : Hq;
-  const double inv_sqrt_d = 1.0 / std::sqrt((double)D);
+  const double inv_sqrt_d = scale != 0.0 ? scale : 1.0 / std::sqrt((double)D);
   std::vector<double> logit(S), add(S);
   for (int b = 0; b < B; ++b)
     for (int r = 0; r < Hs; ++r) {

@@ -35,7 +35,7 @@ class KVCrushError(RuntimeError):
 
 class Shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hq", "Hkv", "S", "D", "dtype", "reduce_groups",
-                                                 "obs_window")]
+                                                 "obs_window")] + [("softmax_scale", ctypes.c_float)]
 
 
 class SelectArgs(ctypes.Structure):
@@ -122,25 +122,27 @@ def _check(status: int, what: str):
         raise KVCrushError(status, what)
 
 
-def make_shape(q: torch.Tensor, k: torch.Tensor, reduce_groups: bool, window: int = 0) -> Shape:
+def make_shape(q: torch.Tensor, k: torch.Tensor, reduce_groups: bool, window: int = 0, scale: float = 0.0) -> Shape:
     B, Hq, S, D = q.shape
-    return Shape(B, Hq, k.shape[1], S, D, _dtype_code(q), int(bool(reduce_groups)), int(window))
+    return Shape(B, Hq, k.shape[1], S, D, _dtype_code(q), int(bool(reduce_groups)), int(window), float(scale))
 
 
 def kvcrush_scores_workspace(shape: Shape) -> int:
     return int(load().kvcrush_scores_workspace(ctypes.byref(shape)))
 
 
-def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=None, stream=None, window=0):
+def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=None, stream=None, window=0,
+                   scale=0.0):
     """q [B,Hq,S,D], k [B,Hkv,S,D] on the GPU -> scores [B,Hs,S] fp32.
     window = W > 0 restricts the contributing queries to the last min(W, S).
+    scale: factor on Q.K before the softmax (0: 1/sqrt(D)).
     Returns (scores, workspace); the workspace's first B*Hq*S floats hold the
     row log-sum-exps when `lse` was not supplied."""
     q, k = _dev(q, "q"), _dev(k, "k")
     if q.dtype != k.dtype or q.dim() != 4 or k.dim() != 4 or q.shape[0] != k.shape[0] \
             or q.shape[2:] != k.shape[2:]:
         raise ValueError("q and k must be [B,H,S,D] tensors of one dtype with matching B, S, D")
-    shape = make_shape(q, k, reduce_groups, window)
+    shape = make_shape(q, k, reduce_groups, window, scale)
     Hs = shape.Hkv if reduce_groups else shape.Hq
     if scores is None:
         scores = torch.empty(shape.B, Hs, shape.S, dtype=torch.float32, device=q.device)
@@ -161,13 +163,13 @@ def kvcrush_row_lse_workspace(shape: Shape) -> int:
     return int(load().kvcrush_row_lse_workspace(ctypes.byref(shape)))
 
 
-def kvcrush_row_lse(q, k, lse_out=None, stream=None, window=0, workspace="auto"):
+def kvcrush_row_lse(q, k, lse_out=None, stream=None, window=0, workspace="auto", scale=0.0):
     """q [B,Hq,S,D], k [B,Hkv,S,D] on the GPU -> natural-log row normalisers fp32 [B,Hq,S]
     (with window = W > 0 only the rows of the last min(W, S) queries are defined).
     workspace: a uint8 tensor, None (run without scratch memory) or "auto" (allocate what
     kvcrush_row_lse_workspace asks for)."""
     q, k = _dev(q, "q"), _dev(k, "k")
-    shape = make_shape(q, k, False, window)
+    shape = make_shape(q, k, False, window, scale)
     if lse_out is None:
         lse_out = torch.empty(shape.B, shape.Hq, shape.S, dtype=torch.float32, device=q.device)
     if isinstance(workspace, str):
@@ -282,7 +284,7 @@ def kvcrush_scores_append_workspace(shape: Shape, capacity: int) -> int:
 
 
 def kvcrush_scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: bool, workspace=None, stream=None,
-                          lengths=None, block_table=None, block_size=16):
+                          lengths=None, block_table=None, block_size=16, scale=0.0):
     """One decoding step, in place on scores_cache [B,Hs,capacity] fp32: the new token's queries
     q_new [B,Hq,D] attend to the first S tokens of k_cache [B,Hkv,capacity,D] (the new key included).
     lengths: optional int32 [B] on the GPU with each sequence's own valid length (S is then their bound).
@@ -304,7 +306,7 @@ def kvcrush_scores_append(q_new, k_cache, scores_cache, S: int, reduce_groups: b
             raise ValueError("paged k_cache must be [n_blocks,block_size,Hkv,D] with block_table int32 [B,n]")
     if tuple(scores_cache.shape) != (B, Hkv if reduce_groups else Hq, cap):
         raise ValueError("scores_cache must be [B,Hs,capacity]")
-    shape = Shape(B, Hq, Hkv, int(S), D, _dtype_code(q_new), int(bool(reduce_groups)), 0)
+    shape = Shape(B, Hq, Hkv, int(S), D, _dtype_code(q_new), int(bool(reduce_groups)), 0, float(scale))
     if workspace is None:
         workspace = torch.empty(max(kvcrush_scores_append_workspace(shape, cap), 16), dtype=torch.uint8,
                                 device=q_new.device)

@@ -48,7 +48,7 @@ struct AppendParams {
   int block_size;
   int B, Hq, Hkv, S, capacity, G, reduce_groups;  // S: valid tokens, or their upper bound with lengths
   int logit_keys, n_kb;  // keys per workgroup of the logits kernel, and how many such blocks S has
-  float scale_log2;    // log2(e) / sqrt(D)
+  float scale_log2;    // log2(e) x softmax scale (1 / sqrt(D) unless the caller set one)
 };
 
 // First byte of key row `key` of sequence b, KV head g (bg = b * Hkv + g).
@@ -336,6 +336,7 @@ bool append_shape_ok(const kvcrush_shape* s, int capacity) {
   if (s->dtype != KVCRUSH_F32 && s->dtype != KVCRUSH_BF16) return false;
   if (s->reduce_groups != 0 && s->reduce_groups != 1) return false;
   if (s->obs_window != 0) return false;
+  if (!(s->softmax_scale >= 0.0f) || s->softmax_scale > 1.0e6f) return false;  // also rejects NaN
   return true;
 }
 
@@ -393,7 +394,8 @@ extern "C" kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int3
   p.reduce_groups = shape->reduce_groups;
   p.logit_keys = logit_keys(shape);
   p.n_kb = key_blocks(shape);
-  p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)shape->D));
+  p.scale_log2 = (float)(1.4426950408889634 *
+                         (shape->softmax_scale != 0.0f ? (double)shape->softmax_scale : 1.0 / sqrt((double)shape->D)));
   hipStream_t stream = (hipStream_t)hip_stream;
   const bool bf16 = shape->dtype == KVCRUSH_BF16;
   if (bf16 && shape->D == 128) return launch_append<true, 128>(p, stream);

@@ -64,7 +64,7 @@ struct ScoreParams {
   float2* split_ml;  // pass A, n_split > 1: [B*Hq, n_split, split_rows] (reference, sum) pairs
   int q_first;       // first query row that contributes (0 unless an observation window is set)
   int tile0;         // pass B: q_first / kTile, the first query tile that is streamed
-  float scale_log2;  // log2(e) / sqrt(D)
+  float scale_log2;  // log2(e) x softmax scale (1 / sqrt(D) unless the caller set one)
 };
 
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2]) {
@@ -764,6 +764,7 @@ bool shape_ok(const kvcrush_shape* s) {
   if (s->dtype != KVCRUSH_F32 && s->dtype != KVCRUSH_BF16) return false;
   if (s->reduce_groups != 0 && s->reduce_groups != 1) return false;
   if (s->obs_window < 0) return false;
+  if (!(s->softmax_scale >= 0.0f) || s->softmax_scale > 1.0e6f) return false;  // also rejects NaN
   return true;
 }
 
@@ -795,7 +796,8 @@ kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const voi
   p.split_ml = nullptr;
   p.q_first = first_query(shape);
   p.tile0 = 0;
-  p.scale_log2 = (float)(1.4426950408889634 / sqrt((double)shape->D));
+  p.scale_log2 = (float)(1.4426950408889634 *
+                         (shape->softmax_scale != 0.0f ? (double)shape->softmax_scale : 1.0 / sqrt((double)shape->D)));
   const bool bf16 = shape->dtype == KVCRUSH_BF16;
   if (bf16 && shape->D == 128) return launch_scores<true, 128>(p, lse, split_ml, lse_only, stream);
   if (bf16 && shape->D == 64) return launch_scores<true, 64>(p, lse, split_ml, lse_only, stream);

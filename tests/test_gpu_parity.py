@@ -426,6 +426,30 @@ def test_window_pool_topk_pipeline(kv, oracle):
     assert torch.equal(vo.cpu().view(torch.uint8), rv.view(torch.uint8))
 
 
+@pytest.mark.parametrize("Dtrue,Dpad,S,W", [(96, 128, 1100, 0), (96, 128, 700, 64), (40, 64, 500, 0)])
+def test_scores_padded_heads_with_their_own_scale(kv, oracle, Dtrue, Dpad, S, W):
+    """Heads of 96 values (Phi-3-mini among the paper's models) or 40: zero-padded to the next
+    supported size and scored with 1/sqrt(true size); the oracle works on the unpadded heads."""
+    say(f"scores with D={Dtrue} padded to {Dpad}, softmax_scale=1/sqrt({Dtrue}), S={S} window={W}")
+    g = torch.Generator().manual_seed(Dtrue + S)
+    q = torch.randn(2, 4, S, Dtrue, generator=g).to(torch.bfloat16)
+    k = torch.randn(2, 2, S, Dtrue, generator=g).to(torch.bfloat16)
+    pad = lambda t: torch.cat([t, torch.zeros(*t.shape[:-1], Dpad - Dtrue, dtype=t.dtype)], dim=-1).contiguous()
+    scale = 1.0 / (Dtrue ** 0.5)
+    sc, _ = kv.kvcrush_scores(pad(q).cuda(), pad(k).cuda(), True, window=W, scale=scale)
+    torch.cuda.synchronize()
+    ref = oracle.scores(q, k, True, threads=THREADS, window=W)
+    got, want = sc.cpu().double(), ref.double()
+    big = want > 1e-30
+    assert ((got[big] - want[big]).abs() / want[big]).max().item() <= SCORE_RTOL
+    # the decoding step takes the same scale
+    old = torch.rand(2, 2, S, generator=g)
+    app = kv.kvcrush_scores_append(pad(q)[:, :, -1].contiguous().cuda(), pad(k).cuda(), old.clone().cuda(), S, True,
+                                   scale=scale)
+    torch.cuda.synchronize()
+    assert rel_err(app, oracle.scores_append(q[:, :, -1].contiguous(), k, old.clone(), S, True)) <= SCORE_RTOL
+
+
 def test_scores_deterministic(kv):
     w = inputs.Workload("t", 1, 8, 2, 1500, 128, "bf16", 256, 0.5, "alternating", True)
     q, k, _ = inputs.make_qkv(w, 1, want_v=False)

@@ -174,7 +174,7 @@ def test_select_protected_ends_validation(lib):
 
 def make_shape(base, overrides):
     d = dict(base, **overrides)
-    return binding.Shape(*[d[f] for f, _ in binding.Shape._fields_])
+    return binding.Shape(*[d.get(f, 0) for f, _ in binding.Shape._fields_])
 
 
 def test_window_pool_and_row_lse_validation(lib):
@@ -182,6 +182,9 @@ def test_window_pool_and_row_lse_validation(lib):
     # a window shrinks the partial-sum part of the workspace, never grows the total past the full one
     assert 0 < binding.kvcrush_scores_workspace(sh(obs_window=64)) <= binding.kvcrush_scores_workspace(sh()) + (1 << 20)
     assert binding.kvcrush_scores_workspace(sh(obs_window=-1)) == 0
+    assert binding.kvcrush_scores_workspace(sh(softmax_scale=-0.5)) == 0
+    assert binding.kvcrush_scores_workspace(sh(softmax_scale=float("nan"))) == 0
+    assert binding.kvcrush_scores_workspace(sh(softmax_scale=0.102)) == binding.kvcrush_scores_workspace(sh())
     # few heads: the normaliser pass wants scratch memory for key slices
     assert binding.kvcrush_row_lse_workspace(sh(obs_window=64)) > 0
     assert binding.kvcrush_row_lse_workspace(sh(B=8, Hq=32, Hkv=8, S=16384)) == 0      # enough workgroups already

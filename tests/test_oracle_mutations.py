@@ -17,8 +17,8 @@ MUTATIONS = [
     ("no causal mask", "for (int j = 0; j <= i; ++j) c[j] += p[j] / L;",
      "for (int j = 0; j < S; ++j) c[j] += (j <= i ? p[j] : p[i]) / L;",
      "tests/test_oracle_scores.py::test_brute_force_full_matrix"),
-    ("no 1/sqrt(D)", "const double inv_sqrt_d = 1.0 / std::sqrt((double)D);\n  for (int i = row_begin",
-     "const double inv_sqrt_d = 1.0;\n  for (int i = row_begin",
+    ("no 1/sqrt(D)", "const double inv_sqrt_d = scale != 0.0 ? scale : 1.0 / std::sqrt((double)D);\n  for (int i = row_begin",
+     "const double inv_sqrt_d = scale != 0.0 ? scale : 1.0;\n  for (int i = row_begin",
      "tests/test_oracle_scores.py::test_against_library_softmax"),
     ("row sums instead of column sums", "c[j] += p[j] / L;", "c[i] += p[j] / L;",
      "tests/test_oracle_scores.py::test_uniform_attention_closed_form"),

@@ -193,3 +193,22 @@ def test_maxpool_matches_library(oracle):
         assert torch.equal(oracle.maxpool(x, kernel), want)
     # hand-worked: kernel 3 on 1 5 2 0 4 -> 5 5 5 4 4
     assert oracle.maxpool(torch.tensor([[1.0, 5.0, 2.0, 0.0, 4.0]]), 3).tolist() == [[5.0, 5.0, 5.0, 4.0, 4.0]]
+
+
+def test_explicit_scale_and_zero_padding(oracle):
+    """A caller-supplied scale replaces 1/sqrt(D): heads of 24 values zero-padded to 32 and scored with
+    1/sqrt(24) give what the unpadded heads give, and the default is 1/sqrt(D)."""
+    g = torch.Generator().manual_seed(31)
+    S, D, Dp = 50, 24, 32
+    q = torch.randn(1, 2, S, D, generator=g)
+    k = torch.randn(1, 1, S, D, generator=g)
+    pad = lambda t: torch.cat([t, torch.zeros(*t.shape[:-1], Dp - D)], dim=-1).contiguous()
+    plain = oracle.scores(q, k, False)
+    assert torch.equal(oracle.scores(q, k, False, scale=1.0 / math.sqrt(D)), plain)
+    assert torch.allclose(oracle.scores(pad(q), pad(k), False, scale=1.0 / math.sqrt(D)).double(), plain.double(),
+                          rtol=1e-6)
+    assert not torch.allclose(oracle.scores(pad(q), pad(k), False), plain, rtol=1e-3)   # 1/sqrt(32) is another method
+    # a library softmax with the same scale
+    logits = (q.double() @ k.double().repeat_interleave(2, 1).transpose(-1, -2)) * 0.3
+    logits = logits.masked_fill(~torch.ones(S, S, dtype=torch.bool).tril(), float("-inf"))
+    assert torch.allclose(oracle.scores(q, k, False, scale=0.3).double(), torch.softmax(logits, -1).sum(-2), rtol=3e-7)
