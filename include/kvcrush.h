@@ -49,7 +49,7 @@ typedef enum {
   KVCRUSH_ERR_HIP = 4          /* the HIP runtime refused a launch or a query    */
 } kvcrush_status;
 
-typedef enum { KVCRUSH_F32 = 0, KVCRUSH_BF16 = 1 } kvcrush_dtype;
+typedef enum { KVCRUSH_F32 = 0, KVCRUSH_BF16 = 1, KVCRUSH_F16 = 2 /* IEEE half */ } kvcrush_dtype;
 
 /* Anchor vector of Alg. 2: the three strategies it names, plus a caller-supplied one. */
 typedef enum {
@@ -100,7 +100,7 @@ typedef struct {
  *   scores  [B, Hs, S] fp32, fully overwritten
  *   workspace  kvcrush_scores_workspace(shape) bytes, always required: the
  *           row log-sum-exps first, then partial column sums of long sequences
- * Accuracy: bf16 (or fp32) products, fp32 accumulation; each score is within
+ * Accuracy: exact bf16 / fp16 (or fp32) products, fp32 accumulation; each score is within
  * 2e-3 relative of the exact value.
  */
 size_t kvcrush_scores_workspace(const kvcrush_shape* shape);

@@ -22,7 +22,7 @@ _LIB = os.path.join(_DIR, "libkvcrush_oracle.so")
 _LIB_OVERRIDE = os.environ.get("KVCRUSH_ORACLE_LIB_FOR_MUTATION_TEST")
 CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC"]
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 ANCHOR_RANDOM, ANCHOR_MEAN, ANCHOR_ALTERNATING, ANCHOR_EXPLICIT = 0, 1, 2, 3
 ANCHORS = {"random": 0, "mean": 1, "alternating": 2, "explicit": 3}
 
@@ -69,7 +69,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
-    raise TypeError(f"oracle handles float32 and bfloat16, got {t.dtype}")
+    if t.dtype == torch.float16:
+        return F16
+    raise TypeError(f"oracle handles float32, bfloat16 and float16, got {t.dtype}")
 
 
 def _cpu(t: torch.Tensor) -> torch.Tensor:

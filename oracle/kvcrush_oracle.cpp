@@ -60,12 +60,22 @@
 
 namespace {
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
 enum { ANCHOR_RANDOM = 0, ANCHOR_MEAN = 1, ANCHOR_ALTERNATING = 2, ANCHOR_EXPLICIT = 3 };
 
 // bf16 is the upper 16 bits of an IEEE binary32; widening is exact.
 double widen(const void* base, size_t i, int dtype) {
   if (dtype == ORC_F32) return (double)((const float*)base)[i];
+  if (dtype == ORC_F16) {
+    // IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits; exact in double.
+    const uint16_t h = ((const uint16_t*)base)[i];
+    const int e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 0) v = std::ldexp((double)f, -24);                       // zero and subnormals
+    else if (e == 31) v = f ? NAN : INFINITY;
+    else v = std::ldexp((double)(1024 + f), e - 25);
+    return (h & 0x8000) ? -v : v;
+  }
   uint32_t u = (uint32_t)((const uint16_t*)base)[i] << 16;
   float f;
   std::memcpy(&f, &u, 4);

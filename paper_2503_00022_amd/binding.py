@@ -14,7 +14,7 @@ import torch
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libkvcrush.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 ANCHORS = {"random": 0, "mean": 1, "alternating": 2, "explicit": 3}
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 
@@ -97,7 +97,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
-    raise TypeError(f"kvcrush handles float32 and bfloat16, got {t.dtype}")
+    if t.dtype == torch.float16:
+        return F16
+    raise TypeError(f"kvcrush handles float32, bfloat16 and float16, got {t.dtype}")
 
 
 def _dev(t: torch.Tensor, name: str) -> torch.Tensor:

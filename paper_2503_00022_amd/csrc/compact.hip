@@ -106,7 +106,7 @@ extern "C" kvcrush_status kvcrush_compact(int32_t B, int32_t Hkv, int32_t S, int
                                           int32_t block_size, void* k_out, void* v_out,
                                           void* hip_stream) {
   if (B < 1 || Hkv < 1 || S < 1 || D < 1 || budget < 0 || budget > S) return KVCRUSH_ERR_INVALID_ARG;
-  if (dtype != KVCRUSH_F32 && dtype != KVCRUSH_BF16) return KVCRUSH_ERR_INVALID_ARG;
+  if (dtype != KVCRUSH_F32 && dtype != KVCRUSH_BF16 && dtype != KVCRUSH_F16) return KVCRUSH_ERR_INVALID_ARG;
   const size_t row_bytes = (size_t)D * (dtype == KVCRUSH_F32 ? 4 : 2);
   if (row_bytes % 16 != 0) return KVCRUSH_ERR_UNSUPPORTED;
   if (block_table && (block_size < 1 || S % block_size != 0)) return KVCRUSH_ERR_INVALID_ARG;
@@ -172,7 +172,7 @@ extern "C" kvcrush_status kvcrush_compact_cache(int32_t B, int32_t Hkv, int32_t 
   if (B < 1 || Hkv < 1 || Hs < 1 || D < 1 || cap_src < 1 || cap_dst < 1 || budget < 0 ||
       budget > cap_src || budget > cap_dst)
     return KVCRUSH_ERR_INVALID_ARG;
-  if (dtype != KVCRUSH_F32 && dtype != KVCRUSH_BF16) return KVCRUSH_ERR_INVALID_ARG;
+  if (dtype != KVCRUSH_F32 && dtype != KVCRUSH_BF16 && dtype != KVCRUSH_F16) return KVCRUSH_ERR_INVALID_ARG;
   const size_t row_bytes = (size_t)D * (dtype == KVCRUSH_F32 ? 4 : 2);
   if (row_bytes % 16 != 0) return KVCRUSH_ERR_UNSUPPORTED;
   if (budget == 0) return KVCRUSH_OK;

@@ -171,7 +171,7 @@ __global__ __launch_bounds__(kThreads) void append_logits_kernel(AppendParams p)
 // bf16: logits of 256 keys x up to 32 heads per pass on the matrix cores.
 // TPW: 64-row tiles per workgroup (4: one tile per wave; 2: two waves share a tile, one 32-row half
 // each, which halves the LDS per workgroup so that more of them overlap their loads on a CU).
-template <int D, int TPW>
+template <int D, int TPW, bool F16>
 __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendParams p) {
   using C = Cfg<true, D>;
   constexpr int kSubs = 2 * TPW / kWaves;  // 32-row halves a wave multiplies: 2 or 1
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
       for (int r = 0; r < 16; ++r) acc[sub][r] = 0.0f;
 #pragma unroll
       for (int s = 0; s < C::kSteps; ++s)
-        mma_step<true>(acc[sub], lds_frag<C>(lds[my_tile], off0, sub0 + sub, s), qf[s]);
+        mma_step<true, F16>(acc[sub], lds_frag<C>(lds[my_tile], off0, sub0 + sub, s), qf[s]);
     }
     // this lane: 16 * kSubs keys of head n.  Keys past the end (and whole unread tiles) are masked here.
     float m = kNegBig;
@@ -321,7 +321,7 @@ size_t logits_bytes(const kvcrush_shape* s) {
 // Keys per workgroup of the logits kernel.  (Two tiles per workgroup on the matrix-core path, 128 keys,
 // measured no faster than four: the kernel is not short of loads in flight.)
 constexpr int kMfmaTilesPerWg = 4;
-int logit_keys(const kvcrush_shape* s) { return s->dtype == KVCRUSH_BF16 ? 64 * kMfmaTilesPerWg : kKeysPerWg; }
+int logit_keys(const kvcrush_shape* s) { return s->dtype != KVCRUSH_F32 ? 64 * kMfmaTilesPerWg : kKeysPerWg; }
 
 int key_blocks(const kvcrush_shape* s) { return (s->S + logit_keys(s) - 1) / logit_keys(s); }
 
@@ -333,17 +333,18 @@ bool append_shape_ok(const kvcrush_shape* s, int capacity) {
   if (!s) return false;
   if (s->B < 1 || s->Hq < 1 || s->Hkv < 1 || s->S < 1 || s->D < 1 || capacity < s->S) return false;
   if (s->Hq % s->Hkv != 0) return false;
-  if (s->dtype != KVCRUSH_F32 && s->dtype != KVCRUSH_BF16) return false;
+  if (s->dtype != KVCRUSH_F32 && s->dtype != KVCRUSH_BF16 && s->dtype != KVCRUSH_F16) return false;
   if (s->reduce_groups != 0 && s->reduce_groups != 1) return false;
   if (s->obs_window != 0) return false;
   if (!(s->softmax_scale >= 0.0f) || s->softmax_scale > 1.0e6f) return false;  // also rejects NaN
   return true;
 }
 
-template <bool BF16, int D>
+template <bool BF16, int D, bool F16 = false>
 kvcrush_status launch_append(const AppendParams& p, hipStream_t stream) {
   if constexpr (BF16) {
-    hipLaunchKernelGGL((append_logits_mfma_kernel<D, kMfmaTilesPerWg>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((append_logits_mfma_kernel<D, kMfmaTilesPerWg, F16>), dim3(p.n_kb, p.B * p.Hkv),
+                       dim3(kThreads), 0, stream, p);
   } else {
     hipLaunchKernelGGL((append_logits_kernel<BF16, D>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
   }
@@ -397,6 +398,8 @@ extern "C" kvcrush_status kvcrush_scores_append(const kvcrush_shape* shape, int3
   p.scale_log2 = (float)(1.4426950408889634 *
                          (shape->softmax_scale != 0.0f ? (double)shape->softmax_scale : 1.0 / sqrt((double)shape->D)));
   hipStream_t stream = (hipStream_t)hip_stream;
+  if (shape->dtype == KVCRUSH_F16)
+    return shape->D == 128 ? launch_append<true, 128, true>(p, stream) : launch_append<true, 64, true>(p, stream);
   const bool bf16 = shape->dtype == KVCRUSH_BF16;
   if (bf16 && shape->D == 128) return launch_append<true, 128>(p, stream);
   if (bf16 && shape->D == 64) return launch_append<true, 64>(p, stream);

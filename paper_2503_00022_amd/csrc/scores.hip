@@ -78,7 +78,7 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[2]) {
 // the fast path).  STREAM_IS_A: the LDS sub-tile supplies the rows (keys) and
 // the two register operands the columns (pass A); otherwise the register
 // operands supply the rows (keys) and the LDS sub-tile the columns (pass B).
-template <class C, bool BF16, bool STREAM_IS_A>
+template <class C, bool BF16, bool STREAM_IS_A, bool F16 = false>
 __device__ __forceinline__ void mma_pair(f32x16 (&acc)[2], const char* buf, int off0, int sub,
                                          const u32x4 (&r0)[C::kSteps], const u32x4 (&r1)[C::kSteps]) {
   zero_acc(acc);
@@ -86,11 +86,11 @@ __device__ __forceinline__ void mma_pair(f32x16 (&acc)[2], const char* buf, int 
   for (int s = 0; s < C::kSteps; ++s) {
     const u32x4 f = lds_frag<C>(buf, off0, sub, s);
     if constexpr (STREAM_IS_A) {
-      mma_step<BF16>(acc[0], f, r0[s]);
-      mma_step<BF16>(acc[1], f, r1[s]);
+      mma_step<BF16, F16>(acc[0], f, r0[s]);
+      mma_step<BF16, F16>(acc[1], f, r1[s]);
     } else {
-      mma_step<BF16>(acc[0], r0[s], f);
-      mma_step<BF16>(acc[1], r1[s], f);
+      mma_step<BF16, F16>(acc[0], r0[s], f);
+      mma_step<BF16, F16>(acc[1], r1[s], f);
     }
   }
 }
@@ -153,7 +153,7 @@ __device__ __forceinline__ void ring_refill(u32x4 (&fr)[C::kSteps / 2], int s, c
 }
 
 // pass B slice: 32 / kSteps of the 32 elements of acc_old per MFMA pair.
-template <class C, int CUR, int NEXT>
+template <class C, int CUR, int NEXT, bool F16>
 __device__ __forceinline__ void colsum_half(f32x16 (&acc_new)[2], const f32x16 (&acc_old)[2],
                                             f32x16 (&col)[2], u32x4 (&fr)[C::kSteps / 2],
                                             const u32x4 (&kf0)[C::kSteps], const u32x4 (&kf1)[C::kSteps],
@@ -164,8 +164,8 @@ __device__ __forceinline__ void colsum_half(f32x16 (&acc_new)[2], const f32x16 (
   zero_acc(acc_new);
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
-    mma_step<true>(acc_new[0], kf0[s], fr[s % kRing]);
-    mma_step<true>(acc_new[1], kf1[s], fr[s % kRing]);
+    mma_step<true, F16>(acc_new[0], kf0[s], fr[s % kRing]);
+    mma_step<true, F16>(acc_new[1], kf1[s], fr[s % kRing]);
     ring_refill<C, CUR, NEXT>(fr, s, lds_base, fo);
 #pragma unroll
     for (int e = s * kPer; e < (s + 1) * kPer; ++e) {
@@ -186,7 +186,7 @@ __device__ __forceinline__ void colsum_half(f32x16 (&acc_new)[2], const f32x16 (
 // pass A slice: exponentials against the lane's fixed reference m (no running
 // maximum: fp32 has the range for any sum whose terms stay below 2^100 or so;
 // the caller checks the sums and re-bases m in the rare case they do not).
-template <class C, int CUR, int NEXT>
+template <class C, int CUR, int NEXT, bool F16>
 __device__ __forceinline__ void lse_half(f32x16 (&acc_new)[2], const f32x16 (&acc_old)[2],
                                          const float (&m)[2], float (&sum)[2], u32x4 (&fr)[C::kSteps / 2],
                                          const u32x4 (&qf0)[C::kSteps], const u32x4 (&qf1)[C::kSteps],
@@ -197,8 +197,8 @@ __device__ __forceinline__ void lse_half(f32x16 (&acc_new)[2], const f32x16 (&ac
   sum[0] = sum[1] = 0.0f;
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
-    mma_step<true>(acc_new[0], fr[s % kRing], qf0[s]);
-    mma_step<true>(acc_new[1], fr[s % kRing], qf1[s]);
+    mma_step<true, F16>(acc_new[0], fr[s % kRing], qf0[s]);
+    mma_step<true, F16>(acc_new[1], fr[s % kRing], qf1[s]);
     ring_refill<C, CUR, NEXT>(fr, s, lds_base, fo);
 #pragma unroll
     for (int e = s * kPer; e < (s + 1) * kPer; ++e) {
@@ -243,7 +243,7 @@ struct IntC { static constexpr int value = N; };
 // K tiles wholly before the workgroup's first query need no mask and run in the
 // pipelined loop; the few tiles that touch the diagonal go through a plain
 // masked loop afterwards.
-template <bool BF16, int D>
+template <bool BF16, int D, bool F16 = false>
 __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   using C = Cfg<BF16, D>;
   __shared__ __attribute__((aligned(1024))) char lds[3][C::kTileBytes];
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
       for (int s = 0; s < C::kSteps; ++s) fo[s] = off0 ^ (s << 4);
       f32x16 acc0[2], acc1[2];
       u32x4 fr[C::kSteps / 2];
-      mma_pair<C, BF16, true>(acc0, lds[0], off0, 0, qf[0], qf[1]);
+      mma_pair<C, BF16, true, F16>(acc0, lds[0], off0, 0, qf[0], qf[1]);
 #pragma unroll
       for (int s = 0; s < C::kSteps / 2; ++s) fr[s] = lds_frag<C>(lds[0], off0, 1, s);
       // reference for the exponentials: the first block's own maximum
@@ -323,11 +323,11 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
         // block (it, sub 1) goes through the MFMAs while block (it, sub 0) is summed
         mref[0] = live ? m[0] : INFINITY;
         mref[1] = live ? m[1] : INFINITY;
-        lse_half<C, cur * kT + kU, nxt * kT>(acc1, acc0, mref, sum, fr, qf[0], qf[1], lds_base, fo, c);
+        lse_half<C, cur * kT + kU, nxt * kT, F16>(acc1, acc0, mref, sum, fr, qf[0], qf[1], lds_base, fo, c);
         lse_commit(acc0, m, l, sum, c);
         mref[0] = live ? m[0] : INFINITY;
         mref[1] = live ? m[1] : INFINITY;
-        lse_half<C, nxt * kT, nxt * kT + kU>(acc0, acc1, mref, sum, fr, qf[0], qf[1], lds_base, fo, c);
+        lse_half<C, nxt * kT, nxt * kT + kU, F16>(acc0, acc1, mref, sum, fr, qf[0], qf[1], lds_base, fo, c);
         lse_commit(acc1, m, l, sum, c);
         wait_async_loads();
         __syncthreads();
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
         const int kmin = kt + 32 * ks, kmax = kmin + 31;
         if (kmin > q0 + 63) continue;  // every key of this sub-tile comes after all 64 rows
         f32x16 acc[2];
-        mma_pair<C, BF16, true>(acc, buf, off0, ks, qf[0], qf[1]);
+        mma_pair<C, BF16, true, F16>(acc, buf, off0, ks, qf[0], qf[1]);
 #pragma unroll
         for (int ns = 0; ns < 2; ++ns) {
           const int qmin = q0 + 32 * ns;
@@ -418,7 +418,7 @@ __global__ __launch_bounds__(256) void lse_combine_kernel(ScoreParams p) {
 // block needs more than one piece, each writes partial sums and
 // colsum_reduce_kernel adds them in a fixed order (no floating-point atomics:
 // the result does not depend on scheduling).
-template <bool BF16, int D>
+template <bool BF16, int D, bool F16 = false>
 __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, const float* lse_in) {
   using C = Cfg<BF16, D>;
   __shared__ __attribute__((aligned(1024))) char lds[3][C::kTileBytes];
@@ -511,7 +511,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       for (int s = 0; s < C::kSteps; ++s) fo[s] = off0 ^ (s << 4);
       f32x16 acc0[2], acc1[2];
       u32x4 fr[C::kSteps / 2];
-      mma_pair<C, BF16, false>(acc0, lds[0], off0, 0, kf[0], kf[1]);
+      mma_pair<C, BF16, false, F16>(acc0, lds[0], off0, 0, kf[0], kf[1]);
 #pragma unroll
       for (int s = 0; s < C::kSteps / 2; ++s) fr[s] = lds_frag<C>(lds[0], off0, 1, s);
       // The trip count is rounded up to a multiple of three; the padding
@@ -526,8 +526,8 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
         const float st_lse = it + 2 < n_fast ? ld_lse : INFINITY;
         const float lse_a = lds_lse[cur][lane & 31], lse_b = lds_lse[cur][32 + (lane & 31)];
         __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);  // the two lse reads lead the block
-        colsum_half<C, cur * kT + kU, nxt * kT>(acc1, acc0, col, fr, kf[0], kf[1], lds_base, fo, c, lse_a);
-        colsum_half<C, nxt * kT, nxt * kT + kU>(acc0, acc1, col, fr, kf[0], kf[1], lds_base, fo, c, lse_b);
+        colsum_half<C, cur * kT + kU, nxt * kT, F16>(acc1, acc0, col, fr, kf[0], kf[1], lds_base, fo, c, lse_a);
+        colsum_half<C, nxt * kT, nxt * kT + kU, F16>(acc0, acc1, col, fr, kf[0], kf[1], lds_base, fo, c, lse_b);
         lds_lse[ld][tid] = st_lse;  // unconditional: keeps the block free of exec changes
         wait_async_loads();
         __syncthreads();
@@ -569,7 +569,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
         if (qmax < k0) continue;  // all 64 keys of this wave come after these queries
         const float lse2 = lds_lse[it & 1][32 * ns + (lane & 31)];
         f32x16 acc[2];
-        mma_pair<C, BF16, false>(acc, buf, off0, ns, kf[0], kf[1]);
+        mma_pair<C, BF16, false, F16>(acc, buf, off0, ns, kf[0], kf[1]);
 #pragma unroll
         for (int ms = 0; ms < 2; ++ms) {
           const int kmin = k0 + 32 * ms;
@@ -687,7 +687,7 @@ size_t split_bytes(const LsePlan& pl, int B, int Hq) {
   return kvc::align_up((size_t)B * Hq * pl.n_split * pl.split_rows * sizeof(float2), 256);
 }
 
-template <bool BF16, int D>
+template <bool BF16, int D, bool F16 = false>
 kvcrush_status launch_lse(const ScoreParams& base, float2* split_ml, hipStream_t stream) {
   ScoreParams a = base;
   const LsePlan pl = lse_plan(a.B, a.Hq, a.Hkv, a.S, BF16, a.q_first, split_ml != nullptr);
@@ -698,7 +698,7 @@ kvcrush_status launch_lse(const ScoreParams& base, float2* split_ml, hipStream_t
   a.split_q0 = pl.split_q0;
   a.split_rows = pl.split_rows;
   a.split_ml = split_ml;
-  hipLaunchKernelGGL((lse_kernel<BF16, D>), dim3((unsigned)(pl.launched * pl.n_split * pl.n_bh)),
+  hipLaunchKernelGGL((lse_kernel<BF16, D, F16>), dim3((unsigned)(pl.launched * pl.n_split * pl.n_bh)),
                      dim3(kThreads), 0, stream, a);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   if (pl.n_split > 1) {
@@ -708,13 +708,13 @@ kvcrush_status launch_lse(const ScoreParams& base, float2* split_ml, hipStream_t
   return KVCRUSH_OK;
 }
 
-template <bool BF16, int D>
+template <bool BF16, int D, bool F16 = false>
 kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, float2* split_ml,
                              bool lse_only, hipStream_t stream) {
   using C = Cfg<BF16, D>;
   ScoreParams p = base;
   if (!lse_user) {
-    if (launch_lse<BF16, D>(p, split_ml, stream) != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+    if (launch_lse<BF16, D, F16>(p, split_ml, stream) != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
   if (lse_only) return KVCRUSH_OK;
   const ColsumPlan pl = colsum_plan(p.S, C::kTile, kChunkQueries / C::kTile, p.q_first);
@@ -723,7 +723,7 @@ kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, flo
   p.n_chunks = pl.n_chunks;
   p.chunk_tiles = pl.chunk_tiles;
   p.n_bh = p.B * (p.reduce_groups ? p.Hkv : p.Hq);
-  hipLaunchKernelGGL((colsum_kernel<BF16, D>), dim3((unsigned)(pl.pieces * p.n_bh)), dim3(kThreads), 0,
+  hipLaunchKernelGGL((colsum_kernel<BF16, D, F16>), dim3((unsigned)(pl.pieces * p.n_bh)), dim3(kThreads), 0,
                      stream, p, lse_user ? lse_user : p.lse);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   if (pl.n_chunks > 1) {
@@ -745,7 +745,7 @@ size_t lse_bytes(const kvcrush_shape* s) {
 }
 
 size_t partial_bytes(const kvcrush_shape* s) {
-  const int tile = s->dtype == KVCRUSH_BF16 ? 64 : 32;
+  const int tile = s->dtype != KVCRUSH_F32 ? 64 : 32;
   const ColsumPlan pl = colsum_plan(s->S, tile, kChunkQueries / tile, first_query(s));
   if (pl.n_chunks <= 1) return 0;
   const size_t rows = (size_t)s->B * (s->reduce_groups ? s->Hkv : s->Hq);
@@ -753,7 +753,7 @@ size_t partial_bytes(const kvcrush_shape* s) {
 }
 
 size_t split_bytes(const kvcrush_shape* s) {
-  return split_bytes(lse_plan(s->B, s->Hq, s->Hkv, s->S, s->dtype == KVCRUSH_BF16, first_query(s), true),
+  return split_bytes(lse_plan(s->B, s->Hq, s->Hkv, s->S, s->dtype != KVCRUSH_F32, first_query(s), true),
                      s->B, s->Hq);
 }
 
@@ -761,7 +761,7 @@ bool shape_ok(const kvcrush_shape* s) {
   if (!s) return false;
   if (s->B < 1 || s->Hq < 1 || s->Hkv < 1 || s->S < 1 || s->D < 1) return false;
   if (s->Hq % s->Hkv != 0) return false;
-  if (s->dtype != KVCRUSH_F32 && s->dtype != KVCRUSH_BF16) return false;
+  if (s->dtype != KVCRUSH_F32 && s->dtype != KVCRUSH_BF16 && s->dtype != KVCRUSH_F16) return false;
   if (s->reduce_groups != 0 && s->reduce_groups != 1) return false;
   if (s->obs_window < 0) return false;
   if (!(s->softmax_scale >= 0.0f) || s->softmax_scale > 1.0e6f) return false;  // also rejects NaN
@@ -798,6 +798,10 @@ kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const voi
   p.tile0 = 0;
   p.scale_log2 = (float)(1.4426950408889634 *
                          (shape->softmax_scale != 0.0f ? (double)shape->softmax_scale : 1.0 / sqrt((double)shape->D)));
+  if (shape->dtype == KVCRUSH_F16) {
+    if (shape->D == 128) return launch_scores<true, 128, true>(p, lse, split_ml, lse_only, stream);
+    return launch_scores<true, 64, true>(p, lse, split_ml, lse_only, stream);
+  }
   const bool bf16 = shape->dtype == KVCRUSH_BF16;
   if (bf16 && shape->D == 128) return launch_scores<true, 128>(p, lse, split_ml, lse_only, stream);
   if (bf16 && shape->D == 64) return launch_scores<true, 64>(p, lse, split_ml, lse_only, stream);

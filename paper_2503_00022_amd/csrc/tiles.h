@@ -16,6 +16,7 @@ namespace tiles {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
@@ -39,9 +40,14 @@ struct Cfg {
 };
 
 // One MFMA "load step": C += A_frag . B_frag^T over this step's k-slice.
-template <bool BF16>
+// BF16: the operands are 16-bit values (eight per fragment); F16 then says they are IEEE half
+// rather than bfloat16 (same layouts and tiling, another matrix instruction).
+template <bool BF16, bool F16 = false>
 __device__ __forceinline__ void mma_step(f32x16& acc, const u32x4& a, const u32x4& b) {
-  if constexpr (BF16) {
+  if constexpr (BF16 && F16) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                 __builtin_bit_cast(f16x8, b), acc, 0, 0, 0);
+  } else if constexpr (BF16) {
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
                                                   __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
   } else {

@@ -26,7 +26,7 @@ class Workload:
     Hkv: int
     S: int
     D: int
-    dtype: str            # "bf16" | "f32"
+    dtype: str            # "bf16" | "f16" | "f32"
     budget: int
     rep_fraction: float   # share of the budget given to the representatives
     anchor: str           # "random" | "mean" | "alternating"
@@ -50,7 +50,7 @@ class Workload:
 
     @property
     def torch_dtype(self):
-        return torch.bfloat16 if self.dtype == "bf16" else torch.float32
+        return {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[self.dtype]
 
     def scaled(self, **kw) -> "Workload":
         return replace(self, **kw)

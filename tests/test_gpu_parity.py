@@ -35,7 +35,7 @@ def say(msg):
 # ------------------------------------------------------------------ stage 5
 @pytest.mark.parametrize("B,Hkv,S,D,dtype,budget", [
     (2, 4, 96, 64, "bf16", 24), (1, 8, 1000, 128, "bf16", 333), (3, 2, 130, 128, "f32", 130),
-    (1, 1, 17, 64, "f32", 1), (2, 8, 4096, 128, "bf16", 1024), (1, 3, 50, 64, "bf16", 0),
+    (1, 1, 17, 64, "f32", 1), (2, 8, 4096, 128, "bf16", 1024), (1, 3, 50, 64, "bf16", 0), (2, 2, 700, 128, "f16", 99),
 ])
 def test_compact_dense(kv, oracle, B, Hkv, S, D, dtype, budget):
     say(f"compact dense B={B} Hkv={Hkv} S={S} D={D} {dtype} budget={budget}")
@@ -307,6 +307,8 @@ def check_scores(kv, oracle, w, seed, reduce_groups, check_lse=True):
     (1, 4, 2, 2100, 64, "bf16", True),       # several query chunks, D = 64 pipeline
     (1, 2, 2, 1333, 128, "bf16", False),     # several query chunks, ragged tail, one head per row
     (2, 2, 1, 1100, 128, "f32", True),       # fp32 path with partial sums
+    (1, 8, 2, 1400, 128, "f16", True),       # IEEE half inputs: same tiling, the f16 matrix instruction
+    (2, 4, 4, 333, 64, "f16", False),
 ])
 def test_scores_small(kv, oracle, B, Hq, Hkv, S, D, dtype, rg):
     say(f"scores B={B} Hq={Hq} Hkv={Hkv} S={S} D={D} {dtype} reduce_groups={rg}")
@@ -551,10 +553,11 @@ def test_config5_long_paged(kv, oracle):
     (2, 2, 2, 513, 600, 128, "f32", False),
     (1, 6, 3, 100, 128, 64, "f32", True),
     (8, 32, 8, 2049, 2304, 128, "bf16", True),    # a compressed config-4 cache in mid-generation
+    (2, 8, 2, 777, 800, 128, "f16", True),
 ])
 def test_scores_append_matches_oracle(kv, oracle, B, Hq, Hkv, S, cap, D, dtype, rg):
     say(f"append B={B} Hq={Hq} Hkv={Hkv} S={S} capacity={cap} D={D} {dtype} reduce_groups={rg}")
-    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    td = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dtype]
     g = torch.Generator().manual_seed(S + Hq)
     qn = torch.randn(B, Hq, D, generator=g).to(td)
     kc = torch.randn(B, Hkv, cap, D, generator=g).to(td)

@@ -69,6 +69,7 @@ def test_scores_rejects_bad_arguments(lib):
     assert call(shape(S=0)) == binding.ERR_INVALID_ARG
     assert call(shape(Hq=5)) == binding.ERR_INVALID_ARG
     assert call(shape(dtype=7)) == binding.ERR_INVALID_ARG
+    assert call(shape(dtype=3)) == binding.ERR_INVALID_ARG
     assert call(shape(reduce_groups=2)) == binding.ERR_INVALID_ARG
     assert call(shape(D=96)) == binding.ERR_UNSUPPORTED
     assert call(shape(), q=None) == binding.ERR_INVALID_ARG
@@ -107,6 +108,7 @@ def test_compact_rejects_bad_arguments(lib):
     assert call(budget=65) == binding.ERR_INVALID_ARG
     assert call(budget=-1) == binding.ERR_INVALID_ARG
     assert call(dtype=3) == binding.ERR_INVALID_ARG
+    assert call(dtype=2, k=None) == binding.ERR_INVALID_ARG     # fp16 is a known type; the null pointer is not
     assert call(D=4) == binding.ERR_UNSUPPORTED                 # 8-byte rows cannot be moved as 16-byte vectors
     assert call(k=None) == binding.ERR_INVALID_ARG
     assert call(ko=ctypes.c_void_p(0x1008)) == binding.ERR_INVALID_ARG
@@ -121,7 +123,7 @@ def test_score_kernels_keep_their_registers():
     from paper_2503_00022_amd import build
     report = build.resource_usage("scores.hip")
     hot = {name: r for name, r in report.items() if "lse_kernel" in name or "colsum_kernel" in name}
-    assert len(hot) == 8, sorted(report)           # {lse, colsum} x {bf16, fp32} x {D = 64, 128}
+    assert len(hot) == 12, sorted(report)          # {lse, colsum} x {bf16, fp16, fp32} x {D = 64, 128}
     for name, r in hot.items():
         assert r["VGPRs Spill"] == 0 and r["SGPRs Spill"] == 0 and r["ScratchSize"] == 0, (name, r)
         assert r["Occupancy"] >= 2, (name, r)

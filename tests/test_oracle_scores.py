@@ -123,10 +123,10 @@ def library_colsums(q, k, G):
 
 
 @pytest.mark.parametrize("S,Hq,Hkv,D,dtype", [(384, 8, 2, 64, torch.bfloat16), (512, 4, 4, 64, torch.float32),
-                                              (257, 4, 1, 128, torch.bfloat16)])
+                                              (257, 4, 1, 128, torch.bfloat16), (300, 4, 2, 128, torch.float16)])
 def test_against_library_softmax(oracle, S, Hq, Hkv, D, dtype):
-    w = inputs.Workload("t", 1, Hq, Hkv, S, D, "bf16" if dtype == torch.bfloat16 else "f32", 64, 0.5,
-                        "alternating", False, sink_bias=True)
+    w = inputs.Workload("t", 1, Hq, Hkv, S, D, {torch.bfloat16: "bf16", torch.float16: "f16", torch.float32: "f32"}[dtype],
+                        64, 0.5, "alternating", False, sink_bias=True)
     q, k, _ = inputs.make_qkv(w, 11)
     G = Hq // Hkv
     ref, ref_lse, A = library_colsums(q, k, G)
@@ -212,3 +212,19 @@ def test_explicit_scale_and_zero_padding(oracle):
     logits = (q.double() @ k.double().repeat_interleave(2, 1).transpose(-1, -2)) * 0.3
     logits = logits.masked_fill(~torch.ones(S, S, dtype=torch.bool).tril(), float("-inf"))
     assert torch.allclose(oracle.scores(q, k, False, scale=0.3).double(), torch.softmax(logits, -1).sum(-2), rtol=3e-7)
+
+
+def test_half_precision_inputs_are_widened_exactly(oracle):
+    """fp16 inputs, subnormals included (values near 1e-6 have no normal fp16 form): with Q = the unit
+    vector e_0 times 1024 and K[:, 0] = the value under test, the last attention row is the softmax of
+    1024 / sqrt(D) times those values, which the library computes from the same halves widened by torch."""
+    S, D = 64, 16
+    vals = torch.cat([torch.tensor([0.0, -0.0, 6.0e-8, -6.0e-8, 5.9e-5, 6.2e-5, 1.0, -2.5, 65504.0 / 4096]),
+                      torch.randn(S - 9, generator=torch.Generator().manual_seed(6)) * 1e-5]).to(torch.float16)
+    q = torch.zeros(1, 1, S, D, dtype=torch.float16)
+    q[..., 0] = 1024.0
+    k = torch.zeros(1, 1, S, D, dtype=torch.float16)
+    k[0, 0, :, 0] = vals
+    got = oracle.scores(q, k, False, window=1).double()[0, 0]
+    want = torch.softmax(vals.double() * 1024.0 / math.sqrt(D), dim=0)
+    assert torch.allclose(got, want, rtol=3e-7)
