@@ -28,6 +28,13 @@
 // MFMA step is free as long as both operands use the same one: lane group g
 // (lane / 32) takes chunk  step + g * steps  of a row, i.e. one 16-byte load.
 //
+// Launch shapes.  Pass A numbers its query blocks from the end of the sequence,
+// so an observation window (only the last W queries score the tokens, the
+// scoring of the SnapKV baseline, Sec. 2.3) simply launches fewer of them; when
+// that leaves the chip short of workgroups, the unmasked key tiles of a block
+// are cut into slices, one workgroup each, and lse_combine_kernel merges the
+// slices' sums.  Pass B cuts the causal triangle into pieces of equal size.
+//
 // Instruction order.  Away from the diagonal the bf16 kernels run a software
 // pipeline written out by hand: every pair of MFMAs of the current 64x32 block
 // is followed by the ds_read that fetches the same fragment of the NEXT block

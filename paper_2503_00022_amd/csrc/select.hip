@@ -23,6 +23,15 @@
 //                         integer cost, wave arg-min with token tie-break.
 //   K4 emit_kernel        ordered compaction of (important | representative)
 //                         bitmaps into the ascending index list.
+//
+// Variants on the same kernels.  Protected ends (Table 1's cache layout): the
+// kernels are handed the tokens between the ends, K4 writes the ends around
+// them.  Chunk- / page-level selection (Sec. 4.3.4, 4.3.5): K1's importance row
+// ranks units (sums of their tokens' importances), K1b unit_rows_kernel turns the
+// token bitmaps into per-unit rows (a unit's vector = its tokens' head vectors
+// concatenated), K2-K4 then treat units as items; K2 and K3 are templates over
+// the 64-bit words per vector (up to 16 = 1024 bits), with a workgroup-per-bucket
+// K3 for the long vectors, whose buckets are few and large.
 #include <algorithm>
 
 #include "common.h"
