@@ -307,6 +307,11 @@ def check_scores(kv, oracle, w, seed, reduce_groups, check_lse=True):
     (1, 4, 2, 2100, 64, "bf16", True),       # several query chunks, D = 64 pipeline
     (1, 2, 2, 1333, 128, "bf16", False),     # several query chunks, ragged tail, one head per row
     (2, 2, 1, 1100, 128, "f32", True),       # fp32 path with partial sums
+    (1, 2, 1, 64, 128, "bf16", True),        # exactly one tile
+    (1, 2, 1, 256, 128, "bf16", True),       # exactly one key block
+    (1, 2, 1, 1152, 128, "bf16", True),      # exactly one query chunk of pass B
+    (1, 2, 1, 1153, 128, "bf16", True),      # one row more
+    (1, 2, 1, 2304, 64, "bf16", False),      # exactly two chunks, D = 64
     (1, 8, 2, 1400, 128, "f16", True),       # IEEE half inputs: same tiling, the f16 matrix instruction
     (2, 4, 4, 333, 64, "f16", False),
 ])
