@@ -8,7 +8,8 @@
 // (B*Hkv*S*D*sizeof bytes); the exponentials and the fp32 dot products are far
 // below the VALU's rate at that pace.
 //
-//   append_logits_mfma_kernel  (bf16) workgroup = 256 keys of one KV head: four
+//   append_logits_mfma_kernel  (bf16 / fp16) workgroup = 256 keys of one KV head
+//                          (dense cache or paged pool): four
 //                          64-row K tiles go global -> LDS asynchronously, each
 //                          wave multiplies its tile with the query vectors of
 //                          the KV group's heads (the 32 columns of a 32x32x16
