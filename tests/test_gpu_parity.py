@@ -222,6 +222,7 @@ def test_per_layer_budgets_share_one_workspace(kv, oracle):
     (1, 8, 32768, 1024, 768, 0, "alternating", True),
     (1, 4, 40000, 5000, 3000, 0, "random", True),  # rows too long for LDS: keys go through the workspace
     (8, 8, 8192, 2048, 1536, 0, "alternating", False),
+    (200, 4, 150, 40, 20, 0, "random", True),      # many short sequences
     (1, 128, 8192, 1000, 600, 0, "mean", True),    # row bitmaps too large for LDS staging
 ])
 def test_select_matches_oracle(kv, oracle, B, Hs, S, budget, n_imp, kbit, anchor, ties):
@@ -307,6 +308,7 @@ def check_scores(kv, oracle, w, seed, reduce_groups, check_lse=True):
     (1, 4, 2, 2100, 64, "bf16", True),       # several query chunks, D = 64 pipeline
     (1, 2, 2, 1333, 128, "bf16", False),     # several query chunks, ragged tail, one head per row
     (2, 2, 1, 1100, 128, "f32", True),       # fp32 path with partial sums
+    (64, 8, 2, 300, 64, "bf16", True),       # many short sequences
     (1, 2, 1, 64, 128, "bf16", True),        # exactly one tile
     (1, 2, 1, 256, 128, "bf16", True),       # exactly one key block
     (1, 2, 1, 1152, 128, "bf16", True),      # exactly one query chunk of pass B
