@@ -626,7 +626,13 @@ __global__ __launch_bounds__(kKeysPerWg) void colsum_reduce_kernel(ScoreParams p
   const int c_min = max(0, kb * tiles_per_kb - p.tile0) / p.chunk_tiles;
   const float* src = p.partial + ((size_t)bh * p.n_blocks + kb) * p.n_chunks * kKeysPerWg + threadIdx.x;
   float acc = 0.0f;
-  for (int c = c_min; c < p.n_chunks; ++c) acc += src[(size_t)c * kKeysPerWg];
+  int c = c_min;
+  for (; c + 4 <= p.n_chunks; c += 4) {  // four loads in flight, added in chunk order
+    const float x0 = src[(size_t)c * kKeysPerWg], x1 = src[(size_t)(c + 1) * kKeysPerWg];
+    const float x2 = src[(size_t)(c + 2) * kKeysPerWg], x3 = src[(size_t)(c + 3) * kKeysPerWg];
+    acc = (((acc + x0) + x1) + x2) + x3;
+  }
+  for (; c < p.n_chunks; ++c) acc += src[(size_t)c * kKeysPerWg];
   p.scores[(size_t)bh * p.S + t] = acc;
 }
 
