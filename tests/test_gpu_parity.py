@@ -914,3 +914,65 @@ def test_scores_append_on_a_paged_pool(kv, oracle, B, Hq, Hkv, S, cap, D, dtype,
     assert rel_err(got[:, :, :S], want[:, :, :S]) <= SCORE_RTOL
     assert torch.equal(got.cpu()[:, :, S:], old[:, :, S:])
     assert torch.equal(got, dense), "paged and dense caches must give identical bits"
+
+
+# ------------------------------------------------------------------ pipeline classes
+def test_layer_compressor_and_decode_cache(kv, oracle):
+    """The buffer-owning wrappers (marshalling only): a layer compressed eagerly and from a captured
+    graph, then a decoding cache fed token by token; every step replayed by the oracle."""
+    say("LayerCompressor (eager + graph) and DecodeCache against the oracle")
+    from paper_2503_00022_amd import pipeline
+    B, Hq, Hkv, D, S0, steps = 2, 8, 2, 128, 900, 70
+    budget, n_imp, sink, recent, cap = 256, 160, 4, 32, 288
+    w = inputs.Workload("t", B, Hq, Hkv, S0 + steps, D, "bf16", budget, 0.5, "mean", True, sink_bias=True)
+    q, k, v = inputs.make_qkv(w, 23)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    q0, k0, v0 = [t[:, :, :S0].contiguous() for t in (qd, kd, vd)]
+    lc = pipeline.LayerCompressor(B, Hq, Hkv, S0, D, torch.bfloat16, budget, n_imp, anchor="mean", anchor_seed=3,
+                                  n_sink=sink, n_recent=recent)
+    idx, ko, vo = lc.run(q0, k0, v0)
+    torch.cuda.synchronize()
+    sc_h = lc.scores.cpu()
+    ref_sc = oracle.scores(q[:, :, :S0].contiguous(), k[:, :, :S0].contiguous(), True, threads=THREADS)
+    assert rel_err(sc_h, ref_sc) <= SCORE_RTOL
+    ridx, _, _ = oracle.select(sc_h, budget, n_imp, 0, "mean", 3, n_sink=sink, n_recent=recent)
+    assert torch.equal(idx.cpu(), ridx)
+    rk, rv = oracle.compact(k[:, :, :S0].contiguous(), v[:, :, :S0].contiguous(), ridx)
+    assert torch.equal(ko.cpu().view(torch.uint8), rk.view(torch.uint8))
+    eager = [t.clone() for t in (idx, ko, vo)]
+    lc.capture(q0, k0, v0)
+    for t in (lc.idx, lc.k_out, lc.v_out):
+        t.zero_()
+    got = lc.replay()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(got, eager))
+
+    # the compressed cache goes on living: scores of the kept tokens, then one append per new token
+    kept_sc = torch.gather(lc.scores, 2, idx.long()[:, None, :].expand(B, Hkv, budget))
+    dc = pipeline.DecodeCache(ko, vo, kept_sc, budget, n_imp, cap, anchor="mean", anchor_seed=3, n_sink=sink,
+                              n_recent=recent)
+    o_k = torch.zeros(B, Hkv, cap, D, dtype=torch.bfloat16)
+    o_v, o_sc = torch.zeros_like(o_k), torch.zeros(B, Hkv, cap)
+    o_k[:, :, :budget], o_v[:, :, :budget], o_sc[:, :, :budget] = rk, rv, kept_sc.cpu()
+    n = budget
+    for step in range(steps):
+        pos = S0 + step
+        if n == cap:                                  # the wrapper evicts by itself; mirror it on the oracle side
+            ridx, _, _ = oracle.select(dc.scores.cpu()[:, :, :n].contiguous(), budget, n_imp, 0, "mean", 3,
+                                       n_sink=sink, n_recent=recent)
+            new = [torch.zeros_like(t) for t in (o_k, o_v, o_sc)]
+            oracle.compact_cache(o_k, o_v, o_sc, ridx, *new)
+            o_k, o_v, o_sc = new
+            n = budget
+        dc.append(qd[:, :, pos].contiguous(), kd[:, :, pos].contiguous(), vd[:, :, pos].contiguous())
+        if dc.evictions and n == budget and step and dc.n == budget + 1:
+            assert torch.equal(dc._idx.cpu(), ridx), "eviction chose other tokens than the oracle on the same scores"
+        o_k[:, :, n], o_v[:, :, n] = k[:, :, pos], v[:, :, pos]
+        n += 1
+        oracle.scores_append(q[:, :, pos].contiguous(), o_k, o_sc, n, True)
+        assert dc.n == n
+    torch.cuda.synchronize()
+    assert dc.evictions == 2
+    assert torch.equal(dc.k.cpu()[:, :, :n].view(torch.uint8), o_k[:, :, :n].view(torch.uint8))
+    assert torch.equal(dc.v.cpu()[:, :, :n].view(torch.uint8), o_v[:, :, :n].view(torch.uint8))
+    assert rel_err(dc.scores[:, :, :n], o_sc[:, :, :n]) <= SCORE_RTOL

@@ -244,3 +244,19 @@ def test_decode_entry_points_validation(lib):
     mk = binding.make_select_args
     assert binding.kvcrush_select_workspace(mk(1, 8, 100, 50, 10, score_stride=99)) == 0
     assert binding.kvcrush_select_workspace(mk(1, 8, 100, 50, 10, score_stride=128)) > 0
+
+
+def test_pipeline_classes_validate_before_touching_the_gpu(lib):
+    """The buffer-owning wrappers import without a GPU and reject a capacity that cannot hold the cache."""
+    import torch
+    from paper_2503_00022_amd import pipeline
+    k = torch.zeros(1, 2, 8, 64, dtype=torch.bfloat16)
+    sc = torch.zeros(1, 2, 8)
+    with pytest.raises(ValueError):
+        pipeline.DecodeCache(k, k, sc, budget=8, n_important=4, capacity=8)
+    with pytest.raises(ValueError):
+        pipeline.DecodeCache(k, k, sc, budget=4, n_important=2, capacity=6)
+    with pytest.raises(RuntimeError):
+        lc = object.__new__(pipeline.LayerCompressor)      # no buffers: only the guard is exercised
+        lc._graph = None
+        lc.replay()
