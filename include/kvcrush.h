@@ -26,6 +26,11 @@
  *     are complete when the stream reaches the end of the enqueued work.
  *   - Errors are return codes.  Arguments are validated on the host before
  *     anything is launched; on an error nothing has been enqueued.
+ *   - Size limits of the launches (KVCRUSH_ERR_UNSUPPORTED beyond them):
+ *     B * Hq <= 65535 and B * Hq * ceil(S / 64) <= 2^30 in the score calls,
+ *     B <= 65535 in kvcrush_select, B * Hs <= 65535 where scores are gathered.
+ *     Offsets inside the arrays are 64-bit: the arrays themselves may exceed
+ *     4 GiB.
  *   - Inputs are assumed finite.  NaN scores give an unspecified (but memory
  *     safe) selection.  -0.0 and +0.0 compare equal.
  *   - Overlapping calls that share a workspace race; give each concurrent

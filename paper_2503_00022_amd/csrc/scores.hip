@@ -638,8 +638,12 @@ __global__ __launch_bounds__(kKeysPerWg) void colsum_reduce_kernel(ScoreParams p
 
 // Work pieces of pass B for a sequence of n_tiles query tiles.
 struct ColsumPlan {
-  int n_kb, n_chunks, chunk_tiles, pieces;  // pieces per (batch, score row)
+  int n_kb, n_chunks, chunk_tiles;
+  long long pieces;  // per (batch, score row)
 };
+
+constexpr long long kMaxGridX = 0x7FFFFFFFll;  // workgroups of a one-dimensional launch
+constexpr long long kMaxGridY = 65535;
 
 ColsumPlan colsum_plan(int S, int tile, int chunk_tiles_wanted, int q_first) {
   ColsumPlan pl;
@@ -711,6 +715,7 @@ kvcrush_status launch_lse(const ScoreParams& base, float2* split_ml, hipStream_t
   a.split_q0 = pl.split_q0;
   a.split_rows = pl.split_rows;
   a.split_ml = split_ml;
+  if ((long long)pl.launched * pl.n_split * pl.n_bh > kMaxGridX) return KVCRUSH_ERR_UNSUPPORTED;
   hipLaunchKernelGGL((lse_kernel<BF16, D, F16>), dim3((unsigned)(pl.launched * pl.n_split * pl.n_bh)),
                      dim3(kThreads), 0, stream, a);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
@@ -726,11 +731,14 @@ kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, flo
                              bool lse_only, hipStream_t stream) {
   using C = Cfg<BF16, D>;
   ScoreParams p = base;
+  const ColsumPlan pl = colsum_plan(p.S, C::kTile, kChunkQueries / C::kTile, p.q_first);
+  const long long rows = (long long)p.B * (p.reduce_groups ? p.Hkv : p.Hq);
+  if (!lse_only && pl.pieces * rows > kMaxGridX) return KVCRUSH_ERR_UNSUPPORTED;  // before anything is enqueued
   if (!lse_user) {
-    if (launch_lse<BF16, D, F16>(p, split_ml, stream) != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+    const kvcrush_status st = launch_lse<BF16, D, F16>(p, split_ml, stream);
+    if (st != KVCRUSH_OK) return st;
   }
   if (lse_only) return KVCRUSH_OK;
-  const ColsumPlan pl = colsum_plan(p.S, C::kTile, kChunkQueries / C::kTile, p.q_first);
   p.tile0 = p.q_first / C::kTile;
   p.n_blocks = pl.n_kb;
   p.n_chunks = pl.n_chunks;
@@ -786,6 +794,7 @@ kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const voi
                             float* scores, bool lse_only, hipStream_t stream) {
   const long long blocks_a = (long long)shape->B * shape->Hq * ((shape->S + 63) / 64);
   if (blocks_a > 0x3FFFFFFFll) return KVCRUSH_ERR_UNSUPPORTED;
+  if ((long long)shape->B * shape->Hq > kMaxGridY) return KVCRUSH_ERR_UNSUPPORTED;  // second grid dimension
   ScoreParams p;
   p.q = (const char*)q;
   p.k = (const char*)k;

@@ -794,6 +794,7 @@ bool select_args_ok(const kvcrush_select_args* a) {
 // Sizes supported by the kernels (beyond what the arguments' own consistency demands).
 bool select_args_supported(const kvcrush_select_args* a) {
   const long long unit = a->unit > 1 ? a->unit : 1;
+  if (a->B > 65535) return false;  // sequences are the second grid dimension
   return a->Hs * unit <= kMaxHs;
 }
 

@@ -76,6 +76,10 @@ def test_scores_rejects_bad_arguments(lib):
     assert call(shape(), q=ctypes.c_void_p(0x1004)) == binding.ERR_INVALID_ARG      # misaligned
     assert call(shape(), ws=None) == binding.ERR_WORKSPACE
     assert call(shape(), ws_bytes=16) == binding.ERR_WORKSPACE
+    # launch-size limits: refused on the host, before anything is enqueued
+    assert call(shape(B=70000, Hq=1, Hkv=1)) == binding.ERR_UNSUPPORTED               # second grid dimension
+    assert call(shape(B=1, Hq=32, Hkv=8, S=1 << 24, reduce_groups=1), ws_bytes=1 << 62) == binding.ERR_UNSUPPORTED   # pass-B pieces
+    assert call(shape(B=4096, Hq=8, Hkv=8, S=1 << 24), ws_bytes=1 << 62) == binding.ERR_UNSUPPORTED     # pass-A blocks
 
 
 def test_select_rejects_bad_arguments(lib):
