@@ -86,6 +86,16 @@ typedef struct {
                             64 or 128 values and passing 1 / sqrt(true size) here
                             (e.g. 96-value heads: D = 128, softmax_scale = 1/sqrt(96));
                             models with their own attention scale pass that.          */
+  int64_t q_stride[3];   /* memory layout of q: elements (not bytes) between consecutive
+                            sequences, heads and tokens, in this order; the D values of
+                            one (sequence, head, token) are always contiguous.  All three
+                            zero: the packed layout [B, Hq, S, D].  A projection output
+                            kept token-major, [B, S, Hq, D], is {S*Hq*D, D, Hq*D}; a
+                            slice of a longer or padded buffer keeps that buffer's
+                            strides.  Each stride is positive and a multiple of 16 bytes,
+                            the token stride at least D and at most 2^24 bytes.  Only
+                            kvcrush_scores and kvcrush_row_lse read these fields.        */
+  int64_t k_stride[3];   /* the same for k ([B, Hkv, S, D] when all zero)                */
 } kvcrush_shape;
 
 /* ---------------------------------------------------------------- stage 1 --
@@ -96,8 +106,9 @@ typedef struct {
  * Every row of every head sums to one, so each score row totals S (times the
  * group size when reduce_groups = 1).
  *
- *   q       [B, Hq,  S, D]  row-major, D contiguous, dtype as in shape
- *   k       [B, Hkv, S, D]
+ *   q       [B, Hq,  S, D]  row-major, D contiguous, dtype as in shape (or any
+ *           layout shape->q_stride describes)
+ *   k       [B, Hkv, S, D]  (or as shape->k_stride describes)
  *   lse     nullable [B, Hq, S] fp32: natural-log sum-exp of each query row's
  *           scaled causal logits, as an attention forward pass leaves it.
  *           NULL: computed here (one more pass over Q K^T) and left in the

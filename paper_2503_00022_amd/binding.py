@@ -35,7 +35,9 @@ class KVCrushError(RuntimeError):
 
 class Shape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("B", "Hq", "Hkv", "S", "D", "dtype", "reduce_groups",
-                                                 "obs_window")] + [("softmax_scale", ctypes.c_float)]
+                                                 "obs_window")] + [("softmax_scale", ctypes.c_float),
+                                                                   ("q_stride", ctypes.c_int64 * 3),
+                                                                   ("k_stride", ctypes.c_int64 * 3)]
 
 
 class SelectArgs(ctypes.Structure):
@@ -110,6 +112,15 @@ def _dev(t: torch.Tensor, name: str) -> torch.Tensor:
     return t
 
 
+def _dev_rows(t: torch.Tensor, name: str) -> torch.Tensor:
+    """A [B,H,S,D] tensor or view on the GPU whose D values are contiguous (any other strides)."""
+    if t.device.type != "cuda":
+        raise ValueError(f"{name} must live in GPU memory")
+    if t.dim() != 4 or (t.shape[3] > 1 and t.stride(3) != 1):
+        raise ValueError(f"{name} must be [B,H,S,D] with the D values contiguous")
+    return t
+
+
 def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
@@ -126,7 +137,11 @@ def _check(status: int, what: str):
 
 def make_shape(q: torch.Tensor, k: torch.Tensor, reduce_groups: bool, window: int = 0, scale: float = 0.0) -> Shape:
     B, Hq, S, D = q.shape
-    return Shape(B, Hq, k.shape[1], S, D, _dtype_code(q), int(bool(reduce_groups)), int(window), float(scale))
+    shape = Shape(B, Hq, k.shape[1], S, D, _dtype_code(q), int(bool(reduce_groups)), int(window), float(scale))
+    for t, field in ((q, shape.q_stride), (k, shape.k_stride)):
+        if not t.is_contiguous():                     # views (a transposed projection output, a slice of a
+            field[:] = list(t.stride()[:3])           # padded buffer) are read in place, never copied
+    return shape
 
 
 def kvcrush_scores_workspace(shape: Shape) -> int:
@@ -139,8 +154,9 @@ def kvcrush_scores(q, k, reduce_groups: bool, lse=None, scores=None, workspace=N
     window = W > 0 restricts the contributing queries to the last min(W, S).
     scale: factor on Q.K before the softmax (0: 1/sqrt(D)).
     Returns (scores, workspace); the workspace's first B*Hq*S floats hold the
-    row log-sum-exps when `lse` was not supplied."""
-    q, k = _dev(q, "q"), _dev(k, "k")
+    row log-sum-exps when `lse` was not supplied.
+    q and k may be views with any sequence, head and token strides (D contiguous)."""
+    q, k = _dev_rows(q, "q"), _dev_rows(k, "k")
     if q.dtype != k.dtype or q.dim() != 4 or k.dim() != 4 or q.shape[0] != k.shape[0] \
             or q.shape[2:] != k.shape[2:]:
         raise ValueError("q and k must be [B,H,S,D] tensors of one dtype with matching B, S, D")
@@ -170,7 +186,7 @@ def kvcrush_row_lse(q, k, lse_out=None, stream=None, window=0, workspace="auto",
     (with window = W > 0 only the rows of the last min(W, S) queries are defined).
     workspace: a uint8 tensor, None (run without scratch memory) or "auto" (allocate what
     kvcrush_row_lse_workspace asks for)."""
-    q, k = _dev(q, "q"), _dev(k, "k")
+    q, k = _dev_rows(q, "q"), _dev_rows(k, "k")
     shape = make_shape(q, k, False, window, scale)
     if lse_out is None:
         lse_out = torch.empty(shape.B, shape.Hq, shape.S, dtype=torch.float32, device=q.device)

@@ -194,12 +194,14 @@ __global__ __launch_bounds__(kThreads) void append_logits_mfma_kernel(AppendPara
     const int row0 = k0 + C::kTile * w;
     if (row0 >= S) continue;  // tiles past the end stay unread
     if (!p.block_table) {
-      tile_load_async<C>(kh, row0, S, lds[w], rel, wave);
+      tile_load_async<C>(kh, row0, S, lds[w], rel, wave, lane);
     } else {
       // paged pool: the same LDS image, every 16-byte chunk fetched from its row's block
 #pragma unroll
       for (int j = 0; j < C::kLoadsPerWave; ++j) {
-        const int row = (int)(rel[j] / C::kRowBytes), in_row = (int)(rel[j] % C::kRowBytes);
+        int row, chunk;
+        tile_lane_chunk<C>(wave, lane, j, row, chunk);
+        const int in_row = chunk * 16;
         const char* src = key_row(p, b, g, bg, min(row0 + row, S - 1), C::kRowBytes) + in_row;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)(lds[w] + (wave + kWaves * j) * 1024),

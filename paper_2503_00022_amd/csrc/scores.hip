@@ -53,8 +53,11 @@ using namespace kvc::tiles;
 constexpr int kKeysPerWg = 64 * kWaves;  // pass B: keys held by one workgroup
 
 struct ScoreParams {
-  const char* q;     // [B,Hq,S,D]
-  const char* k;     // [B,Hkv,S,D]
+  const char* q;     // row (b, h, s) at q + b * q_sb + h * q_sh + s * q_rb bytes, D values contiguous
+  const char* k;     // the same with k_sb, k_sh, k_rb
+  long long q_sb, q_sh, k_sb, k_sh;  // byte strides between sequences and between heads
+  unsigned q_rb, k_rb;               // byte strides between consecutive tokens of one head
+  bool strided;                      // false: both arrays are packed [B,H,S,D] (the strides are not read)
   float* lse;        // [B,Hq,S] natural log (written by pass A, read by pass B)
   float* scores;     // [B,Hs,S]
   float* partial;    // pass B: [n_bh, n_kb, n_chunks, 256] partial column sums (n_chunks > 1)
@@ -250,7 +253,9 @@ struct IntC { static constexpr int value = N; };
 // K tiles wholly before the workgroup's first query need no mask and run in the
 // pipelined loop; the few tiles that touch the diagonal go through a plain
 // masked loop afterwards.
-template <bool BF16, int D, bool F16 = false>
+// STRIDED: Q and K rows lie where the caller's strides put them; otherwise the
+// packed [B,H,S,D] layout, whose strides are compile-time constants.
+template <bool BF16, int D, bool F16 = false, bool STRIDED = false>
 __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   using C = Cfg<BF16, D>;
   __shared__ __attribute__((aligned(1024))) char lds[3][C::kTileBytes];
@@ -270,12 +275,13 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   const int wg_q0 = blk * 64 * qsub;
   const int q0 = wg_q0 + (wave / hpw) * 64;  // first query row of this wave
 
-  const char* qh = p.q + ((size_t)b * p.Hq + head) * S * C::kRowBytes;
-  const char* kh = p.k + ((size_t)b * p.Hkv + kvh) * S * C::kRowBytes;
+  const char* qh = STRIDED ? p.q + b * p.q_sb + head * p.q_sh : p.q + ((size_t)b * p.Hq + head) * S * C::kRowBytes;
+  const char* kh = STRIDED ? p.k + b * p.k_sb + kvh * p.k_sh : p.k + ((size_t)b * p.Hkv + kvh) * S * C::kRowBytes;
+  const unsigned qrb = STRIDED ? p.q_rb : (unsigned)C::kRowBytes, krb = STRIDED ? p.k_rb : (unsigned)C::kRowBytes;
 
   u32x4 qf[2][C::kSteps];
-  load_stationary<C>(qf[0], qh, q0, S, lane);
-  load_stationary<C>(qf[1], qh, q0 + 32, S, lane);
+  load_stationary<C>(qf[0], qh, q0, S, lane, qrb);
+  load_stationary<C>(qf[1], qh, q0 + 32, S, lane, qrb);
 
   const int wg_qmax = min(S, wg_q0 + 64 * qsub) - 1;
   const int n_tiles = wg_qmax / C::kTile + 1;
@@ -286,7 +292,7 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   const int n_full = n_before * (slice + 1) / p.n_split - f_begin;
   const int off0 = lds_frag_offset0<C>(lane);
   uint32_t rel[C::kLoadsPerWave];
-  tile_lane_offsets<C>(rel, wave, lane);
+  tile_lane_offsets<C>(rel, wave, lane, krb);
 
   float m[2] = {kNegBig, kNegBig}, l[2] = {0.0f, 0.0f};
   const float c = p.scale_log2;
@@ -294,8 +300,8 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   if constexpr (C::kPipelined) {
     if (n_full > 0) {
       // (these tiles end before the workgroup's first query: always whole)
-      tile_load_async_full<C>(kh, f_begin * C::kTile, lds[0], rel, wave);
-      tile_load_async_full<C>(kh, (f_begin + min(1, n_full - 1)) * C::kTile, lds[1], rel, wave);
+      tile_load_async_full<C>(kh, f_begin * C::kTile, lds[0], rel, wave, krb);
+      tile_load_async_full<C>(kh, (f_begin + min(1, n_full - 1)) * C::kTile, lds[1], rel, wave, krb);
       wait_async_loads();
       __syncthreads();
       // tile t lives in lds[t % 3]: while iteration `it` multiplies tiles it and
@@ -324,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
       auto body = [&](auto P, int it) {
         constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
         constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
-        tile_load_async_full<C>(kh, (f_begin + min(it + 2, n_full - 1)) * C::kTile, lds[ld], rel, wave);
+        tile_load_async_full<C>(kh, (f_begin + min(it + 2, n_full - 1)) * C::kTile, lds[ld], rel, wave, krb);
         const bool live = it < n_full;
         float sum[2], mref[2];
         // block (it, sub 1) goes through the MFMAs while block (it, sub 0) is summed
@@ -348,13 +354,13 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
   }
 
   if (n_tiles > n_before && slice == p.n_split - 1) {
-    tile_load_async<C>(kh, n_before * C::kTile, S, lds[0], rel, wave);
+    tile_load_async<C>(kh, n_before * C::kTile, S, lds[0], rel, wave, lane, krb);
     wait_async_loads();
     __syncthreads();
     for (int it = n_before; it < n_tiles; ++it) {
       const int kt = it * C::kTile;
       const char* buf = lds[(it - n_before) & 1];
-      if (it + 1 < n_tiles) tile_load_async<C>(kh, kt + C::kTile, S, lds[(it - n_before + 1) & 1], rel, wave);
+      if (it + 1 < n_tiles) tile_load_async<C>(kh, kt + C::kTile, S, lds[(it - n_before + 1) & 1], rel, wave, lane, krb);
 #pragma unroll
       for (int ks = 0; ks < C::kTileSub; ++ks) {
         const int kmin = kt + 32 * ks, kmax = kmin + 31;
@@ -425,7 +431,7 @@ __global__ __launch_bounds__(256) void lse_combine_kernel(ScoreParams p) {
 // block needs more than one piece, each writes partial sums and
 // colsum_reduce_kernel adds them in a fixed order (no floating-point atomics:
 // the result does not depend on scheduling).
-template <bool BF16, int D, bool F16 = false>
+template <bool BF16, int D, bool F16 = false, bool STRIDED = false>
 __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, const float* lse_in) {
   using C = Cfg<BF16, D>;
   __shared__ __attribute__((aligned(1024))) char lds[3][C::kTileBytes];
@@ -459,10 +465,11 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   const int wg_k0 = kb * kKeysPerWg;
   const int k0 = wg_k0 + wave * 64;  // first key row of this wave
 
-  const char* kh = p.k + ((size_t)b * p.Hkv + kvh) * S * C::kRowBytes;
+  const char* kh = STRIDED ? p.k + b * p.k_sb + kvh * p.k_sh : p.k + ((size_t)b * p.Hkv + kvh) * S * C::kRowBytes;
+  const unsigned qrb = STRIDED ? p.q_rb : (unsigned)C::kRowBytes, krb = STRIDED ? p.k_rb : (unsigned)C::kRowBytes;
   u32x4 kf[2][C::kSteps];
-  load_stationary<C>(kf[0], kh, k0, S, lane);
-  load_stationary<C>(kf[1], kh, k0 + 32, S, lane);
+  load_stationary<C>(kf[0], kh, k0, S, lane, krb);
+  load_stationary<C>(kf[1], kh, k0 + 32, S, lane, krb);
 
   // tiles of this piece: [t_first, t_last]; those below f_first touch the diagonal
   const int t_first = max(p.tile0 + chunk * p.chunk_tiles, kb * kTpk);
@@ -473,12 +480,14 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   const float c = p.scale_log2;
   const int off0 = lds_frag_offset0<C>(lane);
   uint32_t rel[C::kLoadsPerWave];
-  tile_lane_offsets<C>(rel, wave, lane);
+  tile_lane_offsets<C>(rel, wave, lane, qrb);
 
   f32x16 col[2];
   zero_acc(col);
 
-  auto q_head = [&](int head) { return p.q + ((size_t)b * p.Hq + head) * S * C::kRowBytes; };
+  auto q_head = [&](int head) {
+    return STRIDED ? p.q + b * p.q_sb + head * p.q_sh : p.q + ((size_t)b * p.Hq + head) * S * C::kRowBytes;
+  };
   const unsigned n_live = (unsigned)(S - p.q_first);
   auto load_lse = [&](int head, int qt) -> float {
     // +inf for rows past the end makes their probabilities exactly zero.  Branch
@@ -501,10 +510,10 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       };
       int head, qt;
       tile_of(0, head, qt);
-      tile_load_async<C>(q_head(head), qt, S, lds[0], rel, wave);
+      tile_load_async<C>(q_head(head), qt, S, lds[0], rel, wave, lane, qrb);
       lds_lse[0][tid] = load_lse(head, qt);
       tile_of(min(1, n_fast - 1), head, qt);
-      tile_load_async<C>(q_head(head), qt, S, lds[1], rel, wave);
+      tile_load_async<C>(q_head(head), qt, S, lds[1], rel, wave, lane, qrb);
       {
         const float v = load_lse(head, qt);
         lds_lse[1][tid] = n_fast > 1 ? v : INFINITY;
@@ -528,7 +537,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
         constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
         constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
         tile_of(min(it + 2, n_fast - 1), head, qt);
-        tile_load_async<C>(q_head(head), qt, S, lds[ld], rel, wave);
+        tile_load_async<C>(q_head(head), qt, S, lds[ld], rel, wave, lane, qrb);
         const float ld_lse = load_lse(head, qt);
         const float st_lse = it + 2 < n_fast ? ld_lse : INFINITY;
         const float lse_a = lds_lse[cur][lane & 31], lse_b = lds_lse[cur][32 + (lane & 31)];
@@ -556,7 +565,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
     };
     int head, qt;
     tile_of(0, head, qt);
-    tile_load_async<C>(q_head(head), qt, S, lds[0], rel, wave);
+    tile_load_async<C>(q_head(head), qt, S, lds[0], rel, wave, lane, qrb);
     lds_lse[0][tid] = load_lse(head, qt);
     wait_async_loads();
     __syncthreads();
@@ -567,7 +576,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       float st_lse = 0.0f;
       if (it + 1 < n_slow) {
         tile_of(it + 1, head, qt);
-        tile_load_async<C>(q_head(head), qt, S, lds[(it + 1) & 1], rel, wave);
+        tile_load_async<C>(q_head(head), qt, S, lds[(it + 1) & 1], rel, wave, lane, qrb);
         st_lse = load_lse(head, qt);
       }
 #pragma unroll
@@ -716,8 +725,11 @@ kvcrush_status launch_lse(const ScoreParams& base, float2* split_ml, hipStream_t
   a.split_rows = pl.split_rows;
   a.split_ml = split_ml;
   if ((long long)pl.launched * pl.n_split * pl.n_bh > kMaxGridX) return KVCRUSH_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((lse_kernel<BF16, D, F16>), dim3((unsigned)(pl.launched * pl.n_split * pl.n_bh)),
-                     dim3(kThreads), 0, stream, a);
+  const dim3 grid((unsigned)(pl.launched * pl.n_split * pl.n_bh));
+  if (a.strided)
+    hipLaunchKernelGGL((lse_kernel<BF16, D, F16, true>), grid, dim3(kThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL((lse_kernel<BF16, D, F16, false>), grid, dim3(kThreads), 0, stream, a);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   if (pl.n_split > 1) {
     hipLaunchKernelGGL(lse_combine_kernel, dim3((pl.split_rows + 3) / 4, a.B * a.Hq), dim3(256), 0, stream, a);
@@ -744,8 +756,13 @@ kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, flo
   p.n_chunks = pl.n_chunks;
   p.chunk_tiles = pl.chunk_tiles;
   p.n_bh = p.B * (p.reduce_groups ? p.Hkv : p.Hq);
-  hipLaunchKernelGGL((colsum_kernel<BF16, D, F16>), dim3((unsigned)(pl.pieces * p.n_bh)), dim3(kThreads), 0,
-                     stream, p, lse_user ? lse_user : p.lse);
+  const dim3 grid((unsigned)(pl.pieces * p.n_bh));
+  if (p.strided)
+    hipLaunchKernelGGL((colsum_kernel<BF16, D, F16, true>), grid, dim3(kThreads), 0, stream, p,
+                       lse_user ? lse_user : p.lse);
+  else
+    hipLaunchKernelGGL((colsum_kernel<BF16, D, F16, false>), grid, dim3(kThreads), 0, stream, p,
+                       lse_user ? lse_user : p.lse);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   if (pl.n_chunks > 1) {
     hipLaunchKernelGGL(colsum_reduce_kernel, dim3(pl.n_kb, p.n_bh), dim3(kKeysPerWg), 0, stream, p,
@@ -778,6 +795,34 @@ size_t split_bytes(const kvcrush_shape* s) {
                      s->B, s->Hq);
 }
 
+size_t elem_bytes(const kvcrush_shape* s) { return s->dtype == KVCRUSH_F32 ? 4 : 2; }
+
+// A caller's strides (elements): all zero (packed), or all positive, multiples of
+// 16 bytes, rows not overlapping their own D values.
+bool strides_ok(const int64_t (&st)[3], const kvcrush_shape* s) {
+  if (st[0] == 0 && st[1] == 0 && st[2] == 0) return true;
+  const long long eb = (long long)elem_bytes(s);
+  for (int i = 0; i < 3; ++i) {
+    if (st[i] <= 0 || st[i] > (1ll << 56) || (st[i] * eb) % 16 != 0) return false;
+  }
+  return st[2] >= s->D && st[2] * eb <= (1ll << 24);
+}
+
+// Byte strides of q (heads = Hq) or k (heads = Hkv): the caller's, or the packed layout's.
+void byte_strides(const int64_t (&st)[3], const kvcrush_shape* s, int heads, long long& sb, long long& sh,
+                  unsigned& rb) {
+  const long long eb = (long long)elem_bytes(s);
+  if (st[0] == 0 && st[1] == 0 && st[2] == 0) {
+    rb = (unsigned)(s->D * eb);
+    sh = (long long)s->S * rb;
+    sb = (long long)heads * sh;
+  } else {
+    sb = st[0] * eb;
+    sh = st[1] * eb;
+    rb = (unsigned)(st[2] * eb);
+  }
+}
+
 bool shape_ok(const kvcrush_shape* s) {
   if (!s) return false;
   if (s->B < 1 || s->Hq < 1 || s->Hkv < 1 || s->S < 1 || s->D < 1) return false;
@@ -786,7 +831,7 @@ bool shape_ok(const kvcrush_shape* s) {
   if (s->reduce_groups != 0 && s->reduce_groups != 1) return false;
   if (s->obs_window < 0) return false;
   if (!(s->softmax_scale >= 0.0f) || s->softmax_scale > 1.0e6f) return false;  // also rejects NaN
-  return true;
+  return strides_ok(s->q_stride, s) && strides_ok(s->k_stride, s);
 }
 
 kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const void* k,
@@ -798,6 +843,13 @@ kvcrush_status scores_entry(const kvcrush_shape* shape, const void* q, const voi
   ScoreParams p;
   p.q = (const char*)q;
   p.k = (const char*)k;
+  byte_strides(shape->q_stride, shape, shape->Hq, p.q_sb, p.q_sh, p.q_rb);
+  byte_strides(shape->k_stride, shape, shape->Hkv, p.k_sb, p.k_sh, p.k_rb);
+  {
+    const long long rb = (long long)shape->D * (long long)elem_bytes(shape), sh = rb * shape->S;
+    p.strided = !(p.q_rb == rb && p.k_rb == rb && p.q_sh == sh && p.k_sh == sh && p.q_sb == sh * shape->Hq &&
+                  p.k_sb == sh * shape->Hkv);
+  }
   p.lse = lse_out;
   p.scores = scores;
   p.partial = partial;

@@ -83,17 +83,28 @@ __device__ __forceinline__ u32x4 lds_frag(const char* buf, int off0, int sub, in
   return *(const u32x4*)(buf + sub * C::kSubBytes + (off0 ^ (step << 4)));
 }
 
-// Per-lane byte offsets, relative to a tile's first row, of the 16-byte chunks
-// this lane copies (one per wave instruction; see tile_load_async).
+// Logical 16-byte chunk (tile row, chunk of the row) that this lane copies with
+// its j-th load of a tile (one load per wave instruction; see tile_load_async).
 template <class C>
-__device__ __forceinline__ void tile_lane_offsets(uint32_t (&rel)[C::kLoadsPerWave], int wave, int lane) {
+__device__ __forceinline__ void tile_lane_chunk(int wave, int lane, int j, int& row, int& chunk) {
+  const int inst = wave + kWaves * j;
+  const int p = inst * 64 + lane;  // physical chunk this lane fills
+  const int line = p >> 4, pos = (p & 15) ^ (line & 15);
+  const int q = line * 16 + pos;   // logical chunk
+  row = q / C::kChunksPerRow;
+  chunk = q % C::kChunksPerRow;
+}
+
+// Per-lane byte offsets of those chunks, relative to a tile's first row, for rows
+// that lie `row_bytes` apart in memory (kRowBytes when the rows are packed).
+template <class C>
+__device__ __forceinline__ void tile_lane_offsets(uint32_t (&rel)[C::kLoadsPerWave], int wave, int lane,
+                                                  uint32_t row_bytes = C::kRowBytes) {
 #pragma unroll
   for (int j = 0; j < C::kLoadsPerWave; ++j) {
-    const int inst = wave + kWaves * j;
-    const int p = inst * 64 + lane;  // physical chunk this lane fills
-    const int line = p >> 4, pos = (p & 15) ^ (line & 15);
-    const int q = line * 16 + pos;   // logical chunk
-    rel[j] = (uint32_t)((q / C::kChunksPerRow) * C::kRowBytes + (q % C::kChunksPerRow) * 16);
+    int row, chunk;
+    tile_lane_chunk<C>(wave, lane, j, row, chunk);
+    rel[j] = (uint32_t)row * row_bytes + (uint32_t)chunk * 16;
   }
 }
 
@@ -103,15 +114,17 @@ __device__ __forceinline__ void tile_lane_offsets(uint32_t (&rel)[C::kLoadsPerWa
 // mask or ignore them).  Completion: s_waitcnt vmcnt(0), then a barrier.
 template <class C>
 __device__ __forceinline__ void tile_load_async(const char* head_base, int row0, int S, char* buf,
-                                                const uint32_t (&rel)[C::kLoadsPerWave], int wave) {
-  const char* tile = head_base + (size_t)row0 * C::kRowBytes;
+                                                const uint32_t (&rel)[C::kLoadsPerWave], int wave, int lane,
+                                                uint32_t row_bytes = C::kRowBytes) {
+  const char* tile = head_base + (size_t)row0 * row_bytes;
   const int valid = S - row0;  // rows of this tile inside the sequence
 #pragma unroll
   for (int j = 0; j < C::kLoadsPerWave; ++j) {
     uint32_t off = rel[j];
     if (valid < C::kTile) {  // ragged last tile (uniform branch)
-      const uint32_t row = off / C::kRowBytes, in_row = off % C::kRowBytes;
-      off = min(row, (uint32_t)(valid - 1)) * C::kRowBytes + in_row;
+      int row, chunk;
+      tile_lane_chunk<C>(wave, lane, j, row, chunk);
+      off = (uint32_t)min(row, valid - 1) * row_bytes + (uint32_t)chunk * 16;
     }
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile + off),
                                      (__attribute__((address_space(3))) void*)(buf + (wave + kWaves * j) * 1024),
@@ -123,8 +136,9 @@ __device__ __forceinline__ void tile_load_async(const char* head_base, int row0,
 // address is the uniform tile base plus the lane's fixed offset.
 template <class C>
 __device__ __forceinline__ void tile_load_async_full(const char* head_base, int row0, char* buf,
-                                                     const uint32_t (&rel)[C::kLoadsPerWave], int wave) {
-  const char* tile = head_base + (size_t)row0 * C::kRowBytes;
+                                                     const uint32_t (&rel)[C::kLoadsPerWave], int wave,
+                                                     uint32_t row_bytes = C::kRowBytes) {
+  const char* tile = head_base + (size_t)row0 * row_bytes;
 #pragma unroll
   for (int j = 0; j < C::kLoadsPerWave; ++j)
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile + rel[j]),
@@ -139,13 +153,13 @@ __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmc
 // (zero rows past the end of the sequence).
 template <class C>
 __device__ __forceinline__ void load_stationary(u32x4 (&frag)[C::kSteps], const char* head_base,
-                                                int row0, int S, int lane) {
+                                                int row0, int S, int lane, uint32_t row_bytes = C::kRowBytes) {
   const int t = row0 + (lane & 31);
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
     u32x4 v = {0u, 0u, 0u, 0u};
     if (t < S)
-      v = *(const u32x4*)(head_base + (size_t)t * C::kRowBytes + (s + (lane >> 5) * C::kSteps) * 16);
+      v = *(const u32x4*)(head_base + (size_t)t * row_bytes + (s + (lane >> 5) * C::kSteps) * 16);
     frag[s] = v;
   }
 }

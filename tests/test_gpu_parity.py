@@ -976,3 +976,41 @@ def test_layer_compressor_and_decode_cache(kv, oracle):
     assert torch.equal(dc.k.cpu()[:, :, :n].view(torch.uint8), o_k[:, :, :n].view(torch.uint8))
     assert torch.equal(dc.v.cpu()[:, :, :n].view(torch.uint8), o_v[:, :, :n].view(torch.uint8))
     assert rel_err(dc.scores[:, :, :n], o_sc[:, :, :n]) <= SCORE_RTOL
+
+
+# ------------------------------------------------------------------ memory layouts of Q and K
+@pytest.mark.parametrize("B,Hq,Hkv,S,D,dtype,rg,W", [
+    (2, 8, 2, 700, 128, "bf16", True, 0),      # ragged last tile
+    (1, 4, 4, 1300, 64, "bf16", False, 0),
+    (2, 4, 2, 333, 128, "f32", True, 0),
+    (1, 8, 2, 2500, 128, "f16", True, 64),     # observation window, key slices
+    (1, 32, 8, 4096, 128, "bf16", True, 0),    # several key blocks and chunks per row
+])
+def test_scores_strided_layouts(kv, oracle, B, Hq, Hkv, S, D, dtype, rg, W):
+    """Q and K read in place from views: token-major projection outputs [B,S,H,D], and the first S
+    tokens of longer (padded) buffers.  The oracle sees packed copies of the same values; the packed
+    GPU call must agree to the bit (same arithmetic, other addresses)."""
+    say(f"strided layouts B={B} Hq={Hq} Hkv={Hkv} S={S} D={D} {dtype} rg={rg} W={W}")
+    w = inputs.Workload("t", B, Hq, Hkv, S, D, dtype, S // 4, 0.5, "alternating", rg, sink_bias=True)
+    q, k, _ = inputs.make_qkv(w, 31)
+    ref = oracle.scores(q, k, rg, threads=THREADS, window=W)
+    packed, _ = kv.kvcrush_scores(q.cuda(), k.cuda(), rg, window=W)
+    # token-major storage, seen as [B,H,S,D]
+    q_tm = q.cuda().transpose(1, 2).contiguous().transpose(1, 2)
+    k_tm = k.cuda().transpose(1, 2).contiguous().transpose(1, 2)
+    assert not q_tm.is_contiguous() and q_tm.stride(2) == Hq * D
+    # packed heads inside buffers of S + 77 and S + 8 tokens
+    q_pad = torch.randn(B, Hq, S + 77, D, device="cuda").to(q.dtype)
+    k_pad = torch.randn(B, Hkv, S + 8, D, device="cuda").to(k.dtype)
+    q_pad[:, :, :S], k_pad[:, :, :S] = q.cuda(), k.cuda()
+    for name, qq, kk in (("token-major", q_tm, k_tm), ("padded", q_pad[:, :, :S], k_pad[:, :, :S]),
+                         ("mixed", q_tm, k_pad[:, :, :S])):
+        got, _ = kv.kvcrush_scores(qq, kk, rg, window=W)
+        torch.cuda.synchronize()
+        assert rel_err(got, ref) <= SCORE_RTOL, name
+        assert torch.equal(got, packed), name
+    lse_p = kv.kvcrush_row_lse(q.cuda(), k.cuda(), window=W)
+    lse_s = kv.kvcrush_row_lse(q_tm, k_pad[:, :, :S], window=W)
+    torch.cuda.synchronize()
+    first = max(S - W, 0) if W else 0
+    assert torch.equal(lse_p[:, :, first:], lse_s[:, :, first:])

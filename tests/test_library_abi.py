@@ -76,6 +76,19 @@ def test_scores_rejects_bad_arguments(lib):
     assert call(shape(), q=ctypes.c_void_p(0x1004)) == binding.ERR_INVALID_ARG      # misaligned
     assert call(shape(), ws=None) == binding.ERR_WORKSPACE
     assert call(shape(), ws_bytes=16) == binding.ERR_WORKSPACE
+    # memory layouts: all-zero strides are the packed layout; otherwise positive multiples of 16 bytes
+    def strided(q=(0, 0, 0), k=(0, 0, 0), **kw):
+        sh = shape(**kw)
+        sh.q_stride[:], sh.k_stride[:] = q, k
+        return sh
+    # (accepted layouts are probed through the size query: no call here may reach a launch)
+    assert lib.kvcrush_scores_workspace(ctypes.byref(strided(q=(64 * 4 * 128, 128, 4 * 128)))) > 0   # [B,S,Hq,D]
+    assert lib.kvcrush_scores_workspace(ctypes.byref(strided(q=(64 * 4 * 128, 128, 0)))) == 0
+    assert call(strided(q=(64 * 4 * 128, 128, 0))) == binding.ERR_INVALID_ARG          # partly given
+    assert call(strided(k=(64 * 2 * 128, 128, 127))) == binding.ERR_INVALID_ARG        # rows overlap their own values
+    assert call(strided(k=(64 * 2 * 128, 132, 2 * 128))) == binding.ERR_INVALID_ARG    # head stride not 16-byte
+    assert call(strided(q=(-1, 128, 512))) == binding.ERR_INVALID_ARG
+    assert call(strided(q=(1 << 30, 128, 1 << 24))) == binding.ERR_INVALID_ARG         # token stride over 2^24 bytes
     # launch-size limits: refused on the host, before anything is enqueued
     assert call(shape(B=70000, Hq=1, Hkv=1)) == binding.ERR_UNSUPPORTED               # second grid dimension
     assert call(shape(B=1, Hq=32, Hkv=8, S=1 << 24, reduce_groups=1), ws_bytes=1 << 62) == binding.ERR_UNSUPPORTED   # pass-B pieces
@@ -127,7 +140,7 @@ def test_score_kernels_keep_their_registers():
     from paper_2503_00022_amd import build
     report = build.resource_usage("scores.hip")
     hot = {name: r for name, r in report.items() if "lse_kernel" in name or "colsum_kernel" in name}
-    assert len(hot) == 12, sorted(report)          # {lse, colsum} x {bf16, fp16, fp32} x {D = 64, 128}
+    assert len(hot) == 24, sorted(report)          # {lse, colsum} x {bf16, fp16, fp32} x {D = 64, 128} x {packed, strided}
     for name, r in hot.items():
         assert r["VGPRs Spill"] == 0 and r["SGPRs Spill"] == 0 and r["ScratchSize"] == 0, (name, r)
         assert r["Occupancy"] >= 2, (name, r)
@@ -159,7 +172,7 @@ def test_struct_layouts_match_the_header(tmp_path):
     text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
     for cname, cls in structs.items():
         body = re.search(r"typedef struct \{([^{}]*)\} " + cname + ";", text).group(1)
-        names = re.findall(r"(\w+)\s*[,;]", body)
+        names = re.findall(r"(\w+)\s*(?:\[\d+\])?\s*[,;]", body)
         assert names == [f for f, _ in cls._fields_], (cname, names)
 
 
@@ -180,7 +193,10 @@ def test_select_protected_ends_validation(lib):
 
 def make_shape(base, overrides):
     d = dict(base, **overrides)
-    return binding.Shape(*[d.get(f, 0) for f, _ in binding.Shape._fields_])
+    shape = binding.Shape(*[d.get(f, 0) for f, _ in binding.Shape._fields_ if not f.endswith("_stride")])
+    for f in ("q_stride", "k_stride"):
+        getattr(shape, f)[:] = d.get(f, (0, 0, 0))
+    return shape
 
 
 def test_window_pool_and_row_lse_validation(lib):
