@@ -301,7 +301,8 @@ kvcrush_status kvcrush_compact_cache(int32_t B, int32_t Hkv, int32_t Hs, int32_t
 
 const char* kvcrush_status_string(kvcrush_status status);
 
-/* Library version, e.g. 110 for 0.1.1. */
+/* Library version: 100 * minor + 10 * patch (120 = 0.1.2); changes whenever a struct or
+ * a signature of this header changes. */
 int32_t kvcrush_version(void);
 
 #ifdef __cplusplus

@@ -940,5 +940,5 @@ extern "C" const char* kvcrush_status_string(kvcrush_status status) {
   return "unknown status";
 }
 
-extern "C" int32_t kvcrush_version(void) { return 110; }
+extern "C" int32_t kvcrush_version(void) { return 120; }
 
