@@ -1014,3 +1014,46 @@ def test_scores_strided_layouts(kv, oracle, B, Hq, Hkv, S, D, dtype, rg, W):
     torch.cuda.synchronize()
     first = max(S - W, 0) if W else 0
     assert torch.equal(lse_p[:, :, first:], lse_s[:, :, first:])
+
+
+def test_scores_append_random_sweep(kv, oracle):
+    """Seeded sweep of the decoding step: dtypes, head dims, group sizes, dense and paged caches,
+    per-sequence device lengths, caller's softmax scale (40 cases)."""
+    import random
+    rng = random.Random(4242)
+    for case in range(40):
+        dtype = rng.choice(["bf16", "bf16", "f16", "f32"])
+        td = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dtype]
+        D, Hkv, G, B = rng.choice([64, 128]), rng.choice([1, 2, 3, 8]), rng.choice([1, 2, 4, 5, 12]), rng.choice([1, 2, 3, 8])
+        bs = rng.choice([16, 32])
+        S = rng.choice([rng.randint(1, 70), rng.randint(1, 1200), rng.randint(1200, 3000)])
+        cap = ((S + rng.randint(0, 200)) + bs - 1) // bs * bs
+        rg, paged, use_len = rng.random() < 0.6, rng.random() < 0.4, rng.random() < 0.4
+        scale = rng.choice([0.0, 0.0, 0.1])
+        Hq = Hkv * G
+        Hs = Hkv if rg else Hq
+        say(f"  sweep {case}: B={B} Hq={Hq} Hkv={Hkv} S={S} cap={cap} D={D} {dtype} rg={rg} paged={paged} "
+            f"block={bs} lengths={use_len} scale={scale}")
+        g = torch.Generator().manual_seed(9000 + case)
+        qn = torch.randn(B, Hq, D, generator=g).to(td)
+        kc = torch.randn(B, Hkv, cap, D, generator=g).to(td)
+        kc[:, :, :4] *= 2.0
+        old = torch.rand(B, Hs, cap, generator=g) * 3.0
+        lens_h = [rng.randint(1, S) for _ in range(B)] if use_len else [S] * B
+        if use_len:
+            lens_h[rng.randrange(B)] = S
+        lens = torch.tensor(lens_h, dtype=torch.int32).cuda() if use_len else None
+        kdev, kw = kc.cuda(), {}
+        if paged:
+            nb = cap // bs
+            table = torch.randperm(B * nb, generator=g).to(torch.int32).view(B, nb)
+            pool = torch.zeros(B * nb, bs, Hkv, D, dtype=td)
+            pool[table.long().view(-1)] = kc.view(B, Hkv, nb, bs, D).permute(0, 2, 3, 1, 4).reshape(B * nb, bs, Hkv, D)
+            kdev, kw = pool.cuda(), dict(block_table=table.cuda(), block_size=bs)
+        got = kv.kvcrush_scores_append(qn.cuda(), kdev, old.clone().cuda(), S, rg, lengths=lens, scale=scale, **kw).cpu()
+        for b in range(B):                     # the oracle takes one length: sequence by sequence
+            n = lens_h[b]
+            want = old[b:b + 1].clone().contiguous()
+            oracle.scores_append(qn[b:b + 1].contiguous(), kc[b:b + 1].contiguous(), want, n, rg, scale=scale)
+            assert torch.equal(got[b, :, n:], old[b, :, n:]), f"case {case}: entries beyond the length were touched"
+            assert rel_err(got[b, :, :n], want[0, :, :n]) <= SCORE_RTOL, f"case {case}"
