@@ -1057,3 +1057,33 @@ def test_scores_append_random_sweep(kv, oracle):
             oracle.scores_append(qn[b:b + 1].contiguous(), kc[b:b + 1].contiguous(), want, n, rg, scale=scale)
             assert torch.equal(got[b, :, n:], old[b, :, n:]), f"case {case}: entries beyond the length were touched"
             assert rel_err(got[b, :, :n], want[0, :, :n]) <= SCORE_RTOL, f"case {case}"
+
+
+def test_thousands_of_sequences_in_one_call(kv, oracle):
+    """Batch sizes in the thousands (the sequence index is a grid dimension of its own in most
+    kernels): every stage and the decoding step at B = 5000, short sequences."""
+    say("B = 5000 through scores, select, compact and the decoding step")
+    B, Hq, Hkv, S, D, budget, n_imp = 5000, 2, 1, 40, 64, 12, 6
+    w = inputs.Workload("t", B, Hq, Hkv, S, D, "bf16", budget, 0.5, "alternating", True, sink_bias=True)
+    q, k, v = inputs.make_qkv(w, 77)
+    sc, _ = kv.kvcrush_scores(q.cuda(), k.cuda(), True)
+    idx, kind, _ = kv.kvcrush_select(sc, budget, n_imp, 0, "random", 5, n_sink=1, n_recent=2)
+    ko, vo = kv.kvcrush_compact(k.cuda(), v.cuda(), idx)
+    torch.cuda.synchronize()
+    assert rel_err(sc, oracle.scores(q, k, True, threads=THREADS)) <= SCORE_RTOL
+    ridx, rkind, _ = oracle.select(sc.cpu(), budget, n_imp, 0, "random", 5, n_sink=1, n_recent=2)
+    assert torch.equal(idx.cpu(), ridx) and torch.equal(kind.cpu(), rkind)
+    rk, rv = oracle.compact(k, v, ridx)
+    assert torch.equal(ko.cpu().view(torch.uint8), rk.view(torch.uint8))
+    assert torch.equal(vo.cpu().view(torch.uint8), rv.view(torch.uint8))
+    # one decoding step on all of them
+    cap = 48
+    kc = torch.zeros(B, Hkv, cap, D, dtype=torch.bfloat16)
+    kc[:, :, :S] = k
+    old = torch.zeros(B, Hkv, cap)
+    old[:, :, :S] = sc.cpu()
+    qn = q[:, :, -1].contiguous()
+    got = kv.kvcrush_scores_append(qn.cuda(), kc.cuda(), old.clone().cuda(), S, True)
+    torch.cuda.synchronize()
+    want = oracle.scores_append(qn, kc, old.clone(), S, True)
+    assert rel_err(got[:, :, :S], want[:, :, :S]) <= SCORE_RTOL
