@@ -1087,3 +1087,36 @@ def test_thousands_of_sequences_in_one_call(kv, oracle):
     torch.cuda.synchronize()
     want = oracle.scores_append(qn, kc, old.clone(), S, True)
     assert rel_err(got[:, :, :S], want[:, :, :S]) <= SCORE_RTOL
+
+
+def test_ragged_batch_from_padded_buffers(kv, oracle):
+    """A prefill batch of unequal lengths in padded [B,H,S_max,D] buffers: one score and one select
+    call per sequence on views of its own tokens (no copies of Q, K or V), one gather for the batch."""
+    say("ragged batch: lengths 90, 700, 1025 in buffers padded to 1100")
+    B, Hq, Hkv, D, S_max, budget, n_imp = 3, 8, 2, 128, 1100, 64, 40
+    lens = [90, 700, 1025]
+    w = inputs.Workload("t", B, Hq, Hkv, S_max, D, "bf16", budget, 0.5, "alternating", True, sink_bias=True)
+    q, k, v = inputs.make_qkv(w, 41)
+    for b, n in enumerate(lens):                       # what lies beyond a sequence's end is never read
+        q[b, :, n:], k[b, :, n:], v[b, :, n:] = float("nan"), float("nan"), float("nan")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    scores = torch.zeros(B, Hkv, S_max, device="cuda")
+    idx = torch.empty(B, budget, dtype=torch.int32, device="cuda")
+    for b, n in enumerate(lens):
+        sc, _ = kv.kvcrush_scores(qd[b:b + 1, :, :n], kd[b:b + 1, :, :n], True)
+        scores[b, :, :n] = sc[0]
+        kv.kvcrush_select(scores[b:b + 1], budget, n_imp, 0, "mean", 9, want_kind=False, idx=idx[b:b + 1],
+                          n_sink=2, n_recent=8, valid_len=n)
+    k_out = torch.zeros(B, Hkv, budget, D, dtype=torch.bfloat16, device="cuda")
+    v_out, sc_out = torch.zeros_like(k_out), torch.zeros(B, Hkv, budget, device="cuda")
+    kv.kvcrush_compact_cache(kd, vd, scores, idx, k_out, v_out, sc_out)
+    torch.cuda.synchronize()
+    for b, n in enumerate(lens):
+        qb, kb, vb = [t[b:b + 1, :, :n].contiguous() for t in (q, k, v)]
+        assert rel_err(scores[b:b + 1, :, :n], oracle.scores(qb, kb, True, threads=THREADS)) <= SCORE_RTOL
+        ridx, _, _ = oracle.select(scores[b:b + 1, :, :n].cpu().contiguous(), budget, n_imp, 0, "mean", 9,
+                                   n_sink=2, n_recent=8)
+        assert torch.equal(idx[b:b + 1].cpu(), ridx)
+        rk, rv = oracle.compact(kb, vb, ridx)
+        assert torch.equal(k_out[b:b + 1].cpu().view(torch.uint8), rk.view(torch.uint8))
+        assert torch.equal(v_out[b:b + 1].cpu().view(torch.uint8), rv.view(torch.uint8))
