@@ -39,6 +39,12 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> str:
+    """Build the library only if there is none (test harnesses, smoke runs and the benchmark call
+    this; the binding itself never builds and raises when the library is missing)."""
+    return LIB_PATH if os.path.exists(LIB_PATH) else build_library()
+
+
 def resource_usage(source: str) -> dict:
     """Compile one csrc file (device code only, no output kept) and return the compiler's
     per-kernel resource report: {mangled kernel name: {"VGPRs": n, "VGPRs Spill": n, ...}}.

@@ -18,8 +18,9 @@ THREADS = min(16, os.cpu_count() or 1)
 @pytest.fixture(scope="module")
 def kv():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
-    from paper_2503_00022_amd import binding
-    binding.load()  # fails loudly when the library was not built
+    from paper_2503_00022_amd import binding, build
+    build.ensure_built()  # compiles only when no library is there
+    binding.load()        # the binding itself never builds and never falls back
     return binding
 
 

@@ -15,9 +15,8 @@ HEADER = os.path.join(ROOT, "include", "kvcrush.h")
 
 @pytest.fixture(scope="module")
 def lib():
-    if not os.path.exists(binding.LIB_PATH):
-        from paper_2503_00022_amd import build
-        build.build_library()
+    from paper_2503_00022_amd import build
+    build.ensure_built()
     return binding.load()
 
 
