@@ -57,9 +57,42 @@ def parse():
                          "replays; stage times still come from the eager pass")
     ap.add_argument("--cache-len", type=int, default=0, help="--decode: valid tokens per cache (0: the workload's budget)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the MFMA-only calibration launch that follows the timed region")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     return ap.parse_args()
+
+
+def mfma_ceiling_tflops(torch, dev, q_sample):
+    """What the matrix pipe sustains on v_mfma_f32_32x32x16_bf16 alone (no LDS traffic, no vector ALU
+    work) with operands drawn from the workload's own Q values: the measured counterpart of the
+    datasheet peak.  The kernel lives in the separate calibration library."""
+    import ctypes
+    from paper_2503_00022_amd import build as b
+    L = ctypes.CDLL(b.BENCH_LIB_PATH)
+    L.kvcrush_bench_mfma_ceiling.restype = ctypes.c_double
+    L.kvcrush_bench_mfma_ceiling.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                             ctypes.c_void_p]
+    L.kvcrush_bench_mfma_operand_bytes.restype = ctypes.c_size_t
+    need = L.kvcrush_bench_mfma_operand_bytes()
+    ops = q_sample.reshape(-1).view(torch.uint8)[:need].contiguous()
+    assert ops.numel() == need, "sample too small for the calibration kernel's operands"
+    grid, iters = 512, 4096                                  # two workgroups per compute unit, about 1 ms
+    out = torch.empty(grid * 256, dtype=torch.float32, device=dev)
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    best = 0.0
+    for rep in range(6):                                     # the first launches also settle the clock
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = L.kvcrush_bench_mfma_ceiling(ops.data_ptr(), iters, grid, out.data_ptr(), st)
+        e1.record()
+        torch.cuda.synchronize()
+        if flop <= 0.0:
+            return None
+        if rep >= 2:
+            best = max(best, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer, row_begin=0, pool=0, unit=0):
@@ -352,6 +385,12 @@ def main():
     }
     if args.graph:
         out["eager_ms_per_step"] = eager_ms_per_step
+    if w.dtype == "bf16" and not args.no_mfma_ceiling:
+        # measured counterpart of the datasheet peak, taken after the timed region
+        ceil = mfma_ceiling_tflops(torch, dev, layers[0]["q"])
+        if ceil:
+            roofline["measured_mfma_only_tflops"] = ceil
+            roofline["frac_of_measured"] = achieved / ceil
     if copy_gbs is not None:
         out["plain_copy_gbs"] = copy_gbs   # the runtime's device-to-device copy of 256 MiB, read + write
     if not args.no_cpu_baseline:

@@ -279,3 +279,20 @@ def test_pipeline_classes_validate_before_touching_the_gpu(lib):
         lc = object.__new__(pipeline.LayerCompressor)      # no buffers: only the guard is exercised
         lc._graph = None
         lc.replay()
+
+
+def test_calibration_library_is_separate_from_the_product():
+    """The benchmark's calibration kernel is built into a library of its own; the product library
+    exports nothing of it."""
+    from paper_2503_00022_amd import build
+    build.ensure_built()
+    bench = ctypes.CDLL(build.BENCH_LIB_PATH)
+    assert hasattr(bench, "kvcrush_bench_mfma_ceiling") and hasattr(bench, "kvcrush_bench_mfma_operand_bytes")
+    bench.kvcrush_bench_mfma_operand_bytes.restype = ctypes.c_size_t
+    assert bench.kvcrush_bench_mfma_operand_bytes() == 64 * 1024
+    bench.kvcrush_bench_mfma_ceiling.restype = ctypes.c_double
+    bench.kvcrush_bench_mfma_ceiling.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                                 ctypes.c_void_p]
+    assert bench.kvcrush_bench_mfma_ceiling(None, 1, 1, None, None) == 0.0       # refused before any launch
+    product = binding.load()
+    assert not hasattr(product, "kvcrush_bench_mfma_ceiling")
