@@ -223,7 +223,8 @@ kvcrush_status kvcrush_select(const kvcrush_select_args* args, const float* scor
  *                 int32 holds the pool block of each logical block;
  *                 S % block_size == 0; entries must be valid pool blocks
  *                 (not checked on the device).
- *   idx     [B, budget] int32 with 0 <= idx < S (as written by kvcrush_select)
+ *   idx     [B, budget] int32 with 0 <= idx < S (as written by kvcrush_select); a value
+ *           outside that range is clamped into it, never followed out of the arrays
  *   k_out, v_out [B, Hkv, budget, D], same dtype
  *   D * sizeof(dtype) must be a multiple of 16.
  */

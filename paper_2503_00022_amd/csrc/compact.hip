@@ -50,7 +50,8 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(CompactParams 
         const long long bh = row / p.budget;
         const int h = (int)(bh % p.Hkv);
         const int b = (int)(bh / p.Hkv);
-        const int t = p.idx[(long long)b * p.budget + j];
+        // an index outside the sequence (a caller's mistake) is pulled inside rather than followed
+        const int t = min(max(p.idx[(long long)b * p.budget + j], 0), p.S - 1);
         long long src_row;
         if (p.block_table) {
           const long long blk = p.block_table[(long long)b * p.blocks_per_seq + t / p.block_size];
@@ -86,7 +87,8 @@ __global__ __launch_bounds__(kCompactThreads) void score_gather_kernel(ScoreGath
   const int row = blockIdx.y;  // b * Hs + r
   const int b = row / p.Hs;
   for (int j = blockIdx.x * kCompactThreads + threadIdx.x; j < p.budget; j += gridDim.x * kCompactThreads)
-    p.scores_out[(size_t)row * p.cap_dst + j] = p.scores[(size_t)row * p.cap_src + p.idx[(size_t)b * p.budget + j]];
+    p.scores_out[(size_t)row * p.cap_dst + j] =
+        p.scores[(size_t)row * p.cap_src + min(max(p.idx[(size_t)b * p.budget + j], 0), p.cap_src - 1)];
 }
 
 kvcrush_status launch_compact(const CompactParams& p, hipStream_t stream) {
@@ -143,7 +145,8 @@ __global__ __launch_bounds__(kCompactThreads) void block_table_gather_kernel(con
                                                                            int unit, int blocks_src) {
   const int b = blockIdx.y, kept = budget / unit;
   for (int j = blockIdx.x * kCompactThreads + threadIdx.x; j < kept; j += gridDim.x * kCompactThreads)
-    out[(size_t)b * kept + j] = block_table[(size_t)b * blocks_src + idx[(size_t)b * budget + (size_t)j * unit] / unit];
+    out[(size_t)b * kept + j] =
+        block_table[(size_t)b * blocks_src + min(max(idx[(size_t)b * budget + (size_t)j * unit] / unit, 0), blocks_src - 1)];
 }
 
 extern "C" kvcrush_status kvcrush_compact_block_table(int32_t B, int32_t S, int32_t budget,

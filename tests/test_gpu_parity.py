@@ -1121,3 +1121,26 @@ def test_ragged_batch_from_padded_buffers(kv, oracle):
         rk, rv = oracle.compact(kb, vb, ridx)
         assert torch.equal(k_out[b:b + 1].cpu().view(torch.uint8), rk.view(torch.uint8))
         assert torch.equal(v_out[b:b + 1].cpu().view(torch.uint8), rv.view(torch.uint8))
+
+
+def test_gathers_clamp_indices_outside_the_sequence(kv, oracle):
+    """An index below 0 or at/after S is pulled to the nearest token instead of being followed
+    out of the arrays (dense gather, capacity-strided gather with its scores)."""
+    say("gather with out-of-range indices: clamped, not followed")
+    B, Hkv, S, D = 2, 2, 300, 128
+    g = torch.Generator().manual_seed(4)
+    k = torch.randn(B, Hkv, S, D, generator=g).to(torch.bfloat16)
+    v = torch.randn(B, Hkv, S, D, generator=g).to(torch.bfloat16)
+    sc = torch.rand(B, Hkv, S, generator=g)
+    idx = torch.tensor([[-7, 0, 5, 299, 300, 100000], [-2 ** 31, 1, 2, 3, 2 ** 31 - 1, 298]], dtype=torch.int32)
+    good = idx.clamp(0, S - 1)
+    ko, vo = kv.kvcrush_compact(k.cuda(), v.cuda(), idx.cuda(), validate=False)
+    outs = [torch.zeros(B, Hkv, 8, D, dtype=torch.bfloat16, device="cuda"),
+            torch.zeros(B, Hkv, 8, D, dtype=torch.bfloat16, device="cuda"), torch.zeros(B, Hkv, 8, device="cuda")]
+    kv.kvcrush_compact_cache(k.cuda(), v.cuda(), sc.cuda(), idx.cuda(), *outs)
+    torch.cuda.synchronize()
+    rk, rv = oracle.compact(k, v, good)
+    assert torch.equal(ko.cpu().view(torch.uint8), rk.view(torch.uint8))
+    assert torch.equal(vo.cpu().view(torch.uint8), rv.view(torch.uint8))
+    assert torch.equal(outs[0].cpu()[:, :, :6].view(torch.uint8), rk.view(torch.uint8))
+    assert torch.equal(outs[2].cpu()[:, :, :6], torch.gather(sc, 2, good.long()[:, None, :].expand(B, Hkv, 6)))
