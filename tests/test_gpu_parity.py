@@ -1144,3 +1144,18 @@ def test_gathers_clamp_indices_outside_the_sequence(kv, oracle):
     assert torch.equal(vo.cpu().view(torch.uint8), rv.view(torch.uint8))
     assert torch.equal(outs[0].cpu()[:, :, :6].view(torch.uint8), rk.view(torch.uint8))
     assert torch.equal(outs[2].cpu()[:, :, :6], torch.gather(sc, 2, good.long()[:, None, :].expand(B, Hkv, 6)))
+
+
+@pytest.mark.parametrize("block,levels", [(64, 2), (64, 3), (128, 2), (32, 2), (1, 2)])
+def test_select_on_blocks_of_alternating_sizes(kv, oracle, block, levels):
+    """Score rows made of blocks of tokens that alternate between a few magnitudes: the first radix
+    pass then sees whole waves leave one histogram bin for another at the same key (its ballot
+    path), or lanes split over a few bins (its run-length path)."""
+    say(f"select on rows of {block}-token blocks cycling through {levels} magnitudes")
+    B, Hs, S = 2, 8, 16384
+    g = torch.Generator().manual_seed(block * 10 + levels)
+    t = torch.arange(S)
+    base = (1.0 + 7.0 * ((t // block) % levels).float())[None, None, :]
+    sc = (base * (1.0 + 1e-3 * torch.rand(B, Hs, S, generator=g))).contiguous()
+    check_select(kv, oracle, sc, 4096, 3072, 0, "mean")
+    check_select(kv, oracle, sc, 1000, 0, 6000, "alternating", n_sink=4, n_recent=60)
