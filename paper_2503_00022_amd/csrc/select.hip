@@ -230,13 +230,15 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   for (int pass = 0; pass < 3; ++pass) {
     const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
     const int bins = pass == 2 ? 1024 : 2048;
-    if (pass == 0) {
-      // First pass, every key counts.  A wave walks its own run of 64-token chunks and each lane
-      // keeps the bin of its previous key with a count: keys 64 tokens apart are mostly of similar
-      // size, so a lane adds to the histogram only when its bin changes (a few times, not once per
-      // key).  If most lanes change bin at nearly every key (blocks of tokens alternating between
-      // sizes), their additions would hit one bin all at once and be served one by one: the wave
-      // then counts the rest of its keys by ballot, as the later passes do.
+    {
+      // Counting the keys that still match the prefix (all of them in the first pass).  A wave
+      // walks its own run of 64-token chunks and each lane keeps the bin of its previous counted
+      // key with a count: keys 64 tokens apart are mostly of similar size, and equal keys share
+      // every digit, so a lane adds to the histogram only when its bin changes (a few times, not
+      // once per key).  If nearly the whole wave changes bin at nearly every key while sitting in
+      // one bin (blocks of tokens alternating between sizes), those additions would hit one
+      // address all at once and be served one by one: the wave then counts the rest of its keys
+      // by ballot (the bin of the first lane left, one add of the popcount, three rounds at most).
       int pc0, pc1;
       wave_chunk_range(nw, kSelWaves, wave, pc0, pc1);
       uint32_t run_bin = 0, run_cnt = 0;
@@ -246,15 +248,15 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int t = (cb + u) * 64 + lane;
-          kk[u] = (cb + u < pc1 && t < S) ? key_at(t) : 0xFFFFFFFFu;
+          kk[u] = (cb + u < pc1 && t < S) ? key_at(t) : 0u;
         }
         if (!by_ballot) {
           int changes = 0;
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int t = (cb + u) * 64 + lane;
-            const uint32_t bin = kk[u] >> shift;
-            if (cb + u < pc1 && t < S) {
+            const uint32_t bin = (kk[u] >> shift) & (uint32_t)(bins - 1);
+            if (cb + u < pc1 && t < S && (kk[u] & known) == prefix) {
               if (bin == run_bin) {
                 ++run_cnt;
               } else {
@@ -265,8 +267,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
               }
             }
           }
-          // (nearly the whole wave changing bin at nearly every key and sitting in one bin right now;
-          // additions spread over two or three bins are still cheaper singly)
+          // (additions spread over two or three bins are still cheaper singly)
           const uint32_t first_bin = (uint32_t)__builtin_amdgcn_readfirstlane((int)run_bin);
           by_ballot = __popcll((unsigned long long)__ballot(changes >= 3 && run_bin == first_bin)) >= 56;
           if (by_ballot) {
@@ -277,8 +278,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int t = (cb + u) * 64 + lane;
-            bool todo = cb + u < pc1 && t < S;
-            const uint32_t bin = kk[u] >> shift;
+            bool todo = cb + u < pc1 && t < S && (kk[u] & known) == prefix;
+            const uint32_t bin = (kk[u] >> shift) & (uint32_t)(bins - 1);
 #pragma unroll
             for (int round = 0; round < 3; ++round) {
               const uint64_t left = __ballot(todo);
@@ -295,36 +296,6 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
         }
       }
       if (run_cnt) atomicAdd(&hist[run_bin], run_cnt);
-    } else {
-      for (int t0 = tid; t0 < S; t0 += kBatch * kSelThreads) {
-        uint32_t kk[kBatch];
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          const int t = t0 + u * kSelThreads;
-          kk[u] = t < S ? key_at(t) : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          const int t = t0 + u * kSelThreads;
-          bool todo = t < S && (kk[u] & known) == prefix;
-          const uint32_t bin = (kk[u] >> shift) & (uint32_t)(bins - 1);
-          // Scores of similar size share their leading bits, so most lanes of a wave want the
-          // same bin and their atomics would be served one by one: the bins of a few lanes are
-          // counted by ballot first, whoever is left (many distinct bins, no such pile-up) adds singly.
-#pragma unroll
-          for (int round = 0; round < 3; ++round) {
-            const uint64_t left = __ballot(todo);
-            if (left == 0) break;
-            const uint32_t lead = (uint32_t)__shfl((int)bin, __ffsll((unsigned long long)left) - 1);
-            const uint64_t same = __ballot(todo && bin == lead);
-            if (todo && bin == lead) {
-              if ((same & lanemask_lt()) == 0) atomicAdd(&hist[lead], (uint32_t)__popcll(same));
-              todo = false;
-            }
-          }
-          if (todo) atomicAdd(&hist[bin], 1u);
-        }
-      }
     }
     __syncthreads();
     // thread i owns bins (bins-1 - per*i) downwards; `above` = keys with a larger digit
