@@ -160,8 +160,66 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   const size_t ld = (size_t)p.ld;
 
   for (int i = tid; i < kRadixBins; i += kSelThreads) hist[i] = 0;
-  // keys: kBatch tokens per thread at a time so that their loads overlap
-  for (int t0 = tid; t0 < S_tok; t0 += kBatch * kSelThreads) {
+  // keys.  Rows that start on a 16-byte boundary are read four tokens a load (the importance row
+  // moves Hs times a row's bytes through this one compute unit: wide loads are what it is bound by)
+  int t_done = 0;
+  if (((reinterpret_cast<uintptr_t>(sc) | (ld * sizeof(float))) & 15) == 0) {
+    constexpr int kQuads = 2;  // independent quads per thread and row
+    const int n4 = S_tok >> 2;
+    for (int g0 = tid; g0 < n4; g0 += kQuads * kSelThreads) {
+      float4 v[kQuads];
+      auto quad = [&](int r, int u) {
+        const int g = g0 + u * kSelThreads;
+        return g < n4 ? *(const float4*)(sc + (size_t)r * ld + 4 * (size_t)g) : make_float4(0.f, 0.f, 0.f, 0.f);
+      };
+      if (row < Hs) {
+#pragma unroll
+        for (int u = 0; u < kQuads; ++u) v[u] = quad(row, u);
+      } else {
+#pragma unroll
+        for (int u = 0; u < kQuads; ++u) v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        int r = 0;
+        for (; r + 8 <= Hs; r += 8) {  // eight rows' loads in flight; the additions stay in row order
+          float4 x[8][kQuads];
+#pragma unroll
+          for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+            for (int u = 0; u < kQuads; ++u) x[rr][u] = quad(r + rr, u);
+#pragma unroll
+          for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+            for (int u = 0; u < kQuads; ++u) {
+              v[u].x = v[u].x + x[rr][u].x;
+              v[u].y = v[u].y + x[rr][u].y;
+              v[u].z = v[u].z + x[rr][u].z;
+              v[u].w = v[u].w + x[rr][u].w;
+            }
+        }
+        for (; r < Hs; ++r) {
+#pragma unroll
+          for (int u = 0; u < kQuads; ++u) {
+            const float4 x = quad(r, u);
+            v[u].x = v[u].x + x.x;
+            v[u].y = v[u].y + x.y;
+            v[u].z = v[u].z + x.z;
+            v[u].w = v[u].w + x.w;
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kQuads; ++u) {
+        const int g = g0 + u * kSelThreads;
+        if (g < n4) {
+          const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) key_put(4 * g + j, unit_row ? __float_as_uint(e[j]) : float_key(e[j]));
+        }
+      }
+    }
+    t_done = 4 * n4;
+  }
+  // the rest (or everything, for rows that are not aligned): kBatch tokens per thread at a time
+  for (int t0 = t_done + tid; t0 < S_tok; t0 += kBatch * kSelThreads) {
     float v[kBatch];
     if (row < Hs) {
 #pragma unroll
