@@ -511,12 +511,11 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
   }
   for (int c = tid; c < wg_nc; c += kGsThreads) p.repmask[(size_t)b * nw + wg_c0 + c] = 0ull;
   for (int i = tid; i < kGsWaves * (WMAX * 64 + 1); i += kGsThreads) (&run[0][0])[i] = 0;
-  for (int i = tid; i < WMAX * 64; i += kGsThreads) head_cnt[i] = 0;
-  __syncthreads();
-
   // ---- anchor (Alg. 2, first step); every workgroup derives the same one
   if (p.anchor_mode == KVCRUSH_ANCHOR_MEAN) {
-    // bit r set in more than half of the grouped tokens?  counts over the whole sequence
+    // bit r set in more than half of the grouped tokens?  counts over the whole sequence (these
+    // loads share their latency with the staging loads above; head_cnt[r], r < Hs, is written here
+    // and read only after the barrier)
     const uint64_t* __restrict__ imp = rm + (size_t)Hs * nw;
     for (int r = wave; r < Hs; r += kGsWaves) {
       int cnt = 0;
@@ -524,8 +523,8 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
       cnt = wave_sum(cnt);
       if (lane == 0) head_cnt[r] = cnt;
     }
-    __syncthreads();
   }
+  __syncthreads();
   if (tid < W) {
     uint64_t a = 0;
     if (p.anchor_mode == KVCRUSH_ANCHOR_RANDOM) {
