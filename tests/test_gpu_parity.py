@@ -470,10 +470,11 @@ def test_scores_deterministic(kv):
 
 
 # -------------------------------------------------------- whole path, configs
-def run_pipeline(kv, oracle, w, cfg_id, layer, check_groups):
+def run_pipeline(kv, oracle, w, cfg_id, layer, check_groups, whole=False):
     """GPU runs the full configuration; the oracle checks the score rows in
-    `check_groups` (list of (b, row)) plus the whole selection and compaction,
-    the latter two on the GPU's own score tensor."""
+    `check_groups` (list of (b, row); whole=True: every row, in one oracle call that
+    keeps all host cores busy) plus the whole selection and compaction, the latter
+    two on the GPU's own score tensor."""
     seed = inputs.layer_seed(cfg_id, layer)
     q, k, v = inputs.make_qkv(w, seed)
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
@@ -490,7 +491,13 @@ def run_pipeline(kv, oracle, w, cfg_id, layer, check_groups):
     torch.cuda.synchronize()
     sc_h = sc.cpu()
     G = w.Hq // w.Hkv
-    # stage 1: sampled rows against the oracle, invariant on all rows
+    # stage 1: rows against the oracle, invariant on all rows
+    if whole:
+        ref = oracle.scores(q, k, w.reduce_groups, threads=THREADS)
+        err = rel_err(sc_h, ref)
+        say(f"  cfg{cfg_id} layer {layer}: score rel err over all {w.B * w.Hs} rows {err:.3e}")
+        assert err <= SCORE_RTOL
+        check_groups = []
     for (b, row) in check_groups:
         if w.reduce_groups:
             ref = oracle.scores(q[b:b + 1, row * G:(row + 1) * G], k[b:b + 1, row:row + 1], True, threads=THREADS)
@@ -533,23 +540,31 @@ def test_config2_full(kv, oracle):
     run_pipeline(kv, oracle, w, 2, 0, [])
 
 
+def all_rows(w):
+    return [(b, r) for b in range(w.B) for r in range(w.Hs)]
+
+
 @pytest.mark.slow
-@pytest.mark.parametrize("layer,rows", [(0, [0, 5]), (31, [7])])
-def test_config3_layers(kv, oracle, layer, rows):
-    say(f"config 3 layer {layer}: score rows {rows} against the oracle, selection and gather in full")
-    run_pipeline(kv, oracle, inputs.CONFIGS[3], 3, layer, [(0, r) for r in rows])
+@pytest.mark.parametrize("layer", [0, 15, 31])
+def test_config3_layers(kv, oracle, layer):
+    say(f"config 3 layer {layer}: every score row against the oracle, selection and gather in full")
+    w = inputs.CONFIGS[3]
+    run_pipeline(kv, oracle, w, 3, layer, all_rows(w), whole=True)
 
 
 @pytest.mark.slow
 def test_config4_batched(kv, oracle):
-    say("config 4: B=8, sampled (sequence, group) rows against the oracle")
-    run_pipeline(kv, oracle, inputs.CONFIGS[4], 4, 0, [(0, 0), (3, 5), (7, 7)])
+    say("config 4: B=8, every (sequence, group) row against the oracle")
+    w = inputs.CONFIGS[4]
+    run_pipeline(kv, oracle, w, 4, 0, all_rows(w), whole=True)
 
 
 @pytest.mark.slow
-def test_config5_long_paged(kv, oracle):
-    say("config 5: S=32768, paged gather, one score row against the oracle")
-    run_pipeline(kv, oracle, inputs.CONFIGS[5], 5, 0, [(0, 3)])
+@pytest.mark.parametrize("layer,rows", [(0, None), (15, [3]), (31, [6])])
+def test_config5_long_paged(kv, oracle, layer, rows):
+    say(f"config 5 layer {layer}: S=32768, paged gather, score rows {rows or 'all'} against the oracle")
+    w = inputs.CONFIGS[5]
+    run_pipeline(kv, oracle, w, 5, layer, all_rows(w) if rows is None else [(0, r) for r in rows], whole=rows is None)
 
 
 # ------------------------------------------------------------------ decoding
