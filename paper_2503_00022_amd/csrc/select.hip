@@ -387,30 +387,48 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   wave_chunk_range(nw, kSelWaves, wave, c0, c1);
   int eq_before = 0;
   const bool ties = count_eq != remaining;  // uniform over the workgroup
+  // (chunks are taken four at a time so that their key reads overlap)
   if (ties) {
     int mine = 0;
-    for (int c = c0; c < c1; ++c) {
-      const int t = c * 64 + lane;
-      mine += (t < S && key_at(t) == T) ? 1 : 0;
+    for (int cb = c0; cb < c1; cb += 4) {
+      uint32_t kk[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = (cb + u) * 64 + lane;
+        kk[u] = (cb + u < c1 && t < S) ? key_at(t) : ~T;  // ~T never equals T
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) mine += kk[u] == T ? 1 : 0;
     }
     mine = wave_sum(mine);
     if (lane == 0) wave_tot[wave] = mine;
     __syncthreads();
     for (int w = 0; w < wave; ++w) eq_before += wave_tot[w];
   }
-  for (int c = c0; c < c1; ++c) {
-    const int t = c * 64 + lane;
-    const uint32_t key = t < S ? key_at(t) : 0u;
-    bool sel = t < S && key >= T;
-    if (ties) {
-      const bool eq = t < S && key == T;
-      const uint64_t m = __ballot(eq);
-      const int rank = eq_before + __popcll(m & lanemask_lt());
-      if (eq) sel = rank < (int)remaining;
-      eq_before += __popcll(m);
+  for (int cb = c0; cb < c1; cb += 4) {
+    uint32_t kk[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = (cb + u) * 64 + lane;
+      kk[u] = (cb + u < c1 && t < S) ? key_at(t) : 0u;
     }
-    const uint64_t word = __ballot(sel);
-    if (lane == 0) mask_out[c] = word;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = cb + u;
+      if (c >= c1) break;  // uniform
+      const int t = c * 64 + lane;
+      const uint32_t key = kk[u];
+      bool sel = t < S && key >= T;
+      if (ties) {
+        const bool eq = t < S && key == T;
+        const uint64_t m = __ballot(eq);
+        const int rank = eq_before + __popcll(m & lanemask_lt());
+        if (eq) sel = rank < (int)remaining;
+        eq_before += __popcll(m);
+      }
+      const uint64_t word = __ballot(sel);
+      if (lane == 0) mask_out[c] = word;
+    }
   }
 }
 
