@@ -98,6 +98,7 @@ struct TopkParams {
   int Hs, S, nw, kbit, n_important;  // S = selectable tokens per row (the middle, when ends are protected)
   int ld;               // row stride of `scores` in floats (the full sequence length)
   int unit;             // tokens per selection unit; the importance row then ranks S / unit units
+  int importance_only;  // 1: no representatives and no bit words are wanted, the per-row masks are skipped
 };
 
 // Block-wide exclusive prefix sum of one int per thread, in thread order.
@@ -138,6 +139,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_mask_kernel(TopkParams p) {
   const int nw = unit_row ? (S + 63) / 64 : p.nw;
   const int k = row < Hs ? p.kbit : p.n_important;
   uint64_t* __restrict__ mask_out = p.rowmask + ((size_t)b * (Hs + 1) + row) * p.nw;
+  if (p.importance_only && row < Hs) return;  // (whole workgroup, before any barrier)
 
   if (k == 0 || k == S) {  // nothing or everything: no search needed
     for (int c = tid; c < nw; c += kSelThreads) {
@@ -810,7 +812,7 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
   __shared__ int sh_base[kSelThreads];
   const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
   const uint64_t* imp = p.impmask_base + (size_t)b * p.imp_stride;
-  const uint64_t* rep = p.repmask + (size_t)b * p.nw;
+  const uint64_t* rep = p.repmask ? p.repmask + (size_t)b * p.nw : nullptr;  // null: no representatives
   int32_t* idx_out = p.idx + (size_t)b * p.budget_full;
   uint8_t* kind_out = p.kind ? p.kind + (size_t)b * p.budget_full : nullptr;
   for (int i = tid; i < p.n_sink + p.n_recent; i += kSelThreads) {
@@ -830,7 +832,7 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
     const int c = w0 + tid;
     uint64_t rw = 0, kept = 0;
     if (c < p.nw) {
-      rw = rep[c];
+      rw = rep ? rep[c] : 0ull;
       kept = imp[c] | rw;
     }
     const int cnt = __popcll(kept);
@@ -971,9 +973,10 @@ kvcrush_status launch_grouping(const GroupParams& g, const MedoidParams& m, cons
                             (int)dyn_b) != hipSuccess)
       return KVCRUSH_ERR_HIP;
   }
+  if (Br == 0) return KVCRUSH_OK;  // the rank order only serves the representatives
   hipLaunchKernelGGL(group_scatter_kernel<CPW>, dim3(P.n_wg, B), dim3(kGsThreads), dyn_b, stream, g);
   if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-  if (Br > 0) {
+  {
     if (WMAX > 2 && Br <= 65535)
       hipLaunchKernelGGL(medoid_wide_kernel<WMAX>, dim3(Br, B), dim3(kMedoidThreads), 0, stream, m);
     else
@@ -1021,6 +1024,9 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
   uint64_t* bits_buf = !bits ? (uint64_t*)(ws + P.bits) : (token_level ? bits + (size_t)args->n_sink * P.W : bits);
   const size_t bits_stride = (bits && token_level) ? (size_t)S_full : (size_t)P.n_items;
 
+  // Plain top-n (no representative budget, token level, bit words not asked for): only the importance
+  // row is ranked and the grouping kernels have nothing to do.
+  const bool plain_topk = Br == 0 && token_level && bits == nullptr;
   if (P.n_items > 0) {
     TopkParams p;
     p.scores = scores + args->n_sink;
@@ -1033,6 +1039,7 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
     p.nw = P.nw_tok;
     p.kbit = kbit;
     p.n_important = P.imp_items;
+    p.importance_only = plain_topk ? 1 : 0;
     const size_t dyn = P.keys_in_lds ? (size_t)P.S_tok * 4 : 0;
     if (dyn > 48 * 1024) {
       if (hipFuncSetAttribute((const void*)topk_mask_kernel<true>,
@@ -1059,7 +1066,7 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
     hipLaunchKernelGGL(unit_rows_kernel, dim3(gx, B), dim3(256), 0, stream, p);
     if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   }
-  if (P.n_items > 0) {
+  if (P.n_items > 0 && !plain_topk) {
     GroupParams g;
     g.rowmask = rowmask;
     g.bits = bits_buf;
@@ -1105,7 +1112,7 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
   if (args->budget > 0) {
     EmitParams p;
     p.impmask_base = rowmask + (size_t)P.Hv * P.nw;
-    p.repmask = repmask;
+    p.repmask = plain_topk ? nullptr : repmask;
     p.idx = idx;
     p.kind = kind;
     p.imp_stride = (size_t)(P.Hv + 1) * P.nw;

@@ -1174,3 +1174,20 @@ def test_select_on_blocks_of_alternating_sizes(kv, oracle, block, levels):
     sc = (base * (1.0 + 1e-3 * torch.rand(B, Hs, S, generator=g))).contiguous()
     check_select(kv, oracle, sc, 4096, 3072, 0, "mean")
     check_select(kv, oracle, sc, 1000, 0, 6000, "alternating", n_sink=4, n_recent=60)
+
+
+@pytest.mark.parametrize("B,Hs,S,budget,sink,recent", [(1, 8, 16384, 4096, 0, 0), (3, 4, 1000, 333, 4, 16), (2, 100, 700, 1, 0, 0),
+                                                       (1, 8, 500, 500, 0, 0), (2, 8, 300, 48, 16, 32)])
+def test_select_plain_topk_without_representatives(kv, oracle, B, Hs, S, budget, sink, recent):
+    """The whole budget given to the important tokens (the baseline's own selection, Sec. 3 first
+    paragraph): only the importance row is ranked.  With and without the bit words asked for."""
+    say(f"plain top-n B={B} Hs={Hs} S={S} budget={budget} sink={sink} recent={recent}")
+    sc = inputs.make_scores(B, Hs, S, seed=S + budget, ties=True)
+    n_imp = budget - sink - recent
+    ridx, rkind, rbits = oracle.select(sc, budget, n_imp, 0, "mean", 1, n_sink=sink, n_recent=recent)
+    idx, kind, _ = kv.kvcrush_select(sc.cuda(), budget, n_imp, 0, "mean", 1, n_sink=sink, n_recent=recent)
+    idx2, kind2, bits2 = kv.kvcrush_select(sc.cuda(), budget, n_imp, 0, "mean", 1, n_sink=sink, n_recent=recent,
+                                           want_bits=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx.cpu(), ridx) and torch.equal(kind.cpu(), rkind)
+    assert torch.equal(idx2.cpu(), ridx) and torch.equal(kind2.cpu(), rkind) and torch.equal(bits2.cpu(), rbits)
