@@ -57,6 +57,9 @@ def parse():
                          "replays; stage times still come from the eager pass")
     ap.add_argument("--cache-len", type=int, default=0, help="--decode: valid tokens per cache (0: the workload's budget)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="also time the steps on two streams (a layer's selection beside the next layer's scores) "
+                         "and report that as ms_per_step; stage times stay those of the one-stream run")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the MFMA-only calibration launch that follows the timed region")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -335,6 +338,52 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) * 1e3 / (replays * n_layers)
+    if args.overlap:
+        # the same steps on two streams: layer L's selection and gather (a few compute units, bound by
+        # latency) run beside layer L+1's score kernels; the scores are double-buffered between them
+        s_sel = torch.cuda.Stream()
+        sc2 = [scores, torch.empty_like(scores)]
+        ready = [torch.cuda.Event() for _ in range(2)]
+        done = [torch.cuda.Event() for _ in range(2)]
+        main = torch.cuda.current_stream()
+
+        def step2(i):
+            L, j = i % n_layers, i % 2
+            ent = layers[L]
+            if i >= 2:
+                main.wait_event(done[j])          # the selection two steps back has read this buffer
+            if not args.lse_supplied:
+                kv.kvcrush_row_lse(ent["q"], ent["k"], lse_out=lse, window=W, workspace=lse_ws)
+            kv.kvcrush_scores(ent["q"], ent["k"], w.reduce_groups, lse=ent["lse"] if args.lse_supplied else lse,
+                              scores=sc2[j], window=W, workspace=sc_ws)
+            ready[j].record(main)
+            with torch.cuda.stream(s_sel):
+                s_sel.wait_event(ready[j])
+                src = sc2[j]
+                if pooled is not None:
+                    src = kv.kvcrush_pool_scores(sc2[j], args.pool, out=pooled)
+                kv.kvcrush_select(src, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(L), want_kind=False,
+                                  idx=idx, workspace=sel_ws, unit=args.unit)
+                if w.paged:
+                    kv.kvcrush_compact(ent["kp"], ent["vp"], idx, block_table=ent["bt"], block_size=w.block_size,
+                                       dense_shape=(w.B, w.Hkv, w.S, w.D), k_out=k_out, v_out=v_out, validate=False)
+                else:
+                    kv.kvcrush_compact(ent["k"], ent["v"], idx, k_out=k_out, v_out=v_out, validate=False)
+                done[j].record(s_sel)
+
+        for i in range(max(args.warmup, 2)):
+            step2(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step2(i)
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        # the last overlapped step against the same layer run on one stream
+        idx_two = idx.clone()
+        step(args.steps - 1)
+        torch.cuda.synchronize()
+        overlap_ok = bool(torch.equal(idx_two, idx))
     stage = [sum(e[j].elapsed_time(e[j + 1]) for e in evs) / args.steps for j in range(4)]  # ms
     t_lse, t_col, t_sel, t_cmp = stage
     med = [sorted(e[j].elapsed_time(e[j + 1]) for e in evs)[len(evs) // 2] for j in range(4)]
@@ -380,11 +429,13 @@ def main():
                    "budget": w.budget, "n_important": w.n_important, "n_representative": w.n_rep,
                    "anchor": w.anchor, "reduce_groups": w.reduce_groups, "paged": w.paged,
                    "resident_layers": n_layers, "obs_window": W, "pool_kernel": args.pool, "unit": args.unit, "lse_supplied": args.lse_supplied,
-                   "launch": "hip_graph" if args.graph else "eager"},
+                   "launch": "hip_graph" if args.graph else ("eager, two streams" if args.overlap else "eager")},
         "roofline": roofline, "stages": stages, "row_sum_check": ok,
     }
-    if args.graph:
-        out["eager_ms_per_step"] = eager_ms_per_step
+    if args.graph or args.overlap:
+        out["eager_ms_per_step"] = eager_ms_per_step   # one stream, one launch after the other
+    if args.overlap:
+        out["overlap_check"] = overlap_ok
     if w.dtype == "bf16" and not args.no_mfma_ceiling:
         # measured counterpart of the datasheet peak, taken after the timed region
         ceil = mfma_ceiling_tflops(torch, dev, layers[0]["q"])
