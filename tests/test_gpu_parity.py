@@ -577,6 +577,23 @@ def test_config5_long_paged(kv, oracle, layer, rows):
     run_pipeline(kv, oracle, w, 5, layer, rows if isinstance(rows, range) else [(0, r) for r in rows])
 
 
+LAYER_GROUPS = [range(g, g + 4) for g in range(0, 32, 4)]
+
+
+@pytest.mark.slow
+@pytest.mark.parametrize("cfg_id", [3, 5])
+@pytest.mark.parametrize("layers", LAYER_GROUPS, ids=lambda r: f"layers{r.start}-{r.stop - 1}")
+def test_every_layer_of_the_32_layer_configs(kv, oracle, cfg_id, layers):
+    """Configs 3 and 5 are 32 layers with seeds of their own.  On every layer: each score row
+    totals the number of query rows it sums (times the group size) and is positive; selection and
+    gather (paged for config 5) on the GPU's own scores are bit-exact against the oracle.  (The
+    oracle's score pass, minutes per layer, runs on layers 0, 15 and 31 in the tests above.)"""
+    w = inputs.CONFIGS[cfg_id]
+    for layer in layers:
+        say(f"config {cfg_id} layer {layer}: row totals, selection and gather")
+        run_pipeline(kv, oracle, w, cfg_id, layer, [])
+
+
 # ------------------------------------------------------------------ decoding
 @pytest.mark.parametrize("B,Hq,Hkv,S,cap,D,dtype,rg", [
     (2, 8, 2, 300, 320, 128, "bf16", True),

@@ -61,6 +61,38 @@ def test_append_is_one_library_softmax_row(oracle):
     assert torch.allclose(scg.double(), wantg, rtol=2e-7)
 
 
+def test_append_with_a_caller_scale_is_the_library_softmax_at_that_scale(oracle):
+    """`scale` replaces 1/sqrt(D) as the factor on q . k (models with an attention scale of their own;
+    zero-padded heads scored with 1/sqrt(true size)).  Pinned by a float64 library softmax at that
+    scale, by scale = 1/sqrt(D) being the default spelled out, and by padding: a head zero-padded
+    from 24 to 32 values with scale 1/sqrt(24) scores as the 24-value head does by default."""
+    B, Hq, Hkv, D, S, cap = 2, 4, 2, 24, 37, 40
+    g = torch.Generator().manual_seed(8)
+    qn = torch.randn(B, Hq, D, generator=g)
+    kc = torch.randn(B, Hkv, cap, D, generator=g)
+    old = torch.rand(B, Hq, cap, generator=g)
+    dots = torch.einsum("bhd,bhsd->bhs", qn.double(), kc[:, :, :S].double().repeat_interleave(2, dim=1))
+    for scale in (0.37, 1.0, 1.0 / math.sqrt(D)):
+        sc = old.clone()
+        oracle.scores_append(qn, kc, sc, S, False, scale=scale)
+        p = torch.softmax(dots * scale, dim=-1)
+        want = old.clone().double()
+        want[:, :, :S - 1] += p[:, :, :S - 1]
+        want[:, :, S - 1] = p[:, :, S - 1]
+        assert torch.allclose(sc.double(), want, rtol=2e-7), f"scale {scale}"
+        assert torch.equal(sc[:, :, S:], old[:, :, S:])
+    default = oracle.scores_append(qn, kc, old.clone(), S, False)
+    spelled = oracle.scores_append(qn, kc, old.clone(), S, False, scale=1.0 / math.sqrt(D))
+    assert torch.equal(default, spelled)
+    # a different scale really gives different probabilities (the argument is not ignored)
+    other = oracle.scores_append(qn, kc, old.clone(), S, False, scale=0.37)
+    assert not torch.allclose(other, default, rtol=1e-3)
+    qp = torch.zeros(B, Hq, 32); qp[..., :D] = qn
+    kp = torch.zeros(B, Hkv, cap, 32); kp[..., :D] = kc
+    padded = oracle.scores_append(qp, kp, old.clone(), S, False, scale=1.0 / math.sqrt(D))
+    assert torch.allclose(padded, default, rtol=1e-6)
+
+
 def test_append_first_token(oracle):
     """S = 1: the only key gets probability one from every head."""
     qn = torch.randn(1, 4, 8, generator=torch.Generator().manual_seed(1))

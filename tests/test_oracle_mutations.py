@@ -52,6 +52,9 @@ MUTATIONS = [
      "tests/test_oracle_select.py::test_unit_level_hand_worked_example"),
     ("append adds to the new slot", "(j == S - 1 ? 0.0 : (double)row[j])", "((double)row[j])",
      "tests/test_oracle_decode.py::test_append_is_one_library_softmax_row"),
+    ("append ignores the caller's scale", "const double inv_sqrt_d = scale != 0.0 ? scale : 1.0 / std::sqrt((double)D);\n  std::vector<double> logit(S), add(S);",
+     "const double inv_sqrt_d = 1.0 / std::sqrt((double)D);\n  std::vector<double> logit(S), add(S);",
+     "tests/test_oracle_decode.py::test_append_with_a_caller_scale_is_the_library_softmax_at_that_scale"),
     ("gather ignores the head", "const size_t src = (((size_t)b * Hkv + h) * cap_src + t) * row;",
      "const size_t src = (((size_t)b * Hkv + 0) * cap_src + t) * row;",
      "tests/test_oracle_decode.py::test_compact_cache_is_a_strided_gather"),
