@@ -213,6 +213,24 @@ kvcrush_status kvcrush_select(const kvcrush_select_args* args, const float* scor
                               uint8_t* kind, uint64_t* bits, void* workspace,
                               size_t workspace_bytes, void* hip_stream);
 
+/* kvcrush_select for callers that cannot allocate device memory and therefore have
+ * no workspace to pass: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Identical arguments and results; the scratch
+ * memory is a fixed array of KVCRUSH_SELECT_STATIC_MAX_BYTES inside the library's
+ * device image (every GPU the library runs on holds one until the process ends).
+ * The call allocates and frees nothing.  The first call on a device looks up the
+ * array's address (do that first call outside a capture).
+ *   - KVCRUSH_ERR_WORKSPACE when the problem needs more scratch than the array
+ *     holds, i.e. when kvcrush_select_workspace(args) exceeds
+ *     KVCRUSH_SELECT_STATIC_MAX_BYTES; nothing is enqueued then.
+ *   - All calls on one GPU share the array: calls that overlap in time on one GPU
+ *     (different streams, different host threads) race.  Calls on one stream, or
+ *     otherwise ordered, are safe; nothing needs clearing between them. */
+#define KVCRUSH_SELECT_STATIC_MAX_BYTES (4u << 20)
+kvcrush_status kvcrush_select_static(const kvcrush_select_args* args, const float* scores,
+                                     int32_t* idx, uint8_t* kind, uint64_t* bits,
+                                     void* hip_stream);
+
 /* ---------------------------------------------------------------- stage 5 --
  * k_out[b, h, j, :] = K[b, h, idx[b, j], :], same for V (Sec. 3.2: the
  * retained tokens form the final cache).  Pure copy, bit exact.

@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 EXPORTS = (
     "kvcrush_scores_workspace", "kvcrush_scores", "kvcrush_row_lse_workspace", "kvcrush_row_lse",
     "kvcrush_pool_scores",
-    "kvcrush_select_workspace", "kvcrush_select", "kvcrush_compact", "kvcrush_scores_append_workspace",
+    "kvcrush_select_workspace", "kvcrush_select", "kvcrush_select_static", "kvcrush_compact", "kvcrush_scores_append_workspace",
     "kvcrush_scores_append", "kvcrush_compact_cache", "kvcrush_compact_block_table", "kvcrush_status_string",
     "kvcrush_version",
 )
@@ -73,6 +73,8 @@ def load() -> ctypes.CDLL:
         L.kvcrush_select_workspace.restype = sz
         L.kvcrush_select.argtypes = [ctypes.POINTER(SelectArgs), vp, vp, vp, vp, vp, sz, vp]
         L.kvcrush_select.restype = ctypes.c_int
+        L.kvcrush_select_static.argtypes = [ctypes.POINTER(SelectArgs), vp, vp, vp, vp, vp]
+        L.kvcrush_select_static.restype = ctypes.c_int
         L.kvcrush_compact.argtypes = [i32] * 6 + [vp, vp, vp, vp, i32, vp, vp, vp]
         L.kvcrush_compact.restype = ctypes.c_int
         L.kvcrush_scores_append_workspace.argtypes = [ctypes.POINTER(Shape), i32]
@@ -259,6 +261,19 @@ def kvcrush_select(scores, budget, n_important, bit_topk=0, anchor="alternating"
     st = load().kvcrush_select(ctypes.byref(args), _ptr(scores), _ptr(idx), _ptr(kind), _ptr(bits),
                                _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "kvcrush_select")
+    return idx, kind, bits
+
+
+SELECT_STATIC_MAX_BYTES = 4 << 20   # KVCRUSH_SELECT_STATIC_MAX_BYTES
+
+
+def kvcrush_select_static(args: SelectArgs, scores, idx, kind=None, bits=None, stream=None):
+    """kvcrush_select on the library's own fixed scratch array: every buffer is the caller's, nothing
+    is allocated here or in the library.  args from make_select_args; idx int32 [B,budget], kind uint8
+    [B,budget] or None, bits int64 or None, all preallocated on the GPU."""
+    st = load().kvcrush_select_static(ctypes.byref(args), _ptr(_dev(scores, "scores")), _ptr(_dev(idx, "idx")),
+                                      _ptr(kind), _ptr(bits), _stream(stream))
+    _check(st, "kvcrush_select_static")
     return idx, kind, bits
 
 

@@ -33,6 +33,7 @@
 // the 64-bit words per vector (up to 16 = 1024 bits), with a workgroup-per-bucket
 // K3 for the long vectors, whose buckets are few and large.
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 
@@ -995,10 +996,63 @@ extern "C" size_t kvcrush_select_workspace(const kvcrush_select_args* args) {
   return select_plan(args, true).total;
 }
 
+namespace {
+kvcrush_status select_run(const kvcrush_select_args* args, const float* scores, int32_t* idx,
+                          uint8_t* kind, uint64_t* bits, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+}  // namespace
+
 extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const float* scores,
                                          int32_t* idx, uint8_t* kind, uint64_t* bits,
                                          void* workspace, size_t workspace_bytes,
                                          void* hip_stream) {
+  return select_run(args, scores, idx, kind, bits, workspace, workspace_bytes, hip_stream);
+}
+
+// ---------------------------------------------- selection without a workspace --
+// For callers that cannot allocate (code under HIP graph capture, tight serving
+// loops): the same kernels on a scratch array that is part of the library's
+// device image.  Host code may not use the array's name as an address; the
+// device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[KVCRUSH_SELECT_STATIC_MAX_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex static_scratch_mutex;
+void* static_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of `scratch` (each GPU holds its own), or null.
+void* static_scratch_for_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(static_scratch_mutex);
+  if (!static_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    static_scratch_ptr[dev] = ptr;
+  }
+  return static_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" kvcrush_status kvcrush_select_static(const kvcrush_select_args* args, const float* scores,
+                                                int32_t* idx, uint8_t* kind, uint64_t* bits,
+                                                void* hip_stream) {
+  if (!select_args_ok(args)) return KVCRUSH_ERR_INVALID_ARG;
+  if (!select_args_supported(args)) return KVCRUSH_ERR_UNSUPPORTED;
+  // (every buffer of the workspace is written before it is read inside one call, so the
+  // previous call's contents need no clearing)
+  if (select_plan(args, bits == nullptr).total > (size_t)KVCRUSH_SELECT_STATIC_MAX_BYTES)
+    return KVCRUSH_ERR_WORKSPACE;
+  void* ptr = static_scratch_for_current_device();
+  if (!ptr) return KVCRUSH_ERR_HIP;
+  return select_run(args, scores, idx, kind, bits, ptr, (size_t)KVCRUSH_SELECT_STATIC_MAX_BYTES, hip_stream);
+}
+
+namespace {
+kvcrush_status select_run(const kvcrush_select_args* args, const float* scores, int32_t* idx,
+                          uint8_t* kind, uint64_t* bits, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
   if (!select_args_ok(args)) return KVCRUSH_ERR_INVALID_ARG;
   if (!select_args_supported(args)) return KVCRUSH_ERR_UNSUPPORTED;
   if (!scores || (!idx && args->budget > 0)) return KVCRUSH_ERR_INVALID_ARG;
@@ -1131,3 +1185,4 @@ extern "C" kvcrush_status kvcrush_select(const kvcrush_select_args* args, const 
   }
   return KVCRUSH_OK;
 }
+}  // namespace
