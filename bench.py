@@ -63,7 +63,12 @@ def parse():
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the MFMA-only calibration launch that follows the timed region")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
+                    help="(kept for the profiling commands: the 256 MiB device copies that serve as the reference "
+                         "for the HBM byte counters are always run now)")
+    ap.add_argument("--per-head-bits", action="store_true",
+                    help="one score row (one bit of the vector) per query head instead of per KV group")
+    ap.add_argument("--quick", action="store_true",
+                    help="only the main workload's eager run: no HIP-graph figure, no short runs of the other workloads")
     return ap.parse_args()
 
 
@@ -207,6 +212,229 @@ def run_decode(args, torch, kv, inputs, dev):
     print(json.dumps(out), flush=True)
 
 
+def copy_ceiling_gbs(torch, dev):
+    """Measured counterpart of the HBM datasheet peak: the runtime's own device-to-device copy of
+    256 MiB (read + write), 10 copies timed."""
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    return 10 * 2.0 * (256 << 20) / (c0.elapsed_time(c1) * 1e-3) / 1e9
+
+
+class Run:
+    """One workload resident in HBM with its buffers; step(i) enqueues one layer's compression."""
+
+    def __init__(self, torch, kv, inputs, dev, cfg_id, w, n_layers, args):
+        self.torch, self.kv, self.inputs, self.w, self.args, self.n_layers = torch, kv, inputs, w, args, n_layers
+        Hs = w.Hs
+        self.layers = []
+        for L in range(n_layers):
+            q, k, v = inputs.make_qkv(w, inputs.layer_seed(cfg_id, L), device=dev)
+            ent = {"q": q, "k": k, "v": v}
+            if w.paged:
+                bt = inputs.make_block_table(w, inputs.layer_seed(cfg_id, L))
+                ent["bt"] = bt.to(dev)
+                ent["kp"] = inputs.to_paged(k, bt, w.block_size)
+                ent["vp"] = inputs.to_paged(v, bt, w.block_size)
+            self.layers.append(ent)
+        torch.cuda.synchronize()
+        self.W = args.window if 0 < args.window < w.S else 0
+        self.q_first = w.S - self.W if self.W else 0
+        self.pooled = torch.empty(w.B, Hs, w.S, dtype=torch.float32, device=dev) if args.pool else None
+        self.lse = torch.empty(w.B, w.Hq, w.S, dtype=torch.float32, device=dev)
+        shape = kv.make_shape(self.layers[0]["q"], self.layers[0]["k"], w.reduce_groups, self.W)
+        self.lse_ws = torch.empty(max(kv.kvcrush_row_lse_workspace(shape), 16), dtype=torch.uint8, device=dev)
+        self.sc_ws = torch.empty(max(kv.kvcrush_scores_workspace(shape), 16), dtype=torch.uint8, device=dev)
+        self.scores = torch.empty(w.B, Hs, w.S, dtype=torch.float32, device=dev)
+        self.idx = torch.empty(w.B, w.budget, dtype=torch.int32, device=dev)
+        self.sel_ws = torch.empty(kv.kvcrush_select_workspace(
+            kv.make_select_args(w.B, Hs, w.S, w.budget, w.n_important, unit=args.unit)), dtype=torch.uint8, device=dev)
+        self.k_out = torch.empty(w.B, w.Hkv, w.budget, w.D, dtype=w.torch_dtype, device=dev)
+        self.v_out = torch.empty_like(self.k_out)
+        if args.lse_supplied:
+            for ent in self.layers:
+                ent["lse"] = kv.kvcrush_row_lse(ent["q"], ent["k"], window=self.W, workspace=self.lse_ws)
+            torch.cuda.synchronize()
+
+    def select_and_gather(self, L, scores, ev=None):
+        kv, w, args, ent = self.kv, self.w, self.args, self.layers[L]
+        src = scores
+        if self.pooled is not None:
+            src = kv.kvcrush_pool_scores(scores, args.pool, out=self.pooled)
+        kv.kvcrush_select(src, w.budget, w.n_important, 0, w.anchor, self.inputs.anchor_seed(L), want_kind=False,
+                          idx=self.idx, workspace=self.sel_ws, unit=args.unit)
+        if ev:
+            ev.record()
+        if w.paged:
+            kv.kvcrush_compact(ent["kp"], ent["vp"], self.idx, block_table=ent["bt"], block_size=w.block_size,
+                               dense_shape=(w.B, w.Hkv, w.S, w.D), k_out=self.k_out, v_out=self.v_out, validate=False)
+        else:
+            kv.kvcrush_compact(ent["k"], ent["v"], self.idx, k_out=self.k_out, v_out=self.v_out, validate=False)
+
+    def timed(self, steps, warmup):
+        """`warmup` untimed steps, then `steps` timed ones on one stream with HIP events between the
+        stages.  Returns wall ms per step and the per-stage event times (lists of ms)."""
+        torch = self.torch
+        for i in range(warmup):
+            self.step_with_events(i, None)
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step_with_events(warmup + i, evs[i])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall * 1e3 / steps, [[e[j].elapsed_time(e[j + 1]) for e in evs] for j in range(4)]
+
+    def step_with_events(self, i, ev):
+        kv, w, args = self.kv, self.w, self.args
+        L = i % self.n_layers
+        ent = self.layers[L]
+        if ev:
+            ev[0].record()
+        if not args.lse_supplied:
+            kv.kvcrush_row_lse(ent["q"], ent["k"], lse_out=self.lse, window=self.W, workspace=self.lse_ws)
+        if ev:
+            ev[1].record()
+        kv.kvcrush_scores(ent["q"], ent["k"], w.reduce_groups, lse=ent["lse"] if args.lse_supplied else self.lse,
+                          scores=self.scores, window=self.W, workspace=self.sc_ws)
+        if ev:
+            ev[2].record()
+        self.select_and_gather(L, self.scores, ev[3] if ev else None)
+        if ev:
+            ev[4].record()
+
+    def graph_ms_per_step(self, steps):
+        """The same steps, one per resident layer, captured once in a HIP graph and replayed."""
+        torch = self.torch
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(self.n_layers):
+                    self.step_with_events(i, None)
+        torch.cuda.synchronize()
+        replays = max(1, steps // self.n_layers)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / (replays * self.n_layers)
+
+    def overlap_ms_per_step(self, steps, warmup):
+        """The same steps on two streams: layer L's selection and gather (a few compute units, bound by
+        latency) run beside layer L+1's score kernels; the scores are double-buffered between them."""
+        torch, kv, w, args = self.torch, self.kv, self.w, self.args
+        s_sel = torch.cuda.Stream()
+        sc2 = [self.scores, torch.empty_like(self.scores)]
+        ready = [torch.cuda.Event() for _ in range(2)]
+        done = [torch.cuda.Event() for _ in range(2)]
+        main = torch.cuda.current_stream()
+
+        def step2(i):
+            L, j = i % self.n_layers, i % 2
+            ent = self.layers[L]
+            if i >= 2:
+                main.wait_event(done[j])          # the selection two steps back has read this buffer
+            if not args.lse_supplied:
+                kv.kvcrush_row_lse(ent["q"], ent["k"], lse_out=self.lse, window=self.W, workspace=self.lse_ws)
+            kv.kvcrush_scores(ent["q"], ent["k"], w.reduce_groups, lse=ent["lse"] if args.lse_supplied else self.lse,
+                              scores=sc2[j], window=self.W, workspace=self.sc_ws)
+            ready[j].record(main)
+            with torch.cuda.stream(s_sel):
+                s_sel.wait_event(ready[j])
+                self.select_and_gather(L, sc2[j])
+                done[j].record(s_sel)
+
+        for i in range(max(warmup, 2)):
+            step2(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step2(i)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        idx_two = self.idx.clone()                # the last overlapped step against the same layer on one stream
+        self.step_with_events(steps - 1, None)
+        torch.cuda.synchronize()
+        return ms, bool(torch.equal(idx_two, self.idx))
+
+    def figures(self, ms_per_step, stage_ms):
+        """Per-stage rates from the algorithmic work (what the method must compute or move, not what a
+        kernel happens to do) and the event times."""
+        w, args = self.w, self.args
+        t_lse, t_col, t_sel, t_cmp = [sum(x) / len(x) for x in stage_ms]
+        med = [sorted(x)[len(x) // 2] for x in stage_ms]
+        q_first = self.q_first
+        pairs = w.S * (w.S + 1) // 2 - q_first * (q_first + 1) // 2   # causal (query, key) pairs per head
+        flop_pass = 2.0 * w.D * pairs * w.Hq * w.B                    # one sweep of Q K^T
+        esz = 2 if w.dtype in ("bf16", "f16") else 4
+        bytes_sel = 4.0 * w.Hs * w.S * w.B + 4.0 * w.budget * w.B
+        bytes_cmp = 2.0 * 2.0 * w.B * w.Hkv * w.budget * w.D * esz + 4.0 * w.budget * w.B
+        n_sweeps = 1 if args.lse_supplied else 2
+        peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 157.3
+        t_scores = (t_lse + t_col) if not args.lse_supplied else t_col
+        stages = {
+            "lse_ms": t_lse, "colsum_ms": t_col, "select_ms": t_sel, "compact_ms": t_cmp,
+            "scores_tflops": n_sweeps * flop_pass / (t_scores * 1e-3) / 1e12,
+            "scores_frac_of_mfma_peak": n_sweeps * flop_pass / (t_scores * 1e-3) / 1e12 / peak,
+            "select_compact_gbs": (bytes_sel + bytes_cmp) / ((t_sel + t_cmp) * 1e-3) / 1e9,
+            "select_compact_frac_of_hbm_peak": (bytes_sel + bytes_cmp) / ((t_sel + t_cmp) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "compact_gbs": bytes_cmp / (t_cmp * 1e-3) / 1e9,
+            "median_ms": {"lse": med[0], "colsum": med[1], "select": med[2], "compact": med[3]},
+        }
+        return stages, flop_pass, peak
+
+    def row_sum_check(self):
+        """Cheap sanity check of the last step's scores: every row totals (group size) x query rows."""
+        torch, w = self.torch, self.w
+        tot = self.scores.double().sum(-1)
+        want = float((w.Hq // w.Hkv if w.reduce_groups else 1) * (w.S - self.q_first))
+        return bool(torch.allclose(tot, torch.full_like(tot, want), rtol=1e-4))
+
+    def config(self, launch):
+        w, args = self.w, self.args
+        return {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "S": w.S, "D": w.D,
+                "budget": w.budget, "n_important": w.n_important, "n_representative": w.n_rep,
+                "anchor": w.anchor, "reduce_groups": w.reduce_groups, "paged": w.paged,
+                "resident_layers": self.n_layers, "obs_window": self.W, "pool_kernel": args.pool, "unit": args.unit,
+                "lse_supplied": args.lse_supplied, "launch": launch}
+
+
+def other_configs(torch, kv, inputs, dev, args, headline_id):
+    """Short timed runs of the other workloads (a few steps each, two or three resident layers), so that
+    one driver run shows every configuration; the headline figure stays the main workload's."""
+    import dataclasses
+    rows = []
+    todo = [(c, inputs.CONFIGS[c], f"cfg{c}") for c in (1, 2, 3, 4, 5) if c != headline_id]
+    # one bit per query head at full GQA size (Sec. 4.3.3 counts 32 bits per token for a Llama-3-8B layer)
+    todo.append((3, dataclasses.replace(inputs.CONFIGS[3], name="cfg3_per_query_head_bits", reduce_groups=False),
+                 "cfg3 with one score row per query head"))
+    for cfg_id, w, label in todo:
+        n_layers = 3 if w.B * w.S <= 16384 else 2
+        run = Run(torch, kv, inputs, dev, cfg_id, w, n_layers, args)
+        steps = 6
+        ms, stage_ms = run.timed(steps, 2)
+        stages, _, _ = run.figures(ms, stage_ms)
+        rows.append({"workload": w.name, "note": label, "steps": steps, "resident_layers": n_layers, "dtype": w.dtype,
+                     "ms_per_step": ms, "tokens_per_s": w.B * w.S / (ms * 1e-3),
+                     "scores_frac_of_mfma_peak": stages["scores_frac_of_mfma_peak"], "lse_ms": stages["lse_ms"],
+                     "colsum_ms": stages["colsum_ms"], "select_ms": stages["select_ms"],
+                     "compact_ms": stages["compact_ms"], "compact_gbs": stages["compact_gbs"],
+                     "row_sum_check": run.row_sum_check()})
+        del run
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -229,227 +457,73 @@ def main():
     if args.decode:
         return run_decode(args, torch, kv, inputs, dev)
     w = inputs.CONFIGS[args.config]
+    if args.per_head_bits:
+        import dataclasses
+        w = dataclasses.replace(w, name=w.name + "_per_query_head_bits", reduce_groups=False)
     n_layers = args.layers or min(w.layers, 32)
     # a single-layer workload still rotates over a few copies so that repeats miss the cache
     if w.layers == 1 and not args.layers:
         n_layers = 4
-    G = w.Hq // w.Hkv
-    Hs = w.Hs
 
-    layers = []
-    for L in range(n_layers):
-        q, k, v = inputs.make_qkv(w, inputs.layer_seed(args.config, L), device=dev)
-        ent = {"q": q, "k": k, "v": v}
-        if w.paged:
-            bt = inputs.make_block_table(w, inputs.layer_seed(args.config, L))
-            ent["bt"] = bt.to(dev)
-            ent["kp"] = inputs.to_paged(k, bt, w.block_size)
-            ent["vp"] = inputs.to_paged(v, bt, w.block_size)
-        layers.append(ent)
-    torch.cuda.synchronize()
-
-    W = args.window if 0 < args.window < w.S else 0
-    q_first = w.S - W if W else 0
-    pooled = torch.empty(w.B, Hs, w.S, dtype=torch.float32, device=dev) if args.pool else None
-    lse = torch.empty(w.B, w.Hq, w.S, dtype=torch.float32, device=dev)
-    shape = kv.make_shape(layers[0]["q"], layers[0]["k"], w.reduce_groups, W)
-    lse_ws = torch.empty(max(kv.kvcrush_row_lse_workspace(shape), 16), dtype=torch.uint8, device=dev)
-    sc_ws = torch.empty(max(kv.kvcrush_scores_workspace(shape), 16), dtype=torch.uint8, device=dev)
-    scores = torch.empty(w.B, Hs, w.S, dtype=torch.float32, device=dev)
-    idx = torch.empty(w.B, w.budget, dtype=torch.int32, device=dev)
-    sel_ws = torch.empty(kv.kvcrush_select_workspace(
-        kv.make_select_args(w.B, Hs, w.S, w.budget, w.n_important, unit=args.unit)), dtype=torch.uint8, device=dev)
-    k_out = torch.empty(w.B, w.Hkv, w.budget, w.D, dtype=w.torch_dtype, device=dev)
-    v_out = torch.empty_like(k_out)
-
-    if args.lse_supplied:
-        for ent in layers:
-            ent["lse"] = kv.kvcrush_row_lse(ent["q"], ent["k"], window=W, workspace=lse_ws)
-        torch.cuda.synchronize()
-
-    def step(i, ev=None):
-        L = i % n_layers
-        ent = layers[L]
-        if ev:
-            ev[0].record()
-        if not args.lse_supplied:
-            kv.kvcrush_row_lse(ent["q"], ent["k"], lse_out=lse, window=W, workspace=lse_ws)
-        if ev:
-            ev[1].record()
-        kv.kvcrush_scores(ent["q"], ent["k"], w.reduce_groups, lse=ent["lse"] if args.lse_supplied else lse,
-                          scores=scores, window=W, workspace=sc_ws)
-        if ev:
-            ev[2].record()
-        if pooled is not None:
-            kv.kvcrush_pool_scores(scores, args.pool, out=pooled)
-        kv.kvcrush_select(scores if pooled is None else pooled, w.budget, w.n_important, 0, w.anchor,
-                          inputs.anchor_seed(L), want_kind=False, idx=idx, workspace=sel_ws, unit=args.unit)
-        if ev:
-            ev[3].record()
-        if w.paged:
-            kv.kvcrush_compact(ent["kp"], ent["vp"], idx, block_table=ent["bt"], block_size=w.block_size,
-                               dense_shape=(w.B, w.Hkv, w.S, w.D), k_out=k_out, v_out=v_out, validate=False)
-        else:
-            kv.kvcrush_compact(ent["k"], ent["v"], idx, k_out=k_out, v_out=v_out, validate=False)
-        if ev:
-            ev[4].record()
-
-    copy_gbs = None
-    if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
-        dst = torch.empty_like(src)
-        dst.copy_(src)       # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        c0.record()
-        for _ in range(10):
-            dst.copy_(src)
-        c1.record()
-        torch.cuda.synchronize()
-        copy_gbs = 10 * 2.0 * (256 << 20) / (c0.elapsed_time(c1) * 1e-3) / 1e9   # read + write
-        del src, dst
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, evs[i])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    ms_per_step = wall * 1e3 / args.steps
+    copy_gbs = copy_ceiling_gbs(torch, dev)
+    run = Run(torch, kv, inputs, dev, args.config, w, n_layers, args)
+    ms_per_step, stage_ms = run.timed(args.steps, args.warmup)      # the headline: eager, one stream
     eager_ms_per_step = ms_per_step
+    launch = "eager"
+    graph_ms = None
+    if args.graph or not args.quick:
+        graph_ms = run.graph_ms_per_step(args.steps)
     if args.graph:
-        # the same steps, one per resident layer, captured once and replayed: launch cost off the host
-        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(n_layers):
-                    step(i)
-        torch.cuda.synchronize()
-        replays = max(1, args.steps // n_layers)
-        graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(replays):
-            graph.replay()
-        torch.cuda.synchronize()
-        ms_per_step = (time.perf_counter() - t0) * 1e3 / (replays * n_layers)
+        ms_per_step, launch = graph_ms, "hip_graph"
     if args.overlap:
-        # the same steps on two streams: layer L's selection and gather (a few compute units, bound by
-        # latency) run beside layer L+1's score kernels; the scores are double-buffered between them
-        s_sel = torch.cuda.Stream()
-        sc2 = [scores, torch.empty_like(scores)]
-        ready = [torch.cuda.Event() for _ in range(2)]
-        done = [torch.cuda.Event() for _ in range(2)]
-        main = torch.cuda.current_stream()
-
-        def step2(i):
-            L, j = i % n_layers, i % 2
-            ent = layers[L]
-            if i >= 2:
-                main.wait_event(done[j])          # the selection two steps back has read this buffer
-            if not args.lse_supplied:
-                kv.kvcrush_row_lse(ent["q"], ent["k"], lse_out=lse, window=W, workspace=lse_ws)
-            kv.kvcrush_scores(ent["q"], ent["k"], w.reduce_groups, lse=ent["lse"] if args.lse_supplied else lse,
-                              scores=sc2[j], window=W, workspace=sc_ws)
-            ready[j].record(main)
-            with torch.cuda.stream(s_sel):
-                s_sel.wait_event(ready[j])
-                src = sc2[j]
-                if pooled is not None:
-                    src = kv.kvcrush_pool_scores(sc2[j], args.pool, out=pooled)
-                kv.kvcrush_select(src, w.budget, w.n_important, 0, w.anchor, inputs.anchor_seed(L), want_kind=False,
-                                  idx=idx, workspace=sel_ws, unit=args.unit)
-                if w.paged:
-                    kv.kvcrush_compact(ent["kp"], ent["vp"], idx, block_table=ent["bt"], block_size=w.block_size,
-                                       dense_shape=(w.B, w.Hkv, w.S, w.D), k_out=k_out, v_out=v_out, validate=False)
-                else:
-                    kv.kvcrush_compact(ent["k"], ent["v"], idx, k_out=k_out, v_out=v_out, validate=False)
-                done[j].record(s_sel)
-
-        for i in range(max(args.warmup, 2)):
-            step2(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            step2(i)
-        torch.cuda.synchronize()
-        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-        # the last overlapped step against the same layer run on one stream
-        idx_two = idx.clone()
-        step(args.steps - 1)
-        torch.cuda.synchronize()
-        overlap_ok = bool(torch.equal(idx_two, idx))
-    stage = [sum(e[j].elapsed_time(e[j + 1]) for e in evs) / args.steps for j in range(4)]  # ms
-    t_lse, t_col, t_sel, t_cmp = stage
-    med = [sorted(e[j].elapsed_time(e[j + 1]) for e in evs)[len(evs) // 2] for j in range(4)]
-    tokens = w.B * w.S
-
-    # algorithmic work (what the method must compute / move, not what a kernel happens to do)
-    pairs = w.S * (w.S + 1) // 2 - q_first * (q_first + 1) // 2   # causal (query, key) pairs per head
-    flop_pass = 2.0 * w.D * pairs * w.Hq * w.B                    # one sweep of Q K^T
-    esz = 2 if w.dtype == "bf16" else 4
-    bytes_sel = 4.0 * Hs * w.S * w.B + 4.0 * w.budget * w.B
-    bytes_cmp = 2.0 * 2.0 * w.B * w.Hkv * w.budget * w.D * esz + 4.0 * w.budget * w.B
+        ms_per_step, overlap_ok = run.overlap_ms_per_step(args.steps, args.warmup)
+        launch = "eager, two streams"
+    stages, flop_pass, peak = run.figures(ms_per_step, stage_ms)
+    t_lse, t_col = stages["lse_ms"], stages["colsum_ms"]
+    # (the events bracket the library call: pass B's time includes its 4 us partial-sum reduction)
     dom_name, dom_ms = ("colsum_kernel", t_col) if t_col >= t_lse else ("lse_kernel", t_lse)
-    n_sweeps = 1 if args.lse_supplied else 2
     achieved = flop_pass / (dom_ms * 1e-3) / 1e12
-    peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 157.3
-    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom_name)) if not W else None
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, dom_name)) if not run.W else None
     roofline = {
         "bound": "mfma", "kernel": dom_name, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
         "frac": achieved / peak, "traffic": traffic,
         "flop_per_launch": flop_pass, "avg_launch_ms": dom_ms,
     }
-    stages = {
-        "lse_ms": t_lse, "colsum_ms": t_col, "select_ms": t_sel, "compact_ms": t_cmp,
-        "scores_tflops": n_sweeps * flop_pass / ((t_lse + t_col) * 1e-3) / 1e12,
-        "scores_frac_of_mfma_peak": n_sweeps * flop_pass / ((t_lse + t_col) * 1e-3) / 1e12 / peak,
-        "select_compact_gbs": (bytes_sel + bytes_cmp) / ((t_sel + t_cmp) * 1e-3) / 1e9,
-        "select_compact_frac_of_hbm_peak": (bytes_sel + bytes_cmp) / ((t_sel + t_cmp) * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "compact_gbs": bytes_cmp / (t_cmp * 1e-3) / 1e9,
-        "median_ms": {"lse": med[0], "colsum": med[1], "select": med[2], "compact": med[3]},
-    }
+    stages["select_compact_frac_of_measured_copy"] = stages["select_compact_gbs"] / copy_gbs
+    stages["compact_frac_of_hbm_peak"] = stages["compact_gbs"] / HBM_PEAK_GBS
+    stages["compact_frac_of_measured_copy"] = stages["compact_gbs"] / copy_gbs
 
-    # cheap sanity check of the last step's scores: every row totals (group size) x S
-    tot = scores.double().sum(-1)
-    want = float((G if w.reduce_groups else 1) * (w.S - q_first))
-    ok = bool(torch.allclose(tot, torch.full_like(tot, want), rtol=1e-4))
-
+    tokens = w.B * w.S
     out = {
         "metric": "kv_compressed_tokens_per_sec_per_layer", "value": tokens / (ms_per_step * 1e-3),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "S": w.S, "D": w.D,
-                   "budget": w.budget, "n_important": w.n_important, "n_representative": w.n_rep,
-                   "anchor": w.anchor, "reduce_groups": w.reduce_groups, "paged": w.paged,
-                   "resident_layers": n_layers, "obs_window": W, "pool_kernel": args.pool, "unit": args.unit, "lse_supplied": args.lse_supplied,
-                   "launch": "hip_graph" if args.graph else ("eager, two streams" if args.overlap else "eager")},
-        "roofline": roofline, "stages": stages, "row_sum_check": ok,
+        "dtype": w.dtype, "data": "synthetic", "config": run.config(launch),
+        "roofline": roofline, "stages": stages, "row_sum_check": run.row_sum_check(),
+        "plain_copy_gbs": copy_gbs,   # the runtime's device-to-device copy of 256 MiB, read + write
     }
+    if graph_ms is not None:
+        out["graph_ms_per_step"] = graph_ms          # the same steps replayed from a HIP graph (informational)
     if args.graph or args.overlap:
         out["eager_ms_per_step"] = eager_ms_per_step   # one stream, one launch after the other
     if args.overlap:
         out["overlap_check"] = overlap_ok
     if w.dtype == "bf16" and not args.no_mfma_ceiling:
-        # measured counterpart of the datasheet peak, taken after the timed region
-        ceil = mfma_ceiling_tflops(torch, dev, layers[0]["q"])
+        # measured counterparts of the datasheet peak, taken after the timed region
+        ceil = mfma_ceiling_tflops(torch, dev, run.layers[0]["q"])
         if ceil:
             roofline["measured_mfma_only_tflops"] = ceil
             roofline["frac_of_measured"] = achieved / ceil
-    if copy_gbs is not None:
-        out["plain_copy_gbs"] = copy_gbs   # the runtime's device-to-device copy of 256 MiB, read + write
     if not args.no_cpu_baseline:
         # layer 0 again, so that its scores are the ones handed to the oracle's selection
-        step(0)
+        run.step_with_events(0, None)
         torch.cuda.synchronize()
-        out["cpu_baseline"] = cpu_baseline(w, layers[0]["q"], layers[0]["k"], layers[0]["v"], scores, 0,
-                                           q_first, args.pool, args.unit)
+        out["cpu_baseline"] = cpu_baseline(w, run.layers[0]["q"], run.layers[0]["k"], run.layers[0]["v"],
+                                           run.scores, 0, run.q_first, args.pool, args.unit)
+    if not args.quick and not (args.window or args.pool or args.unit or args.lse_supplied):
+        del run
+        torch.cuda.empty_cache()
+        out["configs"] = other_configs(torch, kv, inputs, dev, args, None if args.per_head_bits else args.config)
     print(json.dumps(out), flush=True)
 
 

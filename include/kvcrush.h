@@ -21,14 +21,25 @@
  *     nothing; scratch memory is passed in as `workspace` whose size the
  *     matching *_workspace() function returns.  Pointers must be 16-byte
  *     aligned.
- *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*;
- *     NULL is the default stream) and return without synchronising.  Outputs
- *     are complete when the stream reaches the end of the enqueued work.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*)
+ *     and return without synchronising.  Outputs are complete when the stream
+ *     reaches the end of the enqueued work.  NULL names the legacy default
+ *     stream, as it does in every HIP call; the library itself never picks a
+ *     stream, so pass your own to stay off the default one.
  *   - Errors are return codes.  Arguments are validated on the host before
- *     anything is launched; on an error nothing has been enqueued.
+ *     anything is launched: INVALID_ARG, UNSUPPORTED and WORKSPACE mean that
+ *     nothing has been enqueued.  KVCRUSH_ERR_HIP means that the runtime
+ *     refused a launch or a query of THIS call; earlier kernels of the same
+ *     call may already be enqueued and the outputs are then unspecified.
  *   - Size limits of the launches (KVCRUSH_ERR_UNSUPPORTED beyond them):
  *     B * Hq <= 65535 and B * Hq * ceil(S / 64) <= 2^30 in the score calls,
- *     B <= 65535 in kvcrush_select, B * Hs <= 65535 where scores are gathered.
+ *     B <= 65535 in kvcrush_select and in the gathers (kvcrush_compact,
+ *     kvcrush_compact_cache), Hkv + Hs <= 65535 in kvcrush_compact_cache.
+ *     kvcrush_select keeps a table of (V + 1) x ceil(n / 1024) x 4 counters in
+ *     the LDS of a workgroup, V = Hs * unit bits per vector, n = (S - n_sink -
+ *     n_recent) / unit items: at most 30720 counters (Hs = 8: about 870 000
+ *     tokens; Hs = 128: about 60 000).  kvcrush_select_workspace returns 0 and
+ *     kvcrush_select KVCRUSH_ERR_UNSUPPORTED beyond that.
  *     Offsets inside the arrays are 64-bit: the arrays themselves may exceed
  *     4 GiB.
  *   - Inputs are assumed finite.  NaN scores give an unspecified (but memory

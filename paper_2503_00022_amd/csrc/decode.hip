@@ -345,17 +345,17 @@ bool append_shape_ok(const kvcrush_shape* s, int capacity) {
 
 template <bool BF16, int D, bool F16 = false>
 kvcrush_status launch_append(const AppendParams& p, hipStream_t stream) {
+  kvcrush_status st;
   if constexpr (BF16) {
-    hipLaunchKernelGGL((append_logits_mfma_kernel<D, kMfmaTilesPerWg, F16>), dim3(p.n_kb, p.B * p.Hkv),
+    st = kvc::launch(append_logits_mfma_kernel<D, kMfmaTilesPerWg, F16>, dim3(p.n_kb, p.B * p.Hkv),
                        dim3(kThreads), 0, stream, p);
   } else {
-    hipLaunchKernelGGL((append_logits_kernel<BF16, D>), dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
+    st = kvc::launch(append_logits_kernel<BF16, D>, dim3(p.n_kb, p.B * p.Hkv), dim3(kThreads), 0, stream, p);
   }
-  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+  if (st != KVCRUSH_OK) return st;
   const int Hs = p.reduce_groups ? p.Hkv : p.Hq;
-  hipLaunchKernelGGL(append_update_kernel, dim3((p.S + kKeysPerWg - 1) / kKeysPerWg, p.B * Hs), dim3(kThreads), 0,
+  return kvc::launch(append_update_kernel, dim3((p.S + kKeysPerWg - 1) / kKeysPerWg, p.B * Hs), dim3(kThreads), 0,
                      stream, p);
-  return kvc::launch_status();
 }
 
 }  // namespace

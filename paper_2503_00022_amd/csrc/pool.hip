@@ -57,7 +57,6 @@ extern "C" kvcrush_status kvcrush_pool_scores(int32_t rows, int32_t S, int32_t k
   if (a < b + bytes && b < a + bytes) return KVCRUSH_ERR_INVALID_ARG;  // overlapping arrays
   const int segs = (S + kSegment - 1) / kSegment;
   if ((long long)rows * segs > 0x7FFFFFFFll) return KVCRUSH_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(pool_kernel, dim3((unsigned)((long long)rows * segs)), dim3(kPoolThreads), 0,
+  return kvc::launch(pool_kernel, dim3((unsigned)((long long)rows * segs)), dim3(kPoolThreads), 0,
                      (hipStream_t)hip_stream, in, out, S, kernel / 2, segs);
-  return kvc::launch_status();
 }

@@ -726,16 +726,10 @@ kvcrush_status launch_lse(const ScoreParams& base, float2* split_ml, hipStream_t
   a.split_ml = split_ml;
   if ((long long)pl.launched * pl.n_split * pl.n_bh > kMaxGridX) return KVCRUSH_ERR_UNSUPPORTED;
   const dim3 grid((unsigned)(pl.launched * pl.n_split * pl.n_bh));
-  if (a.strided)
-    hipLaunchKernelGGL((lse_kernel<BF16, D, F16, true>), grid, dim3(kThreads), 0, stream, a);
-  else
-    hipLaunchKernelGGL((lse_kernel<BF16, D, F16, false>), grid, dim3(kThreads), 0, stream, a);
-  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-  if (pl.n_split > 1) {
-    hipLaunchKernelGGL(lse_combine_kernel, dim3((pl.split_rows + 3) / 4, a.B * a.Hq), dim3(256), 0, stream, a);
-    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-  }
-  return KVCRUSH_OK;
+  const kvcrush_status st = a.strided ? kvc::launch(lse_kernel<BF16, D, F16, true>, grid, dim3(kThreads), 0, stream, a)
+                                      : kvc::launch(lse_kernel<BF16, D, F16, false>, grid, dim3(kThreads), 0, stream, a);
+  if (st != KVCRUSH_OK || pl.n_split <= 1) return st;
+  return kvc::launch(lse_combine_kernel, dim3((pl.split_rows + 3) / 4, a.B * a.Hq), dim3(256), 0, stream, a);
 }
 
 template <bool BF16, int D, bool F16 = false>
@@ -757,19 +751,13 @@ kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, flo
   p.chunk_tiles = pl.chunk_tiles;
   p.n_bh = p.B * (p.reduce_groups ? p.Hkv : p.Hq);
   const dim3 grid((unsigned)(pl.pieces * p.n_bh));
-  if (p.strided)
-    hipLaunchKernelGGL((colsum_kernel<BF16, D, F16, true>), grid, dim3(kThreads), 0, stream, p,
-                       lse_user ? lse_user : p.lse);
-  else
-    hipLaunchKernelGGL((colsum_kernel<BF16, D, F16, false>), grid, dim3(kThreads), 0, stream, p,
-                       lse_user ? lse_user : p.lse);
-  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-  if (pl.n_chunks > 1) {
-    hipLaunchKernelGGL(colsum_reduce_kernel, dim3(pl.n_kb, p.n_bh), dim3(kKeysPerWg), 0, stream, p,
-                       kKeysPerWg / C::kTile);
-    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-  }
-  return KVCRUSH_OK;
+  const float* lse_in = lse_user ? lse_user : p.lse;
+  const kvcrush_status st =
+      p.strided ? kvc::launch(colsum_kernel<BF16, D, F16, true>, grid, dim3(kThreads), 0, stream, p, lse_in)
+                : kvc::launch(colsum_kernel<BF16, D, F16, false>, grid, dim3(kThreads), 0, stream, p, lse_in);
+  if (st != KVCRUSH_OK || pl.n_chunks <= 1) return st;
+  return kvc::launch(colsum_reduce_kernel, dim3(pl.n_kb, p.n_bh), dim3(kKeysPerWg), 0, stream, p,
+                     kKeysPerWg / C::kTile);
 }
 
 // First query row that contributes to the scores.

@@ -55,20 +55,22 @@ __device__ __forceinline__ uint32_t float_key(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (no LDS
+// round trips): shifts by 1, 2, 4 and 8 lanes inside each row of 16 lanes (lanes shifted in
+// from outside a row read zero), then lane 15 of rows 0 and 2 added to rows 1 and 3, then
+// lane 31 added to rows 2 and 3.
 __device__ __forceinline__ int wave_incl_scan(int v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int off = 1; off < KVC_WAVE; off <<= 1) {
-    const int o = __shfl_up(v, off);
-    if (lane >= off) v += o;
-  }
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
   return v;
 }
 
 __device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int off = KVC_WAVE / 2; off > 0; off >>= 1) v += __shfl_xor(v, off);
-  return v;
+  return __builtin_amdgcn_readlane(wave_incl_scan(v), KVC_WAVE - 1);
 }
 
 // Lanes of the wave that hold the same small integer d (only `nbits` low bits
@@ -91,6 +93,35 @@ __device__ __forceinline__ void wave_chunk_range(int nw, int nwaves, int wave, i
   c1 = min(nw, c0 + per);
 }
 
+// Words that one workgroup writes and another reads inside the same launch (row bitmaps,
+// representative bitmaps) go through agent-scope accesses: such a store is written through to
+// the point where all compute units see it, such a load is served from there.  (Full release /
+// acquire fences would also do, but they write back and invalidate whole caches, tens of
+// microseconds when every workgroup of a launch issues them.)
+__device__ __forceinline__ void store_shared_word(uint64_t* p, uint64_t v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t load_shared_word(const uint64_t* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Arrival of a workgroup at a counter that `expected` workgroups add to; true (for the whole
+// workgroup) in the one that arrives last.  Every word that later readers need must have been
+// written with store_shared_word (or an atomic): each thread waits here until its own vector
+// memory operations have been acknowledged (vmcnt counts stores and atomics on this target),
+// and only then does the workgroup's arrival become visible.  Contains barriers.
+__device__ __forceinline__ bool arrive_last(uint32_t* counter, uint32_t expected, uint32_t* sh_flag) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0)
+    *sh_flag = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1u;
+  __syncthreads();
+  const bool last = *sh_flag != 0u;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+  return last;
+}
+
 // ------------------------------------------------------------------ K1 ----
 struct TopkParams {
   const float* scores;  // first selectable token of row 0 of sequence 0; rows are `ld` floats apart
@@ -105,12 +136,13 @@ struct TopkParams {
 // Block-wide exclusive prefix sum of one int per thread, in thread order.
 // `wave_tot` is LDS scratch of kSelWaves ints; contains two barriers.
 __device__ __forceinline__ int block_excl_scan(int v, int* wave_tot) {
-  const int lane = lane_id(), wave = threadIdx.x / KVC_WAVE;
+  const int lane = lane_id(), wave = threadIdx.x / KVC_WAVE, n_waves = blockDim.x / KVC_WAVE;
   const int incl = wave_incl_scan(v);
   if (lane == KVC_WAVE - 1) wave_tot[wave] = incl;
   __syncthreads();
-  int before = 0;
-  for (int w = 0; w < wave; ++w) before += wave_tot[w];
+  // (at most 16 waves: every wave scans the waves' totals itself, one per lane)
+  const int tot_scan = wave_incl_scan(lane < n_waves ? wave_tot[lane] : 0);
+  const int before = __shfl(tot_scan - (lane < n_waves ? wave_tot[lane] : 0), wave);
   __syncthreads();
   return before + incl - v;
 }
@@ -486,6 +518,11 @@ constexpr int kGsWaves = kGsThreads / KVC_WAVE;
 constexpr int kGsChunksPerWg = 16;  // 64-item chunks a workgroup takes (4 for long bit vectors, whose
                                     // per-item work is large and whose item counts are small)
 constexpr uint32_t kNotGrouped = 0xFFFFFFFFu;
+// Internal anchor mode: the mean anchor when no bit can reach a majority.  A bit is set in at
+// most bit_topk items, so with 2 * bit_topk <= N (the usual case: the kept share of a row is
+// well under half) the strict-majority anchor is all zeros and the per-row counts over the
+// whole sequence need not be taken.
+constexpr int kAnchorZero = 100;
 constexpr int kDistBits = 12;  // distances range over 0..kMaxHs
 
 struct GroupParams {
@@ -555,10 +592,10 @@ __global__ __launch_bounds__(kGsThreads) void group_rank_kernel(GroupParams p) {
       a = 0xAAAAAAAAAAAAAAAAull;
     } else if (p.anchor_mode == KVCRUSH_ANCHOR_EXPLICIT) {
       a = p.anchor_bits[(size_t)b * W + tid];
-    } else {
+    } else if (p.anchor_mode == KVCRUSH_ANCHOR_MEAN) {
       for (int r = tid * 64; r < min(Hs, tid * 64 + 64); ++r)
         if (2ll * head_cnt[r] > (long long)p.N) a |= 1ull << (r - tid * 64);
-    }
+    }  // (kAnchorZero: stays zero)
     const int live = Hs - tid * 64;  // meaningful bits in this word
     if (live < 64) a &= (1ull << live) - 1ull;
     sh_anchor[tid] = a;
@@ -807,16 +844,28 @@ struct EmitParams {
   int unit;              // tokens per selected item: every kept item expands to `unit` indices
 };
 
-__global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
-  __shared__ int wave_tot[kSelWaves];
-  __shared__ uint64_t sh_kept[kSelThreads], sh_rep[kSelThreads];
-  __shared__ int sh_base[kSelThreads];
-  const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
+// The list of one sequence, written by one workgroup of NT threads: one bitmap word per
+// thread, a prefix sum of the words' population counts, then the waves take the words in turn
+// and the lanes whose bit is set write their item at its place, so that the stores of a wave
+// go to consecutive entries.  Contains barriers: every thread of the workgroup calls it.
+constexpr int kEmitTile = 1024;  // bitmap words handled per round (at most one per thread)
+struct EmitScratch {             // LDS
+  uint64_t kept[kEmitTile], rep[kEmitTile];
+  int base[kEmitTile];
+  int wave_tot[kSelWaves];
+  int total;
+};
+
+template <int NT>
+__device__ __forceinline__ void emit_sequence(const EmitParams& p, int b, EmitScratch& sh) {
+  static_assert(NT <= kEmitTile, "one bitmap word per thread and round");
+  constexpr int NW = NT / KVC_WAVE;
+  const int tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
   const uint64_t* imp = p.impmask_base + (size_t)b * p.imp_stride;
   const uint64_t* rep = p.repmask ? p.repmask + (size_t)b * p.nw : nullptr;  // null: no representatives
   int32_t* idx_out = p.idx + (size_t)b * p.budget_full;
   uint8_t* kind_out = p.kind ? p.kind + (size_t)b * p.budget_full : nullptr;
-  for (int i = tid; i < p.n_sink + p.n_recent; i += kSelThreads) {
+  for (int i = tid; i < p.n_sink + p.n_recent; i += NT) {
     const bool head = i < p.n_sink;
     const int o = head ? i : p.budget_full - p.n_recent + (i - p.n_sink);
     const int t = head ? i : p.S_full - p.n_recent + (i - p.n_sink);
@@ -827,31 +876,29 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
   }
   idx_out += p.n_sink;
   if (kind_out) kind_out += p.n_sink;
-  int carried = 0;  // indices emitted by earlier tiles of 1024 words
-  for (int w0 = 0; w0 < p.nw; w0 += kSelThreads) {
-    // one bitmap word per thread: count, prefix-sum, park in LDS
+  int carried = 0;  // items emitted by earlier rounds
+  for (int w0 = 0; w0 < p.nw; w0 += NT) {
     const int c = w0 + tid;
     uint64_t rw = 0, kept = 0;
     if (c < p.nw) {
-      rw = rep ? rep[c] : 0ull;
-      kept = imp[c] | rw;
+      rw = rep ? load_shared_word(rep + c) : 0ull;
+      kept = load_shared_word(imp + c) | rw;
     }
     const int cnt = __popcll(kept);
-    const int before = block_excl_scan(cnt, wave_tot);
-    sh_kept[tid] = kept;
-    sh_rep[tid] = rw;
-    sh_base[tid] = carried + before;
+    const int before = block_excl_scan(cnt, sh.wave_tot);
+    sh.kept[tid] = kept;
+    sh.rep[tid] = rw;
+    sh.base[tid] = carried + before;
+    if (tid == NT - 1) sh.total = before + cnt;
     __syncthreads();
-    const int tile_total = sh_base[kSelThreads - 1] + __popcll(sh_kept[kSelThreads - 1]) - carried;
-    // one word per wave at a time: lanes with their bit set write in order
-    const int n_here = min(kSelThreads, p.nw - w0);
-    for (int j = wave; j < n_here; j += kSelWaves) {
-      const uint64_t kw = sh_kept[j], rj = sh_rep[j];
+    const int n_here = min(NT, p.nw - w0);
+    for (int j = wave; j < n_here; j += NW) {
+      const uint64_t kw = sh.kept[j];
       if ((kw >> lane) & 1ull) {
-        const int o = sh_base[j] + __popcll(kw & lanemask_lt());
+        const int o = sh.base[j] + __popcll(kw & lanemask_lt());
         if (o < p.budget) {  // always true for consistent masks; keeps stores in bounds regardless
           const int item = (w0 + j) * 64 + lane;
-          const uint8_t kd = (uint8_t)((rj >> lane) & 1ull);
+          const uint8_t kd = (uint8_t)((sh.rep[j] >> lane) & 1ull);
           if (p.unit == 1) {
             idx_out[o] = item + p.n_sink;
             if (kind_out) kind_out[o] = kd;
@@ -864,9 +911,370 @@ __global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
         }
       }
     }
-    carried += tile_total;
+    carried += sh.total;
     __syncthreads();
   }
+}
+
+__global__ __launch_bounds__(kSelThreads) void emit_kernel(EmitParams p) {
+  __shared__ EmitScratch sh;
+  emit_sequence<kSelThreads>(p, blockIdx.x, sh);
+}
+
+// =========================================== token-level selection in three launches ==
+// The usual case (tokens, not units, as the selected items; at most 128 score rows; rows
+// that fit the LDS tables below).  Every step that needs a view of a whole row or a whole
+// sequence is a serial chain of short phases, so the stage is bound by how many such chains
+// follow each other and by the fixed cost of a launch.  Three launches:
+//
+//   F1 slice_hist_kernel   the data-parallel part, spread over the chip: per (row, slice
+//                          of 2048 tokens) the histogram of the keys' leading 11 bits; the
+//                          importance row's workgroups first add up the score rows (in
+//                          row order) and leave the sums in the workspace.
+//   F2 row_select_kernel   one workgroup per row: adds the slices' histograms, finds the
+//                          leading digit of the k-th key, settles the remaining 21 bits on
+//                          the keys held in LDS, writes the row's bitmap.  The workgroup
+//                          that finishes a sequence's LAST row goes on to group that
+//                          sequence: bit words, anchor, distances and the stable counting
+//                          sort by (distance, token), all in its LDS.
+//   F3 medoid_emit_kernel  one wave per bucket picks the representative; the workgroup
+//                          that finishes a sequence's LAST bucket writes the index list.
+//
+// "Last" is decided by an arrival counter in the workspace (an atomic add after a release
+// fence; the counters are zeroed by F1, ahead of their first use in F2).  Nobody waits for
+// anybody: a workgroup that is not the last simply ends.
+constexpr int kSliceThreads = 256;
+constexpr int kSliceTokens = 2048;  // tokens of one row handled by an F1 workgroup
+constexpr int kFastMaxRows = 128;   // score rows (two 64-bit words per token)
+constexpr int kFastMaxTokens = 32768;  // a row's keys live in its workgroup's registers: 1024 threads x 32
+
+struct FastParams {
+  const float* scores;   // first selectable token of row 0 of sequence 0; rows are `ld` floats apart
+  float* imp;            // [B,S] token importances (F1 -> F2)
+  uint16_t* phist;       // [B,Hs+1,nsl,2048] slice histograms (F1 -> F2)
+  uint32_t* counters;    // [B,4]: rows finished, bucket workgroups finished
+  uint64_t* rowmask;     // [B,Hs+1,nw]; row Hs = important tokens
+  uint64_t* repmask;     // [B,nw]
+  uint64_t* bits;        // words of token 0 of sequence 0; sequences are bits_stride tokens apart
+  size_t bits_stride;
+  int32_t* order;        // [B,S]: first N entries = grouped tokens by (distance, token)
+  int Hs, S, nw, ld, kbit, n_important;
+  int slice, nsl;        // tokens per slice, slices per row
+  int row0, rows;        // rows handled: all Hs + 1, or the importance row alone
+  int W, N, Br;
+  int tail;              // 1: the row's workgroup writes the index list (plain top-n: no representatives)
+  EmitParams emit;
+};
+
+// One LDS histogram addition per key, except that the lanes sharing the bin of the wave's
+// first counted lane add once together: neighbouring scores are of similar size and equal keys
+// share every digit, so this one round takes most of the same-address traffic away.
+__device__ __forceinline__ void hist_add(uint32_t* hist, uint32_t bin, bool valid) {
+  const uint64_t act = __ballot(valid);
+  if (act == 0) return;  // uniform
+  const int first = __ffsll((unsigned long long)act) - 1;
+  const uint32_t lead = (uint32_t)__builtin_amdgcn_readlane((int)bin, first);
+  const uint64_t same = __ballot(valid && bin == lead);
+  if (valid) {
+    if (bin == lead) {
+      if (lane_id() == first) atomicAdd(&hist[lead], (uint32_t)__popcll(same));
+    } else {
+      atomicAdd(&hist[bin], 1u);
+    }
+  }
+}
+
+__global__ __launch_bounds__(kSliceThreads) void slice_hist_kernel(FastParams p) {
+  __shared__ __align__(16) uint32_t hist[kRadixBins];
+  const int s = blockIdx.x, row = p.row0 + blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int Hs = p.Hs;
+  for (int i = tid; i < kRadixBins; i += kSliceThreads) hist[i] = 0;
+  if (s == 0 && blockIdx.y == 0 && tid < 4) p.counters[(size_t)b * 4 + tid] = 0;
+  __syncthreads();
+  const float* __restrict__ sc = p.scores + (size_t)b * Hs * p.ld;
+  const size_t ld = (size_t)p.ld;
+  const int t0 = s * p.slice, t1 = min(p.S, t0 + p.slice);
+  constexpr int kU = 8;  // tokens per thread in flight
+  for (int base = t0 + tid; base < t1; base += kU * kSliceThreads) {
+    float v[kU];
+    if (row < Hs) {
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int t = base + u * kSliceThreads;
+        v[u] = t < t1 ? sc[(size_t)row * ld + t] : 0.0f;
+      }
+    } else {
+      // token importance: fp32 sum of the score rows, taken in row order (eight rows' loads in
+      // flight at a time; the additions stay in row order)
+#pragma unroll
+      for (int u = 0; u < kU; ++u) v[u] = 0.0f;
+      int r = 0;
+      for (; r + 8 <= Hs; r += 8) {
+        float x[8][kU];
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+          for (int u = 0; u < kU; ++u) {
+            const int t = base + u * kSliceThreads;
+            x[rr][u] = t < t1 ? sc[(size_t)(r + rr) * ld + t] : 0.0f;
+          }
+#pragma unroll
+        for (int rr = 0; rr < 8; ++rr)
+#pragma unroll
+          for (int u = 0; u < kU; ++u) v[u] = v[u] + x[rr][u];
+      }
+      for (; r < Hs; ++r) {
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+          const int t = base + u * kSliceThreads;
+          const float x = t < t1 ? sc[(size_t)r * ld + t] : 0.0f;
+          v[u] = v[u] + x;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kU; ++u) {
+        const int t = base + u * kSliceThreads;
+        if (t < t1) p.imp[(size_t)b * p.S + t] = v[u];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int t = base + u * kSliceThreads;
+      hist_add(hist, float_key(v[u]) >> 21, t < t1);
+    }
+  }
+  __syncthreads();
+  // eight bins per thread, as 16-bit counts (a slice has fewer than 65536 tokens)
+  uint16_t* __restrict__ out = p.phist + (((size_t)b * (Hs + 1) + row) * p.nsl + s) * kRadixBins;
+  const uint4 a = *(const uint4*)&hist[8 * tid], c = *(const uint4*)&hist[8 * tid + 4];
+  uint4 w;
+  w.x = a.x | (a.y << 16);
+  w.y = a.z | (a.w << 16);
+  w.z = c.x | (c.y << 16);
+  w.w = c.z | (c.w << 16);
+  *(uint4*)(out + 8 * tid) = w;
+}
+
+// F2: the k-th largest key of one row and the row's bitmap, by one workgroup.  The row's keys
+// stay in registers (KPT per thread; thread (wave w, lane l) holds token l of the 64-token
+// chunks w, w + 16, ...), the leading digit comes from the slices' histograms, and only the
+// keys that share it (a few percent of the row) go through the two remaining digit passes:
+// every wave keeps its own candidates in its own stretch of LDS (64 * KPT entries, enough
+// for all of its keys).  One compute unit issues every instruction of the row's keys, about
+// 0.1 us per instruction and key at 16 K keys, so the per-key loops are kept short.
+template <int KPT>
+__global__ __launch_bounds__(kSelThreads) void row_select_kernel(FastParams p) {
+  extern __shared__ __align__(16) uint32_t cand[];  // [kSelWaves][64 * KPT] low 21 key bits of each wave's candidates
+  __shared__ uint32_t hist[kRadixBins];
+  __shared__ uint32_t sh_digit, sh_remaining, sh_count, sh_last;
+  __shared__ int wave_tot[kSelWaves];
+  __shared__ int chunk_eq[kSelWaves * KPT];  // ties only: keys equal to the threshold, per chunk
+
+  const int row = p.row0 + blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = lane_id(), wave = tid / KVC_WAVE;
+  const int Hs = p.Hs, S = p.S, nw = p.nw;
+  const int k = row < Hs ? p.kbit : p.n_important;
+  uint64_t* __restrict__ mask_out = p.rowmask + ((size_t)b * (Hs + 1) + row) * nw;
+  const float* __restrict__ src =
+      row < Hs ? p.scores + ((size_t)b * Hs + row) * p.ld : p.imp + (size_t)b * S;
+
+  if (k == 0 || k == S) {  // nothing or everything: no search needed
+    for (int c = tid; c < nw; c += kSelThreads) {
+      uint64_t w = 0;
+      if (k == S) {
+        const int rem = S - c * 64;
+        w = rem >= 64 ? ~0ull : ((1ull << rem) - 1ull);
+      }
+      store_shared_word(mask_out + c, w);
+    }
+  } else {
+    // the row's keys (loads in flight while the histograms are added up); tokens past the end
+    // read as the smallest key and are never selected (k <= S real keys rank above or beside them;
+    // beside them only as key 0, where the lower token index wins)
+    float v[KPT];
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+      const int t = tid + u * kSelThreads;
+      v[u] = t < S ? src[t] : 0.0f;
+    }
+    // leading digit: the slices' histograms added up.  Thread i owns bins 2047 - 2i and 2046 - 2i,
+    // one 32-bit word of two 16-bit counts per slice.
+    const uint32_t* __restrict__ ph =
+        (const uint32_t*)(p.phist + ((size_t)b * (Hs + 1) + row) * p.nsl * kRadixBins);
+    uint32_t c_hi = 0, c_lo = 0;
+    for (int s = 0; s < p.nsl; ++s) {
+      const uint32_t w = ph[(size_t)s * (kRadixBins / 2) + (kRadixBins / 2 - 1 - tid)];
+      c_lo += w & 0xFFFFu;
+      c_hi += w >> 16;
+    }
+    hist[2 * tid] = 0;
+    hist[2 * tid + 1] = 0;
+    uint32_t remaining = (uint32_t)k;
+    {
+      const uint32_t above = (uint32_t)block_excl_scan((int)(c_hi + c_lo), wave_tot);
+      if (above < remaining && remaining <= above + c_hi) {
+        sh_digit = (uint32_t)(kRadixBins - 1 - 2 * tid);
+        sh_remaining = remaining - above;
+        sh_count = c_hi;
+      } else if (above + c_hi < remaining && remaining <= above + c_hi + c_lo) {
+        sh_digit = (uint32_t)(kRadixBins - 2 - 2 * tid);
+        sh_remaining = remaining - above - c_hi;
+        sh_count = c_lo;
+      }
+    }
+    __syncthreads();
+    const uint32_t d1 = sh_digit;
+    remaining = sh_remaining;
+    // this wave's candidates (valid keys with the leading digit d1) -> its stretch of LDS
+    uint32_t key[KPT];
+    uint32_t* __restrict__ mine = cand + wave * (KVC_WAVE * KPT);
+    int n_mine = 0;  // uniform over the wave
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+      const int t = tid + u * kSelThreads;
+      key[u] = t < S ? float_key(v[u]) : 0u;
+      const bool is_cand = (key[u] >> 21) == d1 && t < S;
+      const uint64_t m = __ballot(is_cand);
+      if (is_cand) mine[n_mine + __popcll(m & lanemask_lt())] = key[u] & 0x1FFFFFu;
+      n_mine += __popcll(m);
+    }
+    // the other 21 bits: two passes (11 and 10 bits) over the candidates that match the prefix so far
+    // (a wave reads back only what it wrote itself, so no barrier is needed before the first pass)
+    uint32_t low_prefix = 0, low_known = 0;
+#pragma unroll
+    for (int pass = 1; pass < 3; ++pass) {
+      const int shift = pass == 1 ? 10 : 0;
+      const int bins = pass == 1 ? 2048 : 1024;
+      for (int i0 = 0; i0 < n_mine; i0 += KVC_WAVE) {
+        const int i = i0 + lane;
+        const uint32_t x = i < n_mine ? mine[i] : 0u;
+        hist_add(hist, (x >> shift) & (uint32_t)(bins - 1), i < n_mine && (x & low_known) == low_prefix);
+      }
+      __syncthreads();
+      // thread i owns bins (bins-1 - per*i) downwards; `above` = keys with a larger digit
+      const int per = bins / kSelThreads;  // 2, 1
+      uint32_t c[2] = {0u, 0u};
+      int local = 0;
+      for (int j = 0; j < per; ++j) {
+        const int bin = bins - 1 - per * tid - j;
+        c[j] = hist[bin];
+        hist[bin] = 0;  // ready for the next pass
+        local += (int)c[j];
+      }
+      uint32_t above = (uint32_t)block_excl_scan(local, wave_tot);
+      for (int j = 0; j < per; ++j) {
+        if (above < remaining && remaining <= above + c[j]) {
+          sh_digit = (uint32_t)(bins - 1 - per * tid - j);
+          sh_remaining = remaining - above;
+          sh_count = c[j];
+        }
+        above += c[j];
+      }
+      __syncthreads();
+      low_prefix |= sh_digit << shift;
+      low_known |= (uint32_t)(bins - 1) << shift;
+      remaining = sh_remaining;
+    }
+    const uint32_t T = (d1 << 21) | low_prefix;  // key of the k-th largest element
+    const uint32_t count_eq = sh_count;          // elements equal to it; the first `remaining` of them are taken
+    const bool ties = count_eq != remaining;     // uniform over the workgroup
+    if (ties) {
+      // keys equal to T ahead of each chunk, in token order (chunk c = wave + 16 u)
+#pragma unroll
+      for (int u = 0; u < KPT; ++u) {
+        const int t = tid + u * kSelThreads;
+        const uint64_t m = __ballot(t < S && key[u] == T);
+        if (lane == 0) chunk_eq[wave + kSelWaves * u] = __popcll(m);
+      }
+      __syncthreads();
+      const int own = tid < kSelWaves * KPT ? chunk_eq[tid] : 0;  // one chunk per thread covers them all
+      const int before = block_excl_scan(own, wave_tot);
+      if (tid < kSelWaves * KPT) chunk_eq[tid] = before;
+      __syncthreads();
+    }
+    // the bitmap: lane u of the wave collects the word of the wave's u-th chunk
+    uint64_t word_of_lane = 0;
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+      const int t = tid + u * kSelThreads;
+      bool sel = key[u] >= T && t < S;
+      if (ties) {
+        const bool eq = t < S && key[u] == T;
+        const uint64_t m = __ballot(eq);
+        if (eq) sel = chunk_eq[wave + kSelWaves * u] + __popcll(m & lanemask_lt()) < (int)remaining;
+      }
+      const uint64_t word = __ballot(sel);
+      if (lane == u) word_of_lane = word;
+    }
+    if (lane < KPT && wave + kSelWaves * lane < nw) store_shared_word(mask_out + wave + kSelWaves * lane, word_of_lane);
+  }
+
+  // ---- plain top-n: the only row of the sequence goes straight on to the index list
+  if (p.tail == 0) return;
+  if (!arrive_last(&p.counters[(size_t)b * 4 + 0], (uint32_t)p.rows, &sh_last)) return;
+  emit_sequence<kSelThreads>(p.emit, b, *reinterpret_cast<EmitScratch*>(cand));  // (the candidates are no longer needed)
+}
+
+// F3: representatives (one wave per bucket, as medoid_kernel), then the index list by the
+// workgroup that finishes the sequence's last bucket.
+__global__ __launch_bounds__(kSelThreads) void medoid_emit_kernel(FastParams p) {
+  __shared__ EmitScratch sh;
+  __shared__ uint32_t sh_last;
+  const int b = blockIdx.y, lane = lane_id(), wave = threadIdx.x / KVC_WAVE;
+  const int j = blockIdx.x * kSelWaves + wave;  // bucket of this wave
+  const int W = p.W, Hs = p.Hs;
+  if (j < p.Br) {
+    const long long lo = (long long)j * p.N / p.Br, hi = (long long)(j + 1) * p.N / p.Br;
+    const int n = (int)(hi - lo);
+    const int32_t* order = p.order + (size_t)b * p.S + lo;
+    const uint64_t* bits = p.bits + (size_t)b * p.bits_stride * W;
+    // per-bit member counts: lane l keeps bits l and l + 64
+    int cnt[2] = {0, 0};
+    for (int m0 = 0; m0 < n; m0 += KVC_WAVE) {
+      const int m = m0 + lane;
+      const int t = m < n ? min(max(order[m], 0), p.S - 1) : 0;
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const uint64_t bw = (m < n && w < W) ? bits[(size_t)t * W + w] : 0ull;
+        const int nb = min(64, Hs - 64 * w);
+        for (int rr = 0; rr < nb; ++rr) {
+          const int c = __popcll(__ballot((bw >> rr) & 1ull));
+          if (lane == rr) cnt[w] += c;
+        }
+      }
+    }
+    // cost = summed Hamming distance to the members; keep the (cost, token) minimum
+    unsigned long long best = ~0ull;
+    for (int m0 = 0; m0 < n; m0 += KVC_WAVE) {
+      const int m = m0 + lane;
+      const int t = m < n ? min(max(order[m], 0), p.S - 1) : 0;
+      unsigned int cost = 0;
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const uint64_t bw = (m < n && w < W) ? bits[(size_t)t * W + w] : 0ull;
+        const int nb = min(64, Hs - 64 * w);
+        for (int rr = 0; rr < nb; ++rr) {
+          const int c = __shfl(cnt[w], rr);
+          cost += ((bw >> rr) & 1ull) ? (unsigned)(n - c) : (unsigned)c;
+        }
+      }
+      if (m < n) {
+        const unsigned long long key = ((unsigned long long)cost << 32) | (unsigned)t;
+        best = key < best ? key : best;
+      }
+    }
+#pragma unroll
+    for (int off = KVC_WAVE / 2; off > 0; off >>= 1) {
+      const unsigned long long o = __shfl_xor(best, off);
+      best = o < best ? o : best;
+    }
+    if (lane == 0) {
+      const int t = (int)(best & 0xFFFFFFFFull);
+      atomicOr((unsigned long long*)&p.repmask[(size_t)b * p.nw + (t >> 6)], 1ull << (t & 63));
+    }
+  }
+  if (!arrive_last(&p.counters[(size_t)b * 4 + 1], gridDim.x, &sh_last)) return;
+  emit_sequence<kSelThreads>(p.emit, b, sh);
 }
 
 // ------------------------------------------------------------- host side ---
@@ -880,8 +1288,11 @@ struct SelectPlan {
   int budget_items, imp_items; // kept / important items
   int cpw, n_wg, n_gw;         // chunks per grouping workgroup, workgroups / global waves per sequence
   bool keys_in_lds;
+  // three-launch path (tokens as items, few score rows, tables that fit LDS)
+  bool fast;
+  int slice, nsl;              // tokens per histogram slice, slices per row
   // workspace offsets
-  size_t rowmask_tok, rowmask, repmask, bits, order, dist_rank, counts, keys, total;
+  size_t rowmask_tok, rowmask, repmask, bits, order, dist_rank, counts, keys, imp, phist, counters, total;
 };
 
 // The radix select keeps a row's keys in LDS when they fit beside the static
@@ -930,6 +1341,8 @@ SelectPlan select_plan(const kvcrush_select_args* a, bool need_bits_ws) {
   // ((bits + 1) x global waves) still fits LDS
   P.cpw = kGsChunksPerWg;
   if (P.W > 2 && (size_t)(P.Hv + 1) * ((P.nw + 3) / 4) * kGsWaves * 4 <= 96 * 1024) P.cpw = 4;
+  // short vectors: as many workgroups as the count table allows (the stage is latency bound)
+  if (P.W <= 2 && (size_t)(P.Hv + 1) * ((P.nw + 3) / 4) * kGsWaves * 4 <= 48 * 1024) P.cpw = 4;
   P.n_wg = (P.nw + P.cpw - 1) / P.cpw;
   P.n_gw = P.n_wg * kGsWaves;
   const size_t B = (size_t)a->B;
@@ -953,39 +1366,43 @@ SelectPlan select_plan(const kvcrush_select_args* a, bool need_bits_ws) {
   if (need_bits_ws) off += kvc::align_up(B * P.n_items * P.W * 8, 256);
   P.keys = off;
   if (!P.keys_in_lds) off += kvc::align_up(B * (a->Hs + 1) * P.S_tok * 4, 256);
+  // the short path: per-slice histograms, token importances, arrival counters
+  P.slice = kSliceTokens;
+  P.nsl = P.S_tok > 0 ? (P.S_tok + P.slice - 1) / P.slice : 0;
+  P.fast = P.unit == 1 && a->Hs <= kFastMaxRows && P.S_tok > 0 && P.S_tok <= kFastMaxTokens;
+  P.imp = off;
+  if (P.fast) off += kvc::align_up(B * P.S_tok * 4, 256);
+  P.phist = off;
+  if (P.fast) off += kvc::align_up(B * (a->Hs + 1) * P.nsl * kRadixBins * 2, 256);
+  P.counters = off;
+  if (P.fast) off += kvc::align_up(B * 16, 256);
   P.total = off;
   return P;
 }
 
+// LDS tables of the grouping: (bits + 1) x chunk words of a workgroup, and the scatter's
+// (bits + 1) x global waves counters (the limit stated in the header).
+bool plan_fits_lds(const SelectPlan& P) {
+  return (size_t)(P.Hv + 1) * P.cpw * 8 <= 136 * 1024 && (size_t)(P.Hv + 1) * P.n_gw * 4 <= 120 * 1024;
+}
+
 template <int WMAX, int CPW>
 kvcrush_status launch_grouping(const GroupParams& g, const MedoidParams& m, const SelectPlan& P, int B,
-                               int Br, hipStream_t stream) {
+                               int Br, bool with_medoid, hipStream_t stream) {
   const size_t dyn_a = (size_t)(P.Hv + 1) * CPW * 8;
-  if (dyn_a > 32 * 1024) {
-    if (hipFuncSetAttribute((const void*)group_rank_kernel<WMAX, CPW>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn_a) != hipSuccess)
-      return KVCRUSH_ERR_HIP;
-  }
-  hipLaunchKernelGGL((group_rank_kernel<WMAX, CPW>), dim3(P.n_wg, B), dim3(kGsThreads), dyn_a, stream, g);
-  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
   const size_t dyn_b = (size_t)(P.Hv + 1) * P.n_gw * 4;
-  if (dyn_b > 32 * 1024) {
-    if (hipFuncSetAttribute((const void*)group_scatter_kernel<CPW>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)dyn_b) != hipSuccess)
-      return KVCRUSH_ERR_HIP;
-  }
-  if (Br == 0) return KVCRUSH_OK;  // the rank order only serves the representatives
-  hipLaunchKernelGGL(group_scatter_kernel<CPW>, dim3(P.n_wg, B), dim3(kGsThreads), dyn_b, stream, g);
-  if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-  {
-    if (WMAX > 2 && Br <= 65535)
-      hipLaunchKernelGGL(medoid_wide_kernel<WMAX>, dim3(Br, B), dim3(kMedoidThreads), 0, stream, m);
-    else
-      hipLaunchKernelGGL(medoid_kernel<WMAX>, dim3((Br + kMedoidWaves - 1) / kMedoidWaves, B),
-                         dim3(kMedoidThreads), 0, stream, m);
-    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-  }
-  return KVCRUSH_OK;
+  // (everything that can fail on the host comes before the first launch)
+  if (dyn_a > 32 * 1024 && kvc::allow_large_lds<group_rank_kernel<WMAX, CPW>>(24 * 1024) != KVCRUSH_OK)
+    return KVCRUSH_ERR_HIP;
+  if (dyn_b > 32 * 1024 && kvc::allow_large_lds<group_scatter_kernel<CPW>>(1024) != KVCRUSH_OK)
+    return KVCRUSH_ERR_HIP;
+  kvcrush_status st = kvc::launch(group_rank_kernel<WMAX, CPW>, dim3(P.n_wg, B), dim3(kGsThreads), dyn_a, stream, g);
+  if (st != KVCRUSH_OK || Br == 0) return st;  // the rank order only serves the representatives
+  st = kvc::launch(group_scatter_kernel<CPW>, dim3(P.n_wg, B), dim3(kGsThreads), dyn_b, stream, g);
+  if (st != KVCRUSH_OK || !with_medoid) return st;
+  if (WMAX > 2 && Br <= 65535) return kvc::launch(medoid_wide_kernel<WMAX>, dim3(Br, B), dim3(kMedoidThreads), 0, stream, m);
+  return kvc::launch(medoid_kernel<WMAX>, dim3((Br + kMedoidWaves - 1) / kMedoidWaves, B), dim3(kMedoidThreads), 0,
+                     stream, m);
 }
 
 }  // namespace
@@ -993,7 +1410,8 @@ kvcrush_status launch_grouping(const GroupParams& g, const MedoidParams& m, cons
 extern "C" size_t kvcrush_select_workspace(const kvcrush_select_args* args) {
   if (!select_args_ok(args) || !select_args_supported(args)) return 0;
   // sized for the case where the caller does not ask for the bit words
-  return select_plan(args, true).total;
+  const SelectPlan P = select_plan(args, true);
+  return plan_fits_lds(P) ? P.total : 0;
 }
 
 namespace {
@@ -1040,10 +1458,11 @@ extern "C" kvcrush_status kvcrush_select_static(const kvcrush_select_args* args,
                                                 void* hip_stream) {
   if (!select_args_ok(args)) return KVCRUSH_ERR_INVALID_ARG;
   if (!select_args_supported(args)) return KVCRUSH_ERR_UNSUPPORTED;
-  // (every buffer of the workspace is written before it is read inside one call, so the
-  // previous call's contents need no clearing)
-  if (select_plan(args, bits == nullptr).total > (size_t)KVCRUSH_SELECT_STATIC_MAX_BYTES)
-    return KVCRUSH_ERR_WORKSPACE;
+  // (every buffer of the workspace, the arrival counters included, is written inside a call
+  // before that call reads it, so the previous call's contents need no clearing)
+  const SelectPlan P = select_plan(args, bits == nullptr);
+  if (!plan_fits_lds(P)) return KVCRUSH_ERR_UNSUPPORTED;
+  if (P.total > (size_t)KVCRUSH_SELECT_STATIC_MAX_BYTES) return KVCRUSH_ERR_WORKSPACE;
   void* ptr = static_scratch_for_current_device();
   if (!ptr) return KVCRUSH_ERR_HIP;
   return select_run(args, scores, idx, kind, bits, ptr, (size_t)KVCRUSH_SELECT_STATIC_MAX_BYTES, hip_stream);
@@ -1060,9 +1479,7 @@ kvcrush_status select_run(const kvcrush_select_args* args, const float* scores, 
     return KVCRUSH_ERR_INVALID_ARG;
   const SelectPlan P = select_plan(args, bits == nullptr);
   if (P.total > 0 && (!workspace || workspace_bytes < P.total)) return KVCRUSH_ERR_WORKSPACE;
-  // LDS tables of the grouping: (bits + 1) x 16 chunk words, (bits + 1) x global waves counters
-  if ((size_t)(P.Hv + 1) * P.cpw * 8 > 136 * 1024 || (size_t)(P.Hv + 1) * P.n_gw * 4 > 120 * 1024)
-    return KVCRUSH_ERR_UNSUPPORTED;
+  if (!plan_fits_lds(P)) return KVCRUSH_ERR_UNSUPPORTED;
 
   hipStream_t stream = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
@@ -1081,7 +1498,70 @@ kvcrush_status select_run(const kvcrush_select_args* args, const float* scores, 
   // Plain top-n (no representative budget, token level, bit words not asked for): only the importance
   // row is ranked and the grouping kernels have nothing to do.
   const bool plain_topk = Br == 0 && token_level && bits == nullptr;
-  if (P.n_items > 0) {
+
+  EmitParams ep;
+  ep.impmask_base = rowmask + (size_t)P.Hv * P.nw;
+  ep.repmask = plain_topk ? nullptr : repmask;
+  ep.idx = idx;
+  ep.kind = kind;
+  ep.imp_stride = (size_t)(P.Hv + 1) * P.nw;
+  ep.S = P.n_items;
+  ep.nw = P.nw;
+  ep.budget = P.budget_items;
+  ep.n_sink = args->n_sink;
+  ep.n_recent = args->n_recent;
+  ep.S_full = S_full;
+  ep.budget_full = args->budget;
+  ep.bits_user = token_level ? bits : nullptr;
+  ep.W = P.W;
+  ep.unit = P.unit;
+
+  const bool fast = P.fast && args->budget > 0;
+  FastParams f;
+  if (fast) {
+    f.scores = scores + args->n_sink;
+    f.imp = (float*)(ws + P.imp);
+    f.phist = (uint16_t*)(ws + P.phist);
+    f.counters = (uint32_t*)(ws + P.counters);
+    f.rowmask = rowmask;
+    f.repmask = repmask;
+    f.bits = bits_buf;
+    f.bits_stride = bits_stride;
+    f.order = order;
+    f.Hs = Hs;
+    f.S = P.S_tok;
+    f.nw = P.nw_tok;
+    f.ld = args->score_stride ? args->score_stride : S_full;
+    f.kbit = kbit;
+    f.n_important = P.imp_items;
+    f.slice = P.slice;
+    f.nsl = P.nsl;
+    f.row0 = plain_topk ? Hs : 0;
+    f.rows = plain_topk ? 1 : Hs + 1;
+    f.W = P.W;
+    f.N = N;
+    f.Br = Br;
+    f.tail = plain_topk ? 1 : 0;
+    f.emit = ep;
+  }
+  // large tables in LDS have to be allowed per kernel before the first launch of the call
+  const bool kpt16 = P.S_tok <= 16 * kSelThreads;
+  const size_t row_lds = (size_t)kSelThreads * (kpt16 ? 16 : 32) * 4;  // every key may be a candidate
+  if (fast && (kpt16 ? kvc::allow_large_lds<row_select_kernel<16>>(16 * 1024)
+                     : kvc::allow_large_lds<row_select_kernel<32>>(16 * 1024)) != KVCRUSH_OK)
+    return KVCRUSH_ERR_HIP;
+  if (!fast && P.n_items > 0 && P.keys_in_lds && (size_t)P.S_tok * 4 > 48 * 1024 &&
+      kvc::allow_large_lds<topk_mask_kernel<true>>(12 * 1024) != KVCRUSH_OK)
+    return KVCRUSH_ERR_HIP;
+
+  // ---- per-row top-k -> row bitmaps
+  if (fast) {
+    kvcrush_status st = kvc::launch(slice_hist_kernel, dim3(P.nsl, f.rows, B), dim3(kSliceThreads), 0, stream, f);
+    if (st != KVCRUSH_OK) return st;
+    st = kpt16 ? kvc::launch(row_select_kernel<16>, dim3(f.rows, B), dim3(kSelThreads), row_lds, stream, f)
+               : kvc::launch(row_select_kernel<32>, dim3(f.rows, B), dim3(kSelThreads), row_lds, stream, f);
+    if (st != KVCRUSH_OK || plain_topk) return st;  // (plain top-n: the row's workgroup wrote the list)
+  } else if (P.n_items > 0) {
     TopkParams p;
     p.scores = scores + args->n_sink;
     p.ld = args->score_stride ? args->score_stride : S_full;
@@ -1094,17 +1574,10 @@ kvcrush_status select_run(const kvcrush_select_args* args, const float* scores, 
     p.kbit = kbit;
     p.n_important = P.imp_items;
     p.importance_only = plain_topk ? 1 : 0;
-    const size_t dyn = P.keys_in_lds ? (size_t)P.S_tok * 4 : 0;
-    if (dyn > 48 * 1024) {
-      if (hipFuncSetAttribute((const void*)topk_mask_kernel<true>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn) != hipSuccess)
-        return KVCRUSH_ERR_HIP;
-    }
-    if (P.keys_in_lds)
-      hipLaunchKernelGGL(topk_mask_kernel<true>, dim3(Hs + 1, B), dim3(kSelThreads), dyn, stream, p);
-    else
-      hipLaunchKernelGGL(topk_mask_kernel<false>, dim3(Hs + 1, B), dim3(kSelThreads), 0, stream, p);
-    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+    const kvcrush_status st =
+        P.keys_in_lds ? kvc::launch(topk_mask_kernel<true>, dim3(Hs + 1, B), dim3(kSelThreads), (size_t)P.S_tok * 4, stream, p)
+                      : kvc::launch(topk_mask_kernel<false>, dim3(Hs + 1, B), dim3(kSelThreads), 0, stream, p);
+    if (st != KVCRUSH_OK) return st;
   }
   if (P.n_items > 0 && !token_level) {
     UnitRowsParams p;
@@ -1117,9 +1590,10 @@ kvcrush_status select_run(const kvcrush_select_args* args, const float* scores, 
     p.nw_unit = P.nw;
     const long long words = (long long)(P.Hv + 1) * P.nw;
     const int gx = (int)std::min<long long>((words + 3) / 4, 2048);
-    hipLaunchKernelGGL(unit_rows_kernel, dim3(gx, B), dim3(256), 0, stream, p);
-    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
+    const kvcrush_status st = kvc::launch(unit_rows_kernel, dim3(gx, B), dim3(256), 0, stream, p);
+    if (st != KVCRUSH_OK) return st;
   }
+  // ---- bit words, distances, stable order by (distance, item); representatives
   if (P.n_items > 0 && !plain_topk) {
     GroupParams g;
     g.rowmask = rowmask;
@@ -1137,6 +1611,8 @@ kvcrush_status select_run(const kvcrush_select_args* args, const float* scores, 
     g.W = P.W;
     g.N = N;
     g.anchor_mode = args->anchor;
+    // (token level only: a unit's bit is set in at most bit_topk units as well, but N counts units there)
+    if (args->anchor == KVCRUSH_ANCHOR_MEAN && token_level && 2ll * kbit <= (long long)N) g.anchor_mode = kAnchorZero;
     int dbits = 0;
     while ((1 << dbits) <= P.Hv) ++dbits;  // distances range over 0..Hv
     g.dbits = dbits;
@@ -1154,35 +1630,21 @@ kvcrush_status select_run(const kvcrush_select_args* args, const float* scores, 
     m.Br = Br;
     kvcrush_status st;
     if (P.W <= 2)
-      st = launch_grouping<2, kGsChunksPerWg>(g, m, P, B, Br, stream);
+      st = P.cpw == 4 ? launch_grouping<2, 4>(g, m, P, B, Br, !fast, stream)
+                      : launch_grouping<2, kGsChunksPerWg>(g, m, P, B, Br, !fast, stream);
     else if (P.W <= 4)
-      st = P.cpw == 4 ? launch_grouping<4, 4>(g, m, P, B, Br, stream)
-                      : launch_grouping<4, kGsChunksPerWg>(g, m, P, B, Br, stream);
+      st = P.cpw == 4 ? launch_grouping<4, 4>(g, m, P, B, Br, true, stream)
+                      : launch_grouping<4, kGsChunksPerWg>(g, m, P, B, Br, true, stream);
     else
-      st = P.cpw == 4 ? launch_grouping<kMaxW, 4>(g, m, P, B, Br, stream)
-                      : launch_grouping<kMaxW, kGsChunksPerWg>(g, m, P, B, Br, stream);
+      st = P.cpw == 4 ? launch_grouping<kMaxW, 4>(g, m, P, B, Br, true, stream)
+                      : launch_grouping<kMaxW, kGsChunksPerWg>(g, m, P, B, Br, true, stream);
     if (st != KVCRUSH_OK) return st;
   }
-  if (args->budget > 0) {
-    EmitParams p;
-    p.impmask_base = rowmask + (size_t)P.Hv * P.nw;
-    p.repmask = plain_topk ? nullptr : repmask;
-    p.idx = idx;
-    p.kind = kind;
-    p.imp_stride = (size_t)(P.Hv + 1) * P.nw;
-    p.S = P.n_items;
-    p.nw = P.nw;
-    p.budget = P.budget_items;
-    p.n_sink = args->n_sink;
-    p.n_recent = args->n_recent;
-    p.S_full = S_full;
-    p.budget_full = args->budget;
-    p.bits_user = token_level ? bits : nullptr;
-    p.W = P.W;
-    p.unit = P.unit;
-    hipLaunchKernelGGL(emit_kernel, dim3(B), dim3(kSelThreads), 0, stream, p);
-    if (kvc::launch_status() != KVCRUSH_OK) return KVCRUSH_ERR_HIP;
-  }
+  // ---- the ascending index list
+  if (fast)  // representatives and the list in one launch
+    return kvc::launch(medoid_emit_kernel, dim3(std::max(1, (Br + kSelWaves - 1) / kSelWaves), B),
+                       dim3(kSelThreads), 0, stream, f);
+  if (args->budget > 0) return kvc::launch(emit_kernel, dim3(B), dim3(kSelThreads), 0, stream, ep);
   return KVCRUSH_OK;
 }
 }  // namespace

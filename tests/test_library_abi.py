@@ -111,6 +111,12 @@ def test_select_rejects_bad_arguments(lib):
     assert call(mk(1, 8, 96, 48, 16, unit=-2)) == binding.ERR_INVALID_ARG
     assert call(mk(1, 8, 100, 50, 10, anchor=9)) == binding.ERR_INVALID_ARG
     assert call(mk(1, 8, 100, 50, 10, anchor="explicit")) == binding.ERR_INVALID_ARG  # no anchor_bits
+    # the grouping's counter table must fit a workgroup's LDS: (bits + 1) x 4 x ceil(items / 1024) <= 30720
+    big = mk(1, 128, 70000, 1000, 500)
+    assert binding.kvcrush_select_workspace(big) == 0 and call(big) == binding.ERR_UNSUPPORTED
+    assert binding.kvcrush_select_workspace(mk(1, 128, 60000, 1000, 500)) > 0
+    assert binding.kvcrush_select_workspace(mk(1, 8, 900000, 1000, 500)) == 0
+    assert binding.kvcrush_select_workspace(mk(1, 8, 800000, 1000, 500)) > 0
     assert call(mk(1, 8, 100, 50, 10), scores=None) == binding.ERR_INVALID_ARG
     assert call(mk(1, 8, 100, 50, 10), ws=None) == binding.ERR_WORKSPACE
     assert call(mk(1, 8, 100, 50, 10), ws_bytes=64) == binding.ERR_WORKSPACE
