@@ -103,6 +103,37 @@ def mfma_ceiling_tflops(torch, dev, q_sample):
     return best
 
 
+def mix_ceiling_tflops(torch, dev, q_sample):
+    """What the chip sustains on the score kernels' instruction mix alone: per 64 x 32 block 16 MFMAs
+    and, for each of the previous block's 32 accumulator values, multiply-add, exp2 and add, interleaved
+    as in the kernels; no memory traffic (csrc/bench/mix_ceiling.hip).  Matrix FLOP/s, like the kernels'."""
+    import ctypes
+    from paper_2503_00022_amd import build as b
+    L = ctypes.CDLL(b.BENCH_LIB_PATH)
+    L.kvcrush_bench_mix_ceiling.restype = ctypes.c_double
+    L.kvcrush_bench_mix_ceiling.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                            ctypes.c_void_p]
+    L.kvcrush_bench_mix_operand_bytes.restype = ctypes.c_size_t
+    need = L.kvcrush_bench_mix_operand_bytes()
+    ops = q_sample.reshape(-1).view(torch.uint8)[:need].contiguous()
+    assert ops.numel() == need, "sample too small for the calibration kernel's operands"
+    grid, iters = 512, 1024                                  # two workgroups per compute unit, about 1 ms
+    out = torch.empty(grid * 256, dtype=torch.float32, device=dev)
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    best = 0.0
+    for rep in range(6):                                     # the first launches also settle the clock
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flop = L.kvcrush_bench_mix_ceiling(ops.data_ptr(), iters, grid, out.data_ptr(), st)
+        e1.record()
+        torch.cuda.synchronize()
+        if flop <= 0.0:
+            return None
+        if rep >= 2:
+            best = max(best, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
+
+
 def cpu_baseline(w, q0, k0, v0, sc_gpu_layer0, layer, row_begin=0, pool=0, unit=0):
     """The oracle as it stands, single-threaded, on a bounded sample: every query
     row of the first few query heads of layer 0 (heads are added until about 12 s
@@ -514,6 +545,10 @@ def main():
         if ceil:
             roofline["measured_mfma_only_tflops"] = ceil
             roofline["frac_of_measured"] = achieved / ceil
+        mix = mix_ceiling_tflops(torch, dev, run.layers[0]["q"])
+        if mix:
+            roofline["measured_mix_tflops"] = mix          # 16 MFMAs + 32 x (fma, exp2, add) per block, nothing else
+            roofline["frac_of_measured_mix"] = achieved / mix
     if not args.no_cpu_baseline:
         # layer 0 again, so that its scores are the ones handed to the oracle's selection
         run.step_with_events(0, None)

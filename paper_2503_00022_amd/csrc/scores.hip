@@ -471,12 +471,18 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   load_stationary<C>(kf[0], kh, k0, S, lane, krb);
   load_stationary<C>(kf[1], kh, k0 + 32, S, lane, krb);
 
-  // tiles of this piece: [t_first, t_last]; those below f_first touch the diagonal
+  // tiles of this piece: [t_first, t_last]; those below f_first touch the diagonal, and the
+  // sequence's last tile, when it is a partial one, is taken out of the pipelined range as well
+  // (every tile there is whole, so its loads need no row clamp: fewer address instructions
+  // beside the MFMAs)
   const int t_first = max(p.tile0 + chunk * p.chunk_tiles, kb * kTpk);
   const int f_first = C::kPipelined ? max(t_first, kb * kTpk + kTpk) : t_last + 1;
-  const int n_fullt = max(0, t_last - f_first + 1);
-  const int d_last = t_last - n_fullt;
+  const bool ragged_last = (t_last + 1) * C::kTile > S;
+  const int f_last = t_last - (ragged_last ? 1 : 0);
+  const int n_fullt = max(0, f_last - f_first + 1);
+  const int d_last = min(f_first - 1, t_last);
   const int n_diagt = max(0, d_last - t_first + 1);
+  const int n_extra = (ragged_last && t_last >= f_first) ? 1 : 0;  // the partial tile, if not among the diagonal ones
   const float c = p.scale_log2;
   const int off0 = lds_frag_offset0<C>(lane);
   uint32_t rel[C::kLoadsPerWave];
@@ -504,20 +510,34 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   if constexpr (C::kPipelined) {
     const int n_fast = n_heads * n_fullt;
     if (n_fast > 0) {
-      auto tile_of = [&](int it, int& head, int& qt) {
-        head = head0 + it / n_fullt;
-        qt = (t_last - it % n_fullt) * C::kTile;
+      // The (head, tile) pairs are walked with running pointers: a head's tiles from f_last down
+      // to f_first, then the next head.  Steps past the last pair stay on it (their lse is +inf).
+      // Scalar adds and one compare per step: no division, no 64-bit multiply inside the loop.
+      const long long head_step = STRIDED ? p.q_sh : (long long)S * C::kRowBytes;  // bytes between heads
+      const long long tile_step = (long long)C::kTile * qrb;                      // bytes between tiles
+      const long long head_jump = head_step + (long long)(n_fullt - 1) * tile_step;
+      const char* q_next = q_head(head0) + (size_t)f_last * C::kTile * qrb;
+      const float* lse_next = lse_in + ((size_t)b * p.Hq + head0) * S + (size_t)f_last * C::kTile + (tid & (C::kTile - 1));
+      int qt_next = f_last * C::kTile, left = n_fullt, pair_no = 0;
+      // loads pair `pair_no` (tile -> buf) and returns this thread's lse of it, base 2
+      auto issue = [&](char* buf) -> float {
+        tile_load_async_full<C>(q_next, 0, buf, rel, wave, qrb);
+        const float v = *lse_next * kLog2e;
+        // (every tile here is whole; rows before an observation window contribute nothing)
+        const bool counts = pair_no < n_fast && qt_next + (tid & (C::kTile - 1)) >= p.q_first;
+        // (selects, not branches: the loop body has to stay one straight block)
+        const bool more = pair_no < n_fast - 1, wrap = left == 1;
+        const long long dq = more ? (wrap ? head_jump : -tile_step) : 0ll;
+        const int dl = more ? (wrap ? S + (n_fullt - 1) * C::kTile : -C::kTile) : 0;
+        q_next += dq;
+        lse_next += dl;
+        qt_next = more ? (wrap ? f_last * C::kTile : qt_next - C::kTile) : qt_next;
+        left = more ? (wrap ? n_fullt : left - 1) : left;
+        ++pair_no;
+        return counts ? v : INFINITY;
       };
-      int head, qt;
-      tile_of(0, head, qt);
-      tile_load_async<C>(q_head(head), qt, S, lds[0], rel, wave, lane, qrb);
-      lds_lse[0][tid] = load_lse(head, qt);
-      tile_of(min(1, n_fast - 1), head, qt);
-      tile_load_async<C>(q_head(head), qt, S, lds[1], rel, wave, lane, qrb);
-      {
-        const float v = load_lse(head, qt);
-        lds_lse[1][tid] = n_fast > 1 ? v : INFINITY;
-      }
+      lds_lse[0][tid] = issue(lds[0]);
+      lds_lse[1][tid] = issue(lds[1]);
       wait_async_loads();
       __syncthreads();
       // tile t (and its lse) lives in buffer t % 3, as in pass A
@@ -536,10 +556,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       auto body = [&](auto P, int it) {
         constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
         constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
-        tile_of(min(it + 2, n_fast - 1), head, qt);
-        tile_load_async<C>(q_head(head), qt, S, lds[ld], rel, wave, lane, qrb);
-        const float ld_lse = load_lse(head, qt);
-        const float st_lse = it + 2 < n_fast ? ld_lse : INFINITY;
+        const float st_lse = issue(lds[ld]);  // pair it + 2
         const float lse_a = lds_lse[cur][lane & 31], lse_b = lds_lse[cur][32 + (lane & 31)];
         __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);  // the two lse reads lead the block
         colsum_half<C, cur * kT + kU, nxt * kT, F16>(acc1, acc0, col, fr, kf[0], kf[1], lds_base, fo, c, lse_a);
@@ -557,11 +574,13 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   }
 
   // ---- tiles on the diagonal (and every tile of the fp32 path): masked, plain loop
-  const int n_slow = n_heads * n_diagt;
+  const int n_slowt = n_diagt + n_extra;
+  const int n_slow = n_heads * n_slowt;
   if (n_slow > 0) {
     auto tile_of = [&](int it, int& head, int& qt) {
-      head = head0 + it / n_diagt;
-      qt = (d_last - it % n_diagt) * C::kTile;
+      head = head0 + it / n_slowt;
+      const int j = it % n_slowt;
+      qt = (j < n_extra ? t_last : d_last - (j - n_extra)) * C::kTile;
     };
     int head, qt;
     tile_of(0, head, qt);
