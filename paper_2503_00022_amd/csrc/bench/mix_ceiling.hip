@@ -24,8 +24,12 @@ constexpr int kSchedMfma = 0x008, kSchedValu = 0x002 | 0x400;
 // One block: the MFMAs of acc_new, and exp2(acc_old * c - ref) added into col.
 __device__ __forceinline__ void mix_half(f32x16 (&acc_new)[2], const f32x16 (&acc_old)[2], f32x16 (&col)[2],
                                          const u32x4 (&a0)[kSteps], const u32x4 (&a1)[kSteps],
-                                         const u32x4 (&b)[kSteps], float c, float ref) {
+                                         u32x4 (&b)[kSteps], float c, float ref) {
   constexpr int kPer = 32 / kSteps;  // elements of acc_old per MFMA pair
+  // The operands never change, so without this the compiler would compute the block once and
+  // reuse it: an empty statement that claims to rewrite two operand registers keeps every
+  // block's MFMAs in the loop, at no instruction's cost.
+  asm volatile("" : "+v"(b[0]), "+v"(b[kSteps - 1]));
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll

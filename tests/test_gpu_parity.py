@@ -577,6 +577,19 @@ def test_config5_long_paged(kv, oracle, layer, rows):
     run_pipeline(kv, oracle, w, 5, layer, rows if isinstance(rows, range) else [(0, r) for r in rows])
 
 
+@pytest.mark.slow
+def test_config3_one_bit_per_query_head(kv, oracle):
+    """Sec. 4.3.3 counts 32 bits per token for a Llama-3-8B layer: one bit per QUERY head.  The
+    config-3 layer with reduce_groups = 0 (32 score rows of 16384 tokens under grouped-query
+    attention): every row against the oracle, then selection on the 32-bit vectors and the
+    gather, bit-exact, in the launch shapes the benchmark's per-head variant times."""
+    import dataclasses
+    say("config 3 shape, one score row per query head: 32 rows against the oracle, selection and gather")
+    w = dataclasses.replace(inputs.CONFIGS[3], name="cfg3_per_query_head_bits", reduce_groups=False)
+    assert w.Hs == 32
+    run_pipeline(kv, oracle, w, 3, 0, all_rows(w), whole=True)
+
+
 LAYER_GROUPS = [range(g, g + 4) for g in range(0, 32, 4)]
 
 

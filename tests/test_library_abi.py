@@ -302,3 +302,21 @@ def test_calibration_library_is_separate_from_the_product():
     assert bench.kvcrush_bench_mfma_ceiling(None, 1, 1, None, None) == 0.0       # refused before any launch
     product = binding.load()
     assert not hasattr(product, "kvcrush_bench_mfma_ceiling")
+
+
+def test_mix_calibration_kernel_keeps_its_matrix_instructions(tmp_path):
+    """The mix ceiling is quoted in matrix FLOP/s: its loop must really hold 32 MFMAs (two 64 x 32
+    blocks) and 64 each of fma / exp2 / add per trip.  Its operands never change, so a compiler that
+    is allowed to would compute one block and reuse it; the count is checked in the generated code."""
+    import subprocess
+    from paper_2503_00022_amd import build
+    src = os.path.join(build.CSRC, "bench", "mix_ceiling.hip")
+    out = tmp_path / "mix.s"
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    subprocess.run([os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), *flags, "--cuda-device-only", "-S", "-o", str(out), src],
+                   check=True, capture_output=True)
+    text = out.read_text()
+    body = text[text.index("mix_ceiling_kernel"):]
+    body = body[:body.index("s_endpgm")]
+    assert body.count("v_mfma_f32_32x32x16_bf16") == 32
+    assert body.count("v_exp_f32") == 64 and body.count("v_fma_f32") >= 64
