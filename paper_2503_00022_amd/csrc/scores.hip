@@ -689,7 +689,15 @@ ColsumPlan colsum_plan(int S, int tile, int chunk_tiles_wanted, int q_first) {
   return pl;
 }
 
-constexpr int kChunkQueries = 1152;  // queries per pass-B work piece: 18 tiles, a multiple of 3
+// Pass-B work pieces run about 72 tile steps each (query tiles x the heads a piece walks): 18
+// tiles of 64 queries when a score row sums a KV group of four query heads, 72 when it is one
+// head.  The count is a multiple of three (the loop's unroll).
+constexpr int kPieceSteps = 72;
+int chunk_tiles_for(int tile, int heads_per_row) {
+  const int steps = kPieceSteps * 64 / tile;                       // (fp32 tiles hold 32 queries)
+  const int tiles = (steps + heads_per_row - 1) / heads_per_row;
+  return std::max(3, (tiles + 2) / 3 * 3);
+}
 
 // Launch shape of pass A.  Query blocks are numbered from the end of the
 // sequence: with an observation window only the blocks that reach into it are
@@ -756,7 +764,7 @@ kvcrush_status launch_scores(const ScoreParams& base, const float* lse_user, flo
                              bool lse_only, hipStream_t stream) {
   using C = Cfg<BF16, D>;
   ScoreParams p = base;
-  const ColsumPlan pl = colsum_plan(p.S, C::kTile, kChunkQueries / C::kTile, p.q_first);
+  const ColsumPlan pl = colsum_plan(p.S, C::kTile, chunk_tiles_for(C::kTile, p.reduce_groups ? p.G : 1), p.q_first);
   const long long rows = (long long)p.B * (p.reduce_groups ? p.Hkv : p.Hq);
   if (!lse_only && pl.pieces * rows > kMaxGridX) return KVCRUSH_ERR_UNSUPPORTED;  // before anything is enqueued
   if (!lse_user) {
@@ -791,7 +799,7 @@ size_t lse_bytes(const kvcrush_shape* s) {
 
 size_t partial_bytes(const kvcrush_shape* s) {
   const int tile = s->dtype != KVCRUSH_F32 ? 64 : 32;
-  const ColsumPlan pl = colsum_plan(s->S, tile, kChunkQueries / tile, first_query(s));
+  const ColsumPlan pl = colsum_plan(s->S, tile, chunk_tiles_for(tile, s->reduce_groups ? s->Hq / s->Hkv : 1), first_query(s));
   if (pl.n_chunks <= 1) return 0;
   const size_t rows = (size_t)s->B * (s->reduce_groups ? s->Hkv : s->Hq);
   return kvc::align_up(rows * pl.n_kb * pl.n_chunks * kKeysPerWg * sizeof(float), 256);
