@@ -37,6 +37,10 @@ def say(msg):
 @pytest.mark.parametrize("B,Hkv,S,D,dtype,budget", [
     (2, 4, 96, 64, "bf16", 24), (1, 8, 1000, 128, "bf16", 333), (3, 2, 130, 128, "f32", 130),
     (1, 1, 17, 64, "f32", 1), (2, 8, 4096, 128, "bf16", 1024), (1, 3, 50, 64, "bf16", 0), (2, 2, 700, 128, "f16", 99),
+    (2, 3, 70, 96, "f32", 33),      # 24 vectors a row: lanes per row not a power of two
+    (1, 2, 40, 24, "bf16", 13),     # 3 vectors a row
+    (1, 2, 50, 2048, "f32", 7),     # 8 KiB rows: more vectors than a workgroup has lanes
+    (8, 8, 8192, 128, "bf16", 2048),  # config-4 size: the eight-rows-in-flight instantiation
 ])
 def test_compact_dense(kv, oracle, B, Hkv, S, D, dtype, budget):
     say(f"compact dense B={B} Hkv={Hkv} S={S} D={D} {dtype} budget={budget}")
