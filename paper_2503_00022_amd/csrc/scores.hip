@@ -443,17 +443,20 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
   const int n_tiles = (S + C::kTile - 1) / C::kTile;
   const int n_kb = p.n_blocks;
 
-  // piece -> (chunk, key block): chunks from the end of the sequence backwards
+  // piece -> (chunk, key block): chunks from the start of the sequence on.  The early chunks have
+  // few key blocks and pieces of uneven length (many diagonal tiles); the late ones are a full row
+  // of key blocks each, all pieces alike, and the very last chunk is the short remainder: started
+  // in this order the workgroup slots of the chip run dry at nearly the same time.
   const int bh = (int)(blockIdx.x % p.n_bh);
   int rem = (int)(blockIdx.x / p.n_bh);
-  int chunk = p.n_chunks - 1;
+  int chunk = 0;
   int t_last;
   for (;;) {
     t_last = min(p.tile0 + (chunk + 1) * p.chunk_tiles, n_tiles) - 1;
     const int cnt = min(n_kb, t_last / kTpk + 1);
     if (rem < cnt) break;
     rem -= cnt;
-    --chunk;
+    ++chunk;
   }
   const int kb = rem;
 
@@ -517,14 +520,27 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       const long long tile_step = (long long)C::kTile * qrb;                      // bytes between tiles
       const long long head_jump = head_step + (long long)(n_fullt - 1) * tile_step;
       const char* q_next = q_head(head0) + (size_t)f_last * C::kTile * qrb;
-      const float* lse_next = lse_in + ((size_t)b * p.Hq + head0) * S + (size_t)f_last * C::kTile + (tid & (C::kTile - 1));
+      // A lane needs the lse of two query rows of a tile (lane % 32 of either 32-row block): it
+      // loads them itself, two tiles ahead, and keeps them in registers.
+      const float* lse_next = lse_in + ((size_t)b * p.Hq + head0) * S + (size_t)f_last * C::kTile + (lane & 31);
       int qt_next = f_last * C::kTile, left = n_fullt, pair_no = 0;
-      // loads pair `pair_no` (tile -> buf) and returns this thread's lse of it, base 2
-      auto issue = [&](char* buf) -> float {
-        tile_load_async_full<C>(q_next, 0, buf, rel, wave, qrb);
-        const float v = *lse_next * kLog2e;
+      // The loads are written out so that nothing waits for them before the end-of-step wait that
+      // the tile loads need anyway: the registers hold no value until settle() has run.
+      struct Pending {
+        float raw[2];
+        bool counts[2];
+      };
+      // loads pair `pair_no` (tile -> buf) and starts the loads of this lane's two lse values of it
+      auto issue = [&](char* buf) -> Pending {
+        Pending x;
+        tile_load_async_full_unseen<C>(q_next, 0, buf, rel, wave, qrb);
+        asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
+                     : "=&v"(x.raw[0]), "=&v"(x.raw[1])
+                     : "v"(lse_next)
+                     : "memory");
         // (every tile here is whole; rows before an observation window contribute nothing)
-        const bool counts = pair_no < n_fast && qt_next + (tid & (C::kTile - 1)) >= p.q_first;
+        x.counts[0] = pair_no < n_fast && qt_next + (lane & 31) >= p.q_first;
+        x.counts[1] = pair_no < n_fast && qt_next + 32 + (lane & 31) >= p.q_first;
         // (selects, not branches: the loop body has to stay one straight block)
         const bool more = pair_no < n_fast - 1, wrap = left == 1;
         const long long dq = more ? (wrap ? head_jump : -tile_step) : 0ll;
@@ -534,13 +550,23 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
         qt_next = more ? (wrap ? f_last * C::kTile : qt_next - C::kTile) : qt_next;
         left = more ? (wrap ? n_fullt : left - 1) : left;
         ++pair_no;
-        return counts ? v : INFINITY;
+        return x;
       };
-      lds_lse[0][tid] = issue(lds[0]);
-      lds_lse[1][tid] = issue(lds[1]);
-      wait_async_loads();
+      // waits for every load in flight (tiles and lse) and turns the pair's lse into base 2
+      auto settle = [&](Pending& x, float (&lse2)[2]) {
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(x.raw[0]), "+v"(x.raw[1])::"memory");
+        lse2[0] = x.counts[0] ? x.raw[0] * kLog2e : INFINITY;
+        lse2[1] = x.counts[1] ? x.raw[1] * kLog2e : INFINITY;
+      };
+      float lse_cur[2], lse_nxt[2];
+      {
+        Pending x0 = issue(lds[0]);
+        Pending x1 = issue(lds[1]);
+        settle(x0, lse_cur);
+        settle(x1, lse_nxt);
+      }
       __syncthreads();
-      // tile t (and its lse) lives in buffer t % 3, as in pass A
+      // tile t lives in buffer t % 3, as in pass A
       const char* lds_base = &lds[0][0];
       int fo[C::kSteps];
 #pragma unroll
@@ -556,13 +582,12 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       auto body = [&](auto P, int it) {
         constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
         constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
-        const float st_lse = issue(lds[ld]);  // pair it + 2
-        const float lse_a = lds_lse[cur][lane & 31], lse_b = lds_lse[cur][32 + (lane & 31)];
-        __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 2, 0);  // the two lse reads lead the block
-        colsum_half<C, cur * kT + kU, nxt * kT, F16>(acc1, acc0, col, fr, kf[0], kf[1], lds_base, fo, c, lse_a);
-        colsum_half<C, nxt * kT, nxt * kT + kU, F16>(acc0, acc1, col, fr, kf[0], kf[1], lds_base, fo, c, lse_b);
-        lds_lse[ld][tid] = st_lse;  // unconditional: keeps the block free of exec changes
-        wait_async_loads();
+        Pending ahead = issue(lds[ld]);  // pair it + 2
+        colsum_half<C, cur * kT + kU, nxt * kT, F16>(acc1, acc0, col, fr, kf[0], kf[1], lds_base, fo, c, lse_cur[0]);
+        colsum_half<C, nxt * kT, nxt * kT + kU, F16>(acc0, acc1, col, fr, kf[0], kf[1], lds_base, fo, c, lse_cur[1]);
+        lse_cur[0] = lse_nxt[0];
+        lse_cur[1] = lse_nxt[1];
+        settle(ahead, lse_nxt);
         __syncthreads();
       };
       for (int it = 0; it < n_fast; it += 3) {

@@ -892,20 +892,34 @@ __device__ __forceinline__ void emit_sequence(const EmitParams& p, int b, EmitSc
     if (tid == NT - 1) sh.total = before + cnt;
     __syncthreads();
     const int n_here = min(NT, p.nw - w0);
-    for (int j = wave; j < n_here; j += NW) {
-      const uint64_t kw = sh.kept[j];
-      if ((kw >> lane) & 1ull) {
-        const int o = sh.base[j] + __popcll(kw & lanemask_lt());
-        if (o < p.budget) {  // always true for consistent masks; keeps stores in bounds regardless
-          const int item = (w0 + j) * 64 + lane;
-          const uint8_t kd = (uint8_t)((sh.rep[j] >> lane) & 1ull);
-          if (p.unit == 1) {
-            idx_out[o] = item + p.n_sink;
-            if (kind_out) kind_out[o] = kd;
-          } else {
-            for (int e = 0; e < p.unit; ++e) {
-              idx_out[(size_t)o * p.unit + e] = item * p.unit + e + p.n_sink;
-              if (kind_out) kind_out[(size_t)o * p.unit + e] = kd;
+    constexpr int kAhead = 4;  // words whose LDS reads are in flight together (the loop is bound by their latency)
+    for (int j0 = wave; j0 < n_here; j0 += NW * kAhead) {
+      uint64_t kws[kAhead], reps[kAhead];
+      int bases[kAhead];
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) {
+        const int j = min(j0 + a * NW, NT - 1);
+        kws[a] = sh.kept[j];
+        reps[a] = sh.rep[j];
+        bases[a] = sh.base[j];
+      }
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) {
+        const int j = j0 + a * NW;
+        const uint64_t kw = j < n_here ? kws[a] : 0ull;
+        if ((kw >> lane) & 1ull) {
+          const int o = bases[a] + __popcll(kw & lanemask_lt());
+          if (o < p.budget) {  // always true for consistent masks; keeps stores in bounds regardless
+            const int item = (w0 + j) * 64 + lane;
+            const uint8_t kd = (uint8_t)((reps[a] >> lane) & 1ull);
+            if (p.unit == 1) {
+              idx_out[o] = item + p.n_sink;
+              if (kind_out) kind_out[o] = kd;
+            } else {
+              for (int e = 0; e < p.unit; ++e) {
+                idx_out[(size_t)o * p.unit + e] = item * p.unit + e + p.n_sink;
+                if (kind_out) kind_out[(size_t)o * p.unit + e] = kd;
+              }
             }
           }
         }

@@ -146,6 +146,33 @@ __device__ __forceinline__ void tile_load_async_full(const char* head_base, int 
                                      16, 0, 0);
 }
 
+// The same copy issued as written-out instructions.  The compiler, which cannot tell one LDS
+// buffer from another, makes a wave wait for every copy in flight before its next LDS read after
+// a copy it knows of: right after the copies were issued, for the whole memory latency.  Copies
+// it does not know of cost no such wait; the caller's own wait and barrier at the end of the step
+// (which the other form needs as well) are then the only synchronisation, so the buffer must not
+// be read before them.  M0 holds the wave's LDS destination (one wait state before its use).
+// (M0 is a register the compiler reserves and sets itself before each of its own uses; naming it
+// as clobbered keeps it from merging such a set across this statement, and draws a warning)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+template <class C>
+__device__ __forceinline__ void tile_load_async_full_unseen(const char* head_base, int row0, char* buf,
+                                                            const uint32_t (&rel)[C::kLoadsPerWave], int wave,
+                                                            uint32_t row_bytes = C::kRowBytes) {
+  const char* tile = head_base + (size_t)row0 * row_bytes;
+#pragma unroll
+  for (int j = 0; j < C::kLoadsPerWave; ++j) {
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)(buf + (wave + kWaves * j) * 1024));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(dst), "v"(tile + rel[j])
+                 : "memory", "m0");
+  }
+}
+#pragma clang diagnostic pop
+
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 
