@@ -308,6 +308,8 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
       // it + 1, tile it + 2 lands in the buffer tile it - 1 has left.  The loop
       // is unrolled three times so that every buffer address is an immediate.
       const char* lds_base = &lds[0][0];
+      const uint32_t wave_dst = tile_wave_dst(lds_base, wave);
+      const char* kh_u = wave_uniform(kh);  // (the wave's head picks it: uniform, but not to the compiler)
       int fo[C::kSteps];
 #pragma unroll
       for (int s = 0; s < C::kSteps; ++s) fo[s] = off0 ^ (s << 4);
@@ -330,7 +332,8 @@ __global__ __launch_bounds__(kThreads, 2) void lse_kernel(ScoreParams p) {
       auto body = [&](auto P, int it) {
         constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
         constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
-        tile_load_async_full<C>(kh, (f_begin + min(it + 2, n_full - 1)) * C::kTile, lds[ld], rel, wave, krb);
+        tile_load_async_full_unseen<C>(kh_u + (size_t)((f_begin + min(it + 2, n_full - 1)) * C::kTile) * krb,
+                                       wave_dst + ld * kT, rel);
         const bool live = it < n_full;
         float sum[2], mref[2];
         // block (it, sub 1) goes through the MFMAs while block (it, sub 0) is summed
@@ -519,7 +522,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       const long long head_step = STRIDED ? p.q_sh : (long long)S * C::kRowBytes;  // bytes between heads
       const long long tile_step = (long long)C::kTile * qrb;                      // bytes between tiles
       const long long head_jump = head_step + (long long)(n_fullt - 1) * tile_step;
-      const char* q_next = q_head(head0) + (size_t)f_last * C::kTile * qrb;
+      const char* q_next = wave_uniform(q_head(head0) + (size_t)f_last * C::kTile * qrb);
       // A lane needs the lse of two query rows of a tile (lane % 32 of either 32-row block): it
       // loads them itself, two tiles ahead, and keeps them in registers.
       const float* lse_next = lse_in + ((size_t)b * p.Hq + head0) * S + (size_t)f_last * C::kTile + (lane & 31);
@@ -531,9 +534,10 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
         bool counts[2];
       };
       // loads pair `pair_no` (tile -> buf) and starts the loads of this lane's two lse values of it
-      auto issue = [&](char* buf) -> Pending {
+      const uint32_t wave_dst = tile_wave_dst(&lds[0][0], wave);
+      auto issue = [&](int buf_no) -> Pending {
         Pending x;
-        tile_load_async_full_unseen<C>(q_next, 0, buf, rel, wave, qrb);
+        tile_load_async_full_unseen<C>(q_next, wave_dst + buf_no * C::kTileBytes, rel);
         asm volatile("global_load_dword %0, %2, off\n\tglobal_load_dword %1, %2, off offset:128"
                      : "=&v"(x.raw[0]), "=&v"(x.raw[1])
                      : "v"(lse_next)
@@ -560,8 +564,8 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       };
       float lse_cur[2], lse_nxt[2];
       {
-        Pending x0 = issue(lds[0]);
-        Pending x1 = issue(lds[1]);
+        Pending x0 = issue(0);
+        Pending x1 = issue(1);
         settle(x0, lse_cur);
         settle(x1, lse_nxt);
       }
@@ -582,7 +586,7 @@ __global__ __launch_bounds__(kThreads, 2) void colsum_kernel(ScoreParams p, cons
       auto body = [&](auto P, int it) {
         constexpr int cur = decltype(P)::value, nxt = (cur + 1) % 3, ld = (cur + 2) % 3;
         constexpr int kT = C::kTileBytes, kU = C::kSubBytes;
-        Pending ahead = issue(lds[ld]);  // pair it + 2
+        Pending ahead = issue(ld);  // pair it + 2
         colsum_half<C, cur * kT + kU, nxt * kT, F16>(acc1, acc0, col, fr, kf[0], kf[1], lds_base, fo, c, lse_cur[0]);
         colsum_half<C, nxt * kT, nxt * kT + kU, F16>(acc0, acc1, col, fr, kf[0], kf[1], lds_base, fo, c, lse_cur[1]);
         lse_cur[0] = lse_nxt[0];

@@ -151,25 +151,37 @@ __device__ __forceinline__ void tile_load_async_full(const char* head_base, int 
 // a copy it knows of: right after the copies were issued, for the whole memory latency.  Copies
 // it does not know of cost no such wait; the caller's own wait and barrier at the end of the step
 // (which the other form needs as well) are then the only synchronisation, so the buffer must not
-// be read before them.  M0 holds the wave's LDS destination (one wait state before its use).
+// be read before them.  The statement is ordered against barriers and that wait (all of them have
+// side effects) but not against LDS reads, which touch other buffers and are free to move across
+// it.  M0 holds the wave's LDS destination (one wait state before its use).
 // (M0 is a register the compiler reserves and sets itself before each of its own uses; naming it
 // as clobbered keeps it from merging such a set across this statement, and draws a warning)
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
+// `tile` is the tile's first byte and `wave_dst` the LDS byte address of buf + wave * 1024, both
+// uniform over the wave (scalar registers): the copy's address is scalar base + the lane's fixed
+// 32-bit offset, so a step costs no vector instruction for addresses.
 template <class C>
-__device__ __forceinline__ void tile_load_async_full_unseen(const char* head_base, int row0, char* buf,
-                                                            const uint32_t (&rel)[C::kLoadsPerWave], int wave,
-                                                            uint32_t row_bytes = C::kRowBytes) {
-  const char* tile = head_base + (size_t)row0 * row_bytes;
+__device__ __forceinline__ void tile_load_async_full_unseen(const char* tile, uint32_t wave_dst,
+                                                            const uint32_t (&rel)[C::kLoadsPerWave]) {
 #pragma unroll
-  for (int j = 0; j < C::kLoadsPerWave; ++j) {
-    const uint32_t dst = __builtin_amdgcn_readfirstlane(
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)(buf + (wave + kWaves * j) * 1024));
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+  for (int j = 0; j < C::kLoadsPerWave; ++j)
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(dst), "v"(tile + rel[j])
-                 : "memory", "m0");
-  }
+                 : "s"(wave_dst), "v"(rel[j]), "s"(tile), "n"(kWaves * j * 1024)
+                 : "m0", "scc");
+}
+// A pointer that is the same in every lane of the wave, moved to scalar registers.
+__device__ __forceinline__ const char* wave_uniform(const char* ptr) {
+  const uint64_t v = (uint64_t)(uintptr_t)ptr;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const char*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+// LDS byte address of a wave's first 1 KiB slot in the buffer at `buf` (uniform over the wave).
+__device__ __forceinline__ uint32_t tile_wave_dst(const char* buf, int wave) {
+  return __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)(buf + wave * 1024));
 }
 #pragma clang diagnostic pop
 
