@@ -3,7 +3,7 @@
 // v_mfma_f32_32x32x16_bf16 (one 64 x 32 block of Q K^T at D = 128) and, for each of the 32
 // accumulator values of the PREVIOUS block, the three vector-ALU instructions every score
 // element costs (multiply-add by the softmax scale, exp2, add into a running sum), in the
-// same interleave as the kernels' hand-written pipeline (a pair of MFMAs, then a slice of the
+// same interleave as the kernels' hand-written pipeline (every MFMA followed by its share of the
 // vector work).  No global or LDS traffic inside the loop, two waves per SIMD like the score
 // kernels, operands taken from the benchmark's own Q values.  Matrix-core and vector
 // instructions of a SIMD share one issue port, so this mix runs below the MFMA-only ceiling
@@ -48,8 +48,10 @@ __device__ __forceinline__ void mix_half(f32x16 (&acc_new)[2], const f32x16 (&ac
   }
 #pragma unroll
   for (int s = 0; s < kSteps; ++s) {
-    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
-    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer / 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer / 2, 0);
   }
 }
 

@@ -183,13 +183,16 @@ __device__ __forceinline__ void colsum_half(f32x16 (&acc_new)[2], const f32x16 (
       col[t][r] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc_old[t][r], c, -lse_old));
     }
   }
-  // issue order for the machine scheduler: per MFMA pair, its refill read and a
-  // slice of the exp work (fma, exp, add per element)
+  // issue order for the machine scheduler: every MFMA is followed by half a slice of the exp
+  // work (fma, exp, add per element), the second of a pair also by the pair's refill read
+  // (an MFMA right behind another holds the wave's vector instructions back until it has issued)
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
-    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer / 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
     __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer + 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer / 2 + 1, 0);
   }
 }
 
@@ -218,9 +221,11 @@ __device__ __forceinline__ void lse_half(f32x16 (&acc_new)[2], const f32x16 (&ac
   }
 #pragma unroll
   for (int s = 0; s < C::kSteps; ++s) {
-    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer / 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedMfma, 1, 0);
     __builtin_amdgcn_sched_group_barrier(kSchedDsRead, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer + 2, 0);
+    __builtin_amdgcn_sched_group_barrier(kSchedValu, 3 * kPer / 2 + 1, 0);
   }
 }
 
