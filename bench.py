@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E peak, vendor figure
 # WRITE_SIZE x1.0 by what the same counters read for a plain 256 MiB copy).  Counters cannot be read
 # from inside the timed run, so the figure is carried here; None for workloads not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg3_llama3_8b_gqa_s16384", "colsum_kernel"): (186494.6 * 2.0 + 4323.6) * 1024.0,
-    ("cfg3_llama3_8b_gqa_s16384", "lse_kernel"): (114972.7 * 2.0 + 2048.0) * 1024.0,
+    ("cfg3_llama3_8b_gqa_s16384", "colsum_kernel"): (197737.1 * 2.0 + 4320.0) * 1024.0,
+    ("cfg3_llama3_8b_gqa_s16384", "lse_kernel"): (118440.3 * 2.0 + 2048.0) * 1024.0,
 }
 
 

@@ -88,3 +88,4 @@ def resource_usage(source: str) -> dict:
 
 if __name__ == "__main__":
     print(build_library(verbose=True, extra_flags=sys.argv[1:]))
+    print(build_bench_library())
