@@ -506,9 +506,11 @@ def main():
         graph_ms = run.graph_ms_per_step(args.steps)
     if args.graph:
         ms_per_step, launch = graph_ms, "hip_graph"
+    overlap_ms = overlap_ok = None
+    if args.overlap or not args.quick:
+        overlap_ms, overlap_ok = run.overlap_ms_per_step(args.steps, args.warmup)
     if args.overlap:
-        ms_per_step, overlap_ok = run.overlap_ms_per_step(args.steps, args.warmup)
-        launch = "eager, two streams"
+        ms_per_step, launch = overlap_ms, "eager, two streams"
     stages, flop_pass, peak = run.figures(ms_per_step, stage_ms)
     t_lse, t_col = stages["lse_ms"], stages["colsum_ms"]
     # (the events bracket the library call: pass B's time includes its 4 us partial-sum reduction)
@@ -537,8 +539,10 @@ def main():
         out["graph_ms_per_step"] = graph_ms          # the same steps replayed from a HIP graph (informational)
     if args.graph or args.overlap:
         out["eager_ms_per_step"] = eager_ms_per_step   # one stream, one launch after the other
-    if args.overlap:
-        out["overlap_check"] = overlap_ok
+    if overlap_ms is not None:
+        # layer L's selection and gather on a second stream beside layer L + 1's score kernels (informational)
+        out["overlap_ms_per_step"] = overlap_ms
+        out["overlap_check"] = overlap_ok            # the overlapped run's last index list equals the one-stream one
     if w.dtype == "bf16" and not args.no_mfma_ceiling:
         # measured counterparts of the datasheet peak, taken after the timed region
         ceil = mfma_ceiling_tflops(torch, dev, run.layers[0]["q"])
