@@ -174,8 +174,12 @@ __device__ __forceinline__ void tile_load_async_full_unseen(const char* tile, ui
 // A pointer that is the same in every lane of the wave, moved to scalar registers.
 __device__ __forceinline__ const char* wave_uniform(const char* ptr) {
   const uint64_t v = (uint64_t)(uintptr_t)ptr;
-  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
-  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  // A memory instruction must not read a scalar register within five wait states of a vector
+  // instruction writing it.  The compiler keeps that distance for the instructions it emits
+  // itself, but the written-out copies below are opaque to it: keep it here, once.
+  asm volatile("s_nop 4" : "+s"(lo), "+s"(hi));
   return (const char*)(uintptr_t)(((uint64_t)hi << 32) | lo);
 }
 // LDS byte address of a wave's first 1 KiB slot in the buffer at `buf` (uniform over the wave).
