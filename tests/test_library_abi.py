@@ -320,3 +320,51 @@ def test_mix_calibration_kernel_keeps_its_matrix_instructions(tmp_path):
     body = body[:body.index("s_endpgm")]
     assert body.count("v_mfma_f32_32x32x16_bf16") == 32
     assert body.count("v_exp_f32") == 64 and body.count("v_fma_f32") >= 64
+
+
+def test_score_loops_wait_only_where_they_must(tmp_path):
+    """The pipelined loops of the two score kernels (16-bit operands) hold 96 MFMAs a trip (three
+    unrolled steps).  Their tile copies are kept out of the compiler's sight so that it does not
+    wait for them at the next LDS read: inside a trip there is one `vmcnt(0)` per step (the loop's
+    own, before its barrier) and no LDS wait that drains every read in flight except the one that
+    goes with each barrier.  A compiler or source change that brings the conservative waits back
+    costs several per cent and no numerical test would notice."""
+    import re
+    import subprocess
+    from paper_2503_00022_amd import build
+    src = os.path.join(build.CSRC, "scores.hip")
+    out = tmp_path / "scores.s"
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    subprocess.run([os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), *flags, "--cuda-device-only", "-I",
+                    os.path.join(ROOT, "include"), "-I", build.CSRC, "-S", "-o", str(out), src],
+                   check=True, capture_output=True)
+    text = out.read_text()
+    checked = 0
+    # every kernel's text, cut into basic blocks at the compiler's labels
+    for kern in re.split(r"\n(?=_Z\S+:)", text):
+        name = kern.split(":", 1)[0]
+        if not ("lse_kernel" in name or "colsum_kernel" in name) or "ILb1E" not in name:
+            continue                                   # 16-bit instantiations only (the fp32 path is not pipelined)
+        body = kern[:kern.index("s_endpgm")] if "s_endpgm" in kern else kern
+        blocks = re.split(r"\n(?=\.LBB\d+_\d+:)", body)
+        D = 128 if "ELi128E" in name else 64
+        per_half = D // 8                              # MFMAs of one 64 x 32 block
+        n_mfma = lambda b: len(re.findall(r"v_mfma_f32_32x32x16", b))
+        if "colsum_kernel" in name:
+            loops = [b for b in blocks if n_mfma(b) == 6 * per_half]                     # one straight block a trip
+            assert len(loops) == 1, (name, [n_mfma(b) for b in blocks])
+            loop = loops[0]
+        else:
+            # pass A's trip is six blocks of one half step each (a rarely taken re-basing branch ends each)
+            idx = [i for i, b in enumerate(blocks) if n_mfma(b) == per_half and "s_cbranch_vccnz" in b]
+            assert len(idx) >= 6, (name, len(idx))
+            loop = "\n".join(blocks[idx[0]:idx[5] + 2])
+        assert loop.count("s_waitcnt vmcnt(0)") == 3, (name, loop.count("s_waitcnt vmcnt(0)"))
+        assert loop.count("s_barrier") == 3, name
+        lgkm = [int(n) for n in re.findall(r"s_waitcnt lgkmcnt\((\d+)\)", loop)]
+        assert lgkm.count(0) <= 3, (name, lgkm)        # only the drain in front of each barrier
+        if D == 128:
+            assert sum(1 for n in lgkm if n >= 2) >= 36, (name, lgkm)   # fragment waits leave reads in flight
+        assert "global_load_lds_dwordx4" in loop
+        checked += 1
+    assert checked == 16, checked   # {lse, colsum} x {bf16, fp16} x {D = 64, 128} x {packed, strided}
