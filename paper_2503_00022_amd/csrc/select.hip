@@ -1215,7 +1215,7 @@ __global__ __launch_bounds__(kSelThreads) void row_select_kernel(FastParams p) {
       if (ties) {
         const bool eq = t < S && key[u] == T;
         const uint64_t m = __ballot(eq);
-        if (eq) sel = chunk_eq[wave + kSelWaves * u] + __popcll(m & lanemask_lt()) < (int)remaining;
+        if (eq) sel = (int)chunk_eq[wave + kSelWaves * u] + __popcll(m & lanemask_lt()) < (int)remaining;
       }
       const uint64_t word = __ballot(sel);
       if (lane == u) word_of_lane = word;
